@@ -1,0 +1,156 @@
+/*
+ * bcnn.h - C ABI of the binary-convolution hot path for AMD MI355X (gfx950).
+ *
+ * The operation is the CNN-style 2D convolution of the BCNN paper (Section 1:
+ * a 3D input tensor and a 4D weight tensor give a 3D output tensor, and the
+ * operator lowers to a matrix-matrix product) with both operands binary
+ * (Section 4.2.1: inputs and weights are +1 or -1).  A leading batch index is
+ * added; images are independent.
+ *
+ * Conventions shared by every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or keeps them and uses no hidden workspace.
+ *   - Calls are asynchronous: kernels are enqueued on `hip_stream` (a
+ *     hipStream_t passed as void*, NULL = the default stream) and the call
+ *     returns without synchronising.  Outputs are valid once the stream has
+ *     reached that point.
+ *   - Return value: BCNN_OK (0) or a negative bcnn_status.  Arguments are
+ *     checked on the host before anything is launched; a call that returns an
+ *     error has launched nothing.  Pointers are checked for NULL and for
+ *     4-byte alignment only; whether they really are device memory of the
+ *     required size is the caller's responsibility.
+ *   - Bit convention: bit 1 <=> +1, bit 0 <=> -1.  32 consecutive channels
+ *     form one little-endian uint32, channel 32*j+i is bit i of word j, and
+ *     the unused high bits of the last word of a channel vector are 0 in
+ *     every packed tensor (inputs must obey this, outputs do).
+ *   - Packed activations: [n][h][w][ceil(c/32)] uint32.
+ *     Packed weights:     [c_out][kh][kw][ceil(c_in/32)] uint32.
+ *   - Padding: a position outside the image counts as -1 in every channel
+ *     (all-zero packed words).  The paper pads real values before bias and
+ *     sign (Section 4.2.1, last paragraph), so a padded operand is a fixed
+ *     +-1, never 0; -1 is the convention fixed here.
+ *   - Output extent: floor((in + 2*pad - k) / stride) + 1.
+ *   - Supported: kh = kw in {1, 3}; stride in {1, 2}; pad in {0, 1} with
+ *     pad <= (kh-1)/2; every extent >= 1; n*h_out*w_out*c_out and
+ *     n*h*w*ceil(c_in/32) below 2^31.  Anything else returns
+ *     BCNN_ERR_UNSUPPORTED.
+ */
+#ifndef BCNN_H
+#define BCNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BCNN_OK = 0,
+    BCNN_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive extent, aliasing in/out */
+    BCNN_ERR_UNSUPPORTED = -2, /* filter size, stride, padding or size outside the list above */
+    BCNN_ERR_ALIGNMENT = -3,   /* a pointer is not 4-byte aligned */
+    BCNN_ERR_DEVICE = -4       /* the HIP runtime refused the launch */
+} bcnn_status;
+
+typedef enum { BCNN_F32 = 0, BCNN_F16 = 1, BCNN_I8 = 2 } bcnn_dtype;
+
+/* Which arithmetic the convolution runs on.  All variants give identical
+ * results; AUTO picks the fastest one measured for the shape. */
+typedef enum {
+    BCNN_VARIANT_AUTO = 0,
+    BCNN_VARIANT_VALU = 1,     /* xor + popcount on the vector ALUs */
+    BCNN_VARIANT_MFMA_I8 = 2,  /* +-1 expanded to int8, matrix cores */
+    BCNN_VARIANT_MFMA_FP4 = 3  /* +-1 expanded to 4-bit floats, matrix cores */
+} bcnn_variant;
+
+typedef struct {
+    int32_t n, c_in, h, w; /* input  [n][c_in][h][w] (logical) */
+    int32_t c_out, kh, kw; /* weights [c_out][c_in][kh][kw] (logical) */
+    int32_t stride, pad;
+} bcnn_conv_desc;
+
+/*
+ * Sign-binarise and pack along the channel axis (Section 4.2.1: sign turns
+ * activations, and implicitly weights, into +-1; Section 2.4: storage and
+ * data movement scale with the number of bits).
+ *   src : device, contiguous [outer][channels][inner] of `dtype`.
+ *         NCHW activations: outer = n, inner = h*w.  OIHW weights: outer =
+ *         c_out, inner = kh*kw.  Channel-last data: inner = 1.
+ *   dst : device, [outer][inner][ceil(channels/32)] uint32.
+ *   bit = (value >= 0); so +0.0 and -0.0 give 1, NaN gives 0.
+ * Errors: INVALID_ARG for NULL or non-positive sizes, UNSUPPORTED for an
+ * unknown dtype or more than 2^31-1 output words, ALIGNMENT if dst is not
+ * 4-byte aligned or src not aligned to its element size.
+ */
+int bcnn_pack(const void *src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+              uint32_t *dst, void *hip_stream);
+
+/*
+ * Binary convolution, integer sums (Section 1 operator, Section 4.2.1
+ * operands):
+ *   y[n][oh][ow][o] = sum_{u,v,c} X~[n][oh*s-p+u][ow*s-p+v][c] * W[o][u][v][c]
+ * with X~ = -1 outside the image.  Evaluated as K - 2*popcount(x xor w) over
+ * packed words, K = c_in*kh*kw.
+ *   x_packed : device, packed activations  [n][h][w][ceil(c_in/32)]
+ *   w_packed : device, packed weights      [c_out][kh][kw][ceil(c_in/32)]
+ *   y        : device, int32 [n][h_out][w_out][c_out] (the row-major M x c_out
+ *              matrix of the matrix-product view, M = n*h_out*w_out)
+ */
+int bcnn_conv2d_binary(const bcnn_conv_desc *desc, const uint32_t *x_packed,
+                       const uint32_t *w_packed, int32_t *y, void *hip_stream);
+
+/*
+ * Binary convolution with the fused epilogue: the per-channel scale and bias
+ * of batch norm followed by the next module's bias and sign (Section 4.2.1,
+ * first paragraph; without the real identity path) reduce to one integer
+ * threshold per output channel.  The sums never leave the chip:
+ *   bit[n][oh][ow][o] = (y[n][oh][ow][o] >= thr[o])
+ *   thr      : device, int32 [c_out]
+ *   y_packed : device, packed activations [n][h_out][w_out][ceil(c_out/32)],
+ *              directly usable as the next layer's x_packed.  Must not alias
+ *              x_packed.
+ */
+int bcnn_conv2d_binary_sign_pack(const bcnn_conv_desc *desc, const uint32_t *x_packed,
+                                 const uint32_t *w_packed, const int32_t *thr,
+                                 uint32_t *y_packed, void *hip_stream);
+
+/*
+ * The two calls above with the arithmetic variant chosen by the caller, for
+ * measuring one variant against another.  thr == NULL: `out` is int32 sums;
+ * thr != NULL: `out` is packed bits.  A variant that does not cover the shape
+ * returns BCNN_ERR_UNSUPPORTED.
+ */
+int bcnn_conv2d_binary_variant(const bcnn_conv_desc *desc, const uint32_t *x_packed,
+                               const uint32_t *w_packed, const int32_t *thr, void *out,
+                               int variant, void *hip_stream);
+
+/*
+ * The epilogue alone (same decision as the fused call), for sums that are
+ * already in memory:  y int32 [rows][c_out], thr int32 [c_out] ->
+ * y_packed [rows][ceil(c_out/32)].
+ */
+int bcnn_threshold_sign_pack(const int32_t *y, const int32_t *thr, int64_t rows, int64_t c_out,
+                             uint32_t *y_packed, void *hip_stream);
+
+/* floor((in + 2*pad - k)/stride) + 1, or 0 if the window does not fit. Host only. */
+int bcnn_out_dim(int32_t in, int32_t k, int32_t stride, int32_t pad);
+
+/* Static, NUL-terminated description of a bcnn_status value. Host only. */
+const char *bcnn_status_string(int status);
+
+/*
+ * Measurement helpers (not part of the method).
+ * bcnn_diag_copy_u32: dst[i] = src[i] for `words` 32-bit words; the known-size
+ *   kernel that memory-traffic counters are calibrated against.
+ * bcnn_diag_valu_peak: every lane runs `iters` rounds of 64 independent
+ *   xor + popcount-accumulate pairs on registers and writes one word to
+ *   sink[global thread id]; sink holds blocks*256 words.  Times the vector
+ *   ALUs' xor/popcount issue rate with no memory traffic.
+ */
+int bcnn_diag_copy_u32(const uint32_t *src, uint32_t *dst, int64_t words, void *hip_stream);
+int bcnn_diag_valu_peak(uint32_t *sink, int32_t blocks, int32_t iters, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCNN_H */

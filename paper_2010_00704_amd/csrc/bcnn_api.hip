@@ -1,0 +1,191 @@
+// The C ABI of libbcnn (declared in include/bcnn.h): argument checks on the
+// host, then one kernel launch on the caller's stream.  No allocation, no
+// synchronisation, no state.
+#include "bcnn.h"
+#include "bcnn_common.h"
+
+#include <limits.h>
+
+namespace bcnn {
+namespace {
+
+// Issue-rate probe: 64 independent accumulators per lane, each fed by one
+// v_xor_b32 (scalar operand x vector operand, as in the convolution) and one
+// v_bcnt_u32_b32 per round; operands live in registers only.  8 vector words
+// times 8 scalar words give the 64 distinct pairs; the scalar words change
+// every round so no xor can be hoisted out of the loop.
+__global__ __launch_bounds__(256) void diag_valu_peak_kernel(uint32_t* __restrict__ sink, int iters)
+{
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc[64];
+#pragma unroll
+    for (int a = 0; a < 64; ++a) acc[a] = 0;
+    uint32_t xv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xv[j] = (gid + j) * 2654435761u + 12345u;
+    uint32_t sv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sv[j] = __builtin_amdgcn_readfirstlane(0x9E3779B9u * (j + 1));
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sv[j] = sv[j] * 5u + 1u;
+#pragma unroll
+        for (int a = 0; a < 64; ++a)
+            acc[a] += __builtin_popcount(xv[a & 7] ^ sv[a >> 3]);
+    }
+    uint32_t r = 0;
+#pragma unroll
+    for (int a = 0; a < 64; ++a) r ^= acc[a];
+    sink[gid] = r;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int out_dim(int in, int k, int stride, int pad)
+{
+    if (stride < 1 || k < 1 || pad < 0) return 0;
+    const int span = in + 2 * pad - k;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+// Fills `s` from the descriptor; returns BCNN_OK or the error to hand back.
+int make_shape(const bcnn_conv_desc* d, ConvShape* s)
+{
+    if (!d) return BCNN_ERR_INVALID_ARG;
+    if (d->n < 1 || d->c_in < 1 || d->h < 1 || d->w < 1 || d->c_out < 1) return BCNN_ERR_INVALID_ARG;
+    if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0) return BCNN_ERR_INVALID_ARG;
+    if (d->kh != d->kw || (d->kh != 1 && d->kh != 3)) return BCNN_ERR_UNSUPPORTED;
+    if (d->stride > 2) return BCNN_ERR_UNSUPPORTED;
+    if (d->pad > (d->kh - 1) / 2) return BCNN_ERR_UNSUPPORTED;
+    const int ho = out_dim(d->h, d->kh, d->stride, d->pad);
+    const int wo = out_dim(d->w, d->kw, d->stride, d->pad);
+    if (ho < 1 || wo < 1) return BCNN_ERR_INVALID_ARG;
+    const int64_t cw = ((int64_t)d->c_in + 31) / 32;
+    const int64_t m = (int64_t)d->n * ho * wo;
+    const int64_t k = (int64_t)d->c_in * d->kh * d->kw;
+    if (m * d->c_out > INT_MAX || (int64_t)d->n * d->h * d->w * cw > INT_MAX || k > INT_MAX / 4 ||
+        (int64_t)d->c_out * d->kh * d->kw * cw > INT_MAX)
+        return BCNN_ERR_UNSUPPORTED;
+    s->n = d->n; s->h = d->h; s->w = d->w; s->cw = (int32_t)cw;
+    s->c_out = d->c_out; s->cwo = (d->c_out + 31) / 32;
+    s->ks = d->kh; s->stride = d->stride; s->pad = d->pad;
+    s->ho = ho; s->wo = wo; s->m = (int32_t)m; s->k = (int32_t)k;
+    return BCNN_OK;
+}
+
+int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w, const int32_t* thr,
+               bool fused, void* out, int variant, void* stream)
+{
+    ConvShape s;
+    const int rc = make_shape(desc, &s);
+    if (rc != BCNN_OK) return rc;
+    if (!x || !w || !out || (fused && !thr)) return BCNN_ERR_INVALID_ARG;
+    if (static_cast<const void*>(x) == out) return BCNN_ERR_INVALID_ARG;
+    if (!aligned(x, 4) || !aligned(w, 4) || !aligned(out, 4) || (fused && !aligned(thr, 4)))
+        return BCNN_ERR_ALIGNMENT;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    switch (variant) {
+        case BCNN_VARIANT_AUTO:
+        case BCNN_VARIANT_VALU:
+            e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, st);
+            break;
+        case BCNN_VARIANT_MFMA_I8:
+        case BCNN_VARIANT_MFMA_FP4:
+            return BCNN_ERR_UNSUPPORTED;
+        default:
+            return BCNN_ERR_INVALID_ARG;
+    }
+    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+}  // namespace
+}  // namespace bcnn
+
+extern "C" {
+
+int bcnn_out_dim(int32_t in, int32_t k, int32_t stride, int32_t pad)
+{
+    return bcnn::out_dim(in, k, stride, pad);
+}
+
+const char* bcnn_status_string(int status)
+{
+    switch (status) {
+        case BCNN_OK: return "ok";
+        case BCNN_ERR_INVALID_ARG: return "invalid argument (null pointer, non-positive extent or aliased buffers)";
+        case BCNN_ERR_UNSUPPORTED: return "unsupported filter size, stride, padding, dtype or tensor size";
+        case BCNN_ERR_ALIGNMENT: return "pointer not sufficiently aligned";
+        case BCNN_ERR_DEVICE: return "HIP runtime error at kernel launch";
+        default: return "unknown status";
+    }
+}
+
+int bcnn_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+              uint32_t* dst, void* hip_stream)
+{
+    if (!src || !dst || outer < 1 || channels < 1 || inner < 1) return BCNN_ERR_INVALID_ARG;
+    if (dtype != BCNN_F32 && dtype != BCNN_F16 && dtype != BCNN_I8) return BCNN_ERR_UNSUPPORTED;
+    const int64_t cw = (channels + 31) / 32;
+    if (outer > INT_MAX || inner > INT_MAX || outer * inner > INT_MAX / cw) return BCNN_ERR_UNSUPPORTED;
+    if ((double)outer * (double)channels * (double)inner > 9.0e18) return BCNN_ERR_UNSUPPORTED;
+    const uintptr_t esz = dtype == BCNN_F32 ? 4 : dtype == BCNN_F16 ? 2 : 1;
+    if (!bcnn::aligned(src, esz) || !bcnn::aligned(dst, 4)) return BCNN_ERR_ALIGNMENT;
+    if (src == static_cast<const void*>(dst)) return BCNN_ERR_INVALID_ARG;
+    const hipError_t e = bcnn::launch_pack(src, dtype, outer, channels, inner, dst,
+                                           static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+int bcnn_conv2d_binary(const bcnn_conv_desc* desc, const uint32_t* x_packed,
+                       const uint32_t* w_packed, int32_t* y, void* hip_stream)
+{
+    return bcnn::conv_entry(desc, x_packed, w_packed, nullptr, false, y, BCNN_VARIANT_AUTO, hip_stream);
+}
+
+int bcnn_conv2d_binary_sign_pack(const bcnn_conv_desc* desc, const uint32_t* x_packed,
+                                 const uint32_t* w_packed, const int32_t* thr,
+                                 uint32_t* y_packed, void* hip_stream)
+{
+    return bcnn::conv_entry(desc, x_packed, w_packed, thr, true, y_packed, BCNN_VARIANT_AUTO, hip_stream);
+}
+
+int bcnn_conv2d_binary_variant(const bcnn_conv_desc* desc, const uint32_t* x_packed,
+                               const uint32_t* w_packed, const int32_t* thr, void* out,
+                               int variant, void* hip_stream)
+{
+    return bcnn::conv_entry(desc, x_packed, w_packed, thr, thr != nullptr, out, variant, hip_stream);
+}
+
+int bcnn_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows, int64_t c_out,
+                             uint32_t* y_packed, void* hip_stream)
+{
+    if (!y || !thr || !y_packed || rows < 1 || c_out < 1) return BCNN_ERR_INVALID_ARG;
+    if (c_out > INT_MAX || rows > INT_MAX || rows * ((c_out + 31) / 32) > INT_MAX)
+        return BCNN_ERR_UNSUPPORTED;
+    if (!bcnn::aligned(y, 4) || !bcnn::aligned(thr, 4) || !bcnn::aligned(y_packed, 4))
+        return BCNN_ERR_ALIGNMENT;
+    if (static_cast<const void*>(y) == static_cast<const void*>(y_packed)) return BCNN_ERR_INVALID_ARG;
+    const hipError_t e = bcnn::launch_threshold_sign_pack(y, thr, rows, c_out, y_packed,
+                                                          static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+int bcnn_diag_copy_u32(const uint32_t* src, uint32_t* dst, int64_t words, void* hip_stream)
+{
+    if (!src || !dst || words < 1) return BCNN_ERR_INVALID_ARG;
+    if (!bcnn::aligned(src, 4) || !bcnn::aligned(dst, 4)) return BCNN_ERR_ALIGNMENT;
+    const hipError_t e = bcnn::launch_diag_copy(src, dst, words, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+int bcnn_diag_valu_peak(uint32_t* sink, int32_t blocks, int32_t iters, void* hip_stream)
+{
+    if (!sink || blocks < 1 || iters < 1) return BCNN_ERR_INVALID_ARG;
+    if (!bcnn::aligned(sink, 4)) return BCNN_ERR_ALIGNMENT;
+    hipLaunchKernelGGL(bcnn::diag_valu_peak_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), sink, iters);
+    return hipGetLastError() == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+}  // extern "C"

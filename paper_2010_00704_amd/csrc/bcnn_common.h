@@ -1,0 +1,32 @@
+// Internal declarations shared by the HIP translation units of libbcnn.
+// Nothing here is visible through the C ABI (include/bcnn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bcnn {
+
+// Shape of one convolution call as the kernels see it.
+struct ConvShape {
+    int32_t n, h, w;        // input images and their extent
+    int32_t cw;             // packed input words per pixel = ceil(c_in/32)
+    int32_t c_out;
+    int32_t cwo;            // packed output words per pixel = ceil(c_out/32)
+    int32_t ks;             // filter extent, 1 or 3
+    int32_t stride, pad;
+    int32_t ho, wo;         // output extent
+    int32_t m;              // n*ho*wo output pixels (rows of the GEMM view)
+    int32_t k;              // c_in*ks*ks, the K of "dot = K - 2*popcount"
+};
+
+// Launchers, one per kernel family.  Each returns the hipError_t of its launch.
+hipError_t launch_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+                       uint32_t* dst, hipStream_t stream);
+hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows,
+                                      int64_t c_out, uint32_t* y_packed, hipStream_t stream);
+hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_t* w,
+                            const int32_t* thr, void* out, hipStream_t stream);
+hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
+
+}  // namespace bcnn

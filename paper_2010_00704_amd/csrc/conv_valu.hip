@@ -1,0 +1,209 @@
+// Binary convolution on the vector ALUs: implicit GEMM over packed words,
+//   dot = K - 2 * sum_words popcount(x_word xor w_word)
+// (BCNN paper, Section 1: the operator lowers to a matrix product; Section
+// 4.2.1: operands are +-1).  No im2col buffer exists anywhere.
+//
+// Mapping.  A wave owns 64*TM output pixels (one or more per lane) and TN = 32
+// consecutive output channels, i.e. exactly one packed output word per pixel.
+// The weights of a wave are the same for all of its lanes, so they are read
+// with scalar loads into SGPRs and enter v_xor_b32 as the scalar operand:
+// weights cost no vector-memory or LDS bandwidth and no VGPRs.  Each lane
+// loads its own pixels' packed input words (VEC words at a time) straight from
+// global memory; a tap outside the image is the all-zero word (-1 in every
+// channel), so borders need no correction term.  Per VEC input words a lane
+// issues VEC*TM*TN xor+popcount pairs, so vector loads are <1% of the
+// instruction stream and latency is hidden by the other waves of the SIMD.
+#include "bcnn_common.h"
+
+namespace bcnn {
+namespace {
+
+constexpr int TN = 32;
+
+template <int VEC> struct WordVec;
+template <> struct WordVec<1> { using type = uint32_t; };
+template <> struct WordVec<2> { using type = uint2; };
+template <> struct WordVec<4> { using type = uint4; };
+
+template <int VEC>
+__device__ __forceinline__ void load_words(const uint32_t* p, bool ok, uint32_t (&out)[VEC])
+{
+    if constexpr (VEC == 1) {
+        out[0] = ok ? *p : 0u;
+    } else if constexpr (VEC == 2) {
+        uint2 v = ok ? *reinterpret_cast<const uint2*>(p) : make_uint2(0u, 0u);
+        out[0] = v.x; out[1] = v.y;
+    } else {
+        uint4 v = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0u, 0u, 0u, 0u);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    }
+}
+
+template <int TM, int VEC, bool FUSED>
+__global__ __launch_bounds__(256) void conv_valu_kernel(
+    ConvShape s, int32_t n_mtiles, int32_t n_ctiles,
+    const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
+    const int32_t* __restrict__ thr, void* __restrict__ out)
+{
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * 4 + wave;
+    // channel tile fastest: the waves that share one pixel tile run together
+    const int ctile = tile % n_ctiles;
+    const int mtile = tile / n_ctiles;
+    if (mtile >= n_mtiles) return;
+    const int o0 = ctile * TN;
+
+    int pn[TM], ph[TM], pw[TM];
+    bool live[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = mtile * (64 * TM) + i * 64 + lane;
+        live[i] = m < s.m;
+        const int mc = live[i] ? m : s.m - 1;
+        const int hw = s.ho * s.wo;
+        pn[i] = mc / hw;
+        const int r = mc - pn[i] * hw;
+        const int oh = r / s.wo;
+        ph[i] = oh * s.stride - s.pad;
+        pw[i] = (r - oh * s.wo) * s.stride - s.pad;
+    }
+
+    int32_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int o = 0; o < TN; ++o) acc[i][o] = 0;
+
+    const int taps = s.ks * s.ks;
+    const int wrow = taps * s.cw;  // words per output channel
+    // Rows of channels beyond c_out are clamped to the last real channel so
+    // that every scalar load stays inside the weight tensor.
+    const int o_last = s.c_out - 1;
+
+    for (int tap = 0; tap < taps; ++tap) {
+        const int u = tap / s.ks, v = tap - u * s.ks;
+        const uint32_t* xp[TM];
+        bool inb[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int ih = ph[i] + u, iw = pw[i] + v;
+            inb[i] = ih >= 0 && ih < s.h && iw >= 0 && iw < s.w;
+            const int ihc = inb[i] ? ih : 0, iwc = inb[i] ? iw : 0;
+            xp[i] = x + ((size_t)(pn[i] * s.h + ihc) * s.w + iwc) * s.cw;
+        }
+        const uint32_t* wt = w + (size_t)tap * s.cw;
+        for (int j0 = 0; j0 < s.cw; j0 += VEC) {
+            uint32_t xv[TM][VEC];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) load_words<VEC>(xp[i] + j0, inb[i], xv[i]);
+#pragma unroll
+            for (int o = 0; o < TN; ++o) {
+                const int oc = (o0 + o < o_last) ? (o0 + o) : o_last;
+                const uint32_t* wp = wt + (size_t)oc * wrow + j0;
+                uint32_t wv[VEC];
+                if constexpr (VEC == 1) {
+                    wv[0] = wp[0];
+                } else if constexpr (VEC == 2) {
+                    const uint2 t = *reinterpret_cast<const uint2*>(wp);
+                    wv[0] = t.x; wv[1] = t.y;
+                } else {
+                    const uint4 t = *reinterpret_cast<const uint4*>(wp);
+                    wv[0] = t.x; wv[1] = t.y; wv[2] = t.z; wv[3] = t.w;
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < VEC; ++j)
+                        acc[i][o] += __builtin_popcount(xv[i][j] ^ wv[j]);
+            }
+        }
+    }
+
+    // Epilogue.  dot = K - 2*popcount; padding needs no correction because
+    // padded taps were real all-zero words.
+    if constexpr (FUSED) {
+        uint32_t* yp = static_cast<uint32_t*>(out);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int o = 0; o < TN; ++o) {
+                const int oc = (o0 + o < o_last) ? (o0 + o) : o_last;
+                const bool on = (o0 + o <= o_last) && (s.k - 2 * acc[i][o] >= thr[oc]);
+                word |= (uint32_t)on << o;
+            }
+            if (live[i]) {
+                const int m = mtile * (64 * TM) + i * 64 + lane;
+                yp[(size_t)m * s.cwo + ctile] = word;
+            }
+        }
+    } else {
+        int32_t* y = static_cast<int32_t*>(out);
+        const bool vec_ok = (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
+                            (o0 + TN <= s.c_out);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            if (!live[i]) continue;
+            const int m = mtile * (64 * TM) + i * 64 + lane;
+            int32_t* row = y + (size_t)m * s.c_out + o0;
+            if (vec_ok) {
+#pragma unroll
+                for (int o = 0; o < TN; o += 4) {
+                    int4 q;
+                    q.x = s.k - 2 * acc[i][o + 0];
+                    q.y = s.k - 2 * acc[i][o + 1];
+                    q.z = s.k - 2 * acc[i][o + 2];
+                    q.w = s.k - 2 * acc[i][o + 3];
+                    *reinterpret_cast<int4*>(row + o) = q;
+                }
+            } else {
+#pragma unroll
+                for (int o = 0; o < TN; ++o)
+                    if (o0 + o < s.c_out) row[o] = s.k - 2 * acc[i][o];
+            }
+        }
+    }
+}
+
+template <int TM, int VEC>
+hipError_t launch_tm_vec(const ConvShape& s, const uint32_t* x, const uint32_t* w,
+                         const int32_t* thr, void* out, hipStream_t stream)
+{
+    const int n_ctiles = (s.c_out + TN - 1) / TN;
+    const int n_mtiles = (s.m + 64 * TM - 1) / (64 * TM);
+    const int64_t waves = (int64_t)n_ctiles * n_mtiles;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    if (thr)
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, true>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out);
+    else
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, false>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out);
+    return hipGetLastError();
+}
+
+template <int TM>
+hipError_t launch_tm(const ConvShape& s, const uint32_t* x, const uint32_t* w, const int32_t* thr,
+                     void* out, hipStream_t stream)
+{
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w);
+    if (s.cw % 4 == 0 && (bits & 15) == 0) return launch_tm_vec<TM, 4>(s, x, w, thr, out, stream);
+    if (s.cw % 2 == 0 && (bits & 7) == 0) return launch_tm_vec<TM, 2>(s, x, w, thr, out, stream);
+    return launch_tm_vec<TM, 1>(s, x, w, thr, out, stream);
+}
+
+}  // namespace
+
+hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_t* w,
+                            const int32_t* thr, void* out, hipStream_t stream)
+{
+    // Two pixels per lane halve the scalar weight traffic per popcount; one
+    // pixel per lane gives twice as many waves, which small problems need to
+    // cover 1024 SIMDs.
+    const int64_t waves2 = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 127) / 128);
+    if (waves2 >= 2048) return launch_tm<2>(s, x, w, thr, out, stream);
+    return launch_tm<1>(s, x, w, thr, out, stream);
+}
+
+}  // namespace bcnn

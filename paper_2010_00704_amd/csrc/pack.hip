@@ -1,0 +1,217 @@
+// Sign-binarise + channel-pack kernels and the stand-alone threshold epilogue
+// (BCNN paper, Section 4.2.1: sign before every binary convolution; Section
+// 2.4: storage scales with the number of bits).  Both are pure streaming
+// kernels: 4 bytes (or 2, or 1) read and 1 bit written per element, so HBM
+// bandwidth is the only bound and the design goal is wide, coalesced reads
+// with many of them in flight.
+#include "bcnn_common.h"
+
+
+namespace bcnn {
+namespace {
+
+__device__ __forceinline__ bool nonneg(float v) { return v >= 0.0f; }
+__device__ __forceinline__ bool nonneg(_Float16 v) { return (float)v >= 0.0f; }
+__device__ __forceinline__ bool nonneg(int8_t v) { return v >= 0; }
+
+// ---- [outer][C][inner] with inner >= 64: lanes run along `inner` ------------
+// One thread owns one inner position and builds all Cw words of that pixel.
+// For a fixed channel the 256 threads of a block read 256 consecutive
+// elements; the 32 channel reads of a word are independent and all in flight.
+// The block's output is a contiguous run of 256*Cw words, staged through LDS
+// so that the stores are contiguous too.
+constexpr int PACK_THREADS = 256;
+constexpr int PACK_CW_CHUNK = 8;  // words staged per pass: 256*8*4 B = 8 KB LDS
+
+template <typename T>
+__global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
+    const T* __restrict__ src, int64_t channels, int64_t inner, int64_t cw_total,
+    uint32_t* __restrict__ dst)
+{
+    __shared__ uint32_t stage[PACK_THREADS * PACK_CW_CHUNK];
+    const int64_t a = blockIdx.y;
+    const int64_t i0 = (int64_t)blockIdx.x * PACK_THREADS;
+    const int tid = threadIdx.x;
+    const int64_t i = i0 + tid;
+    const bool live = i < inner;
+    const int64_t icl = live ? i : inner - 1;
+    const T* col = src + a * channels * inner + icl;
+    const int rows_here = (int)((inner - i0 < PACK_THREADS) ? (inner - i0) : PACK_THREADS);
+
+    for (int64_t j0 = 0; j0 < cw_total; j0 += PACK_CW_CHUNK) {
+        const int jn = (int)((cw_total - j0 < PACK_CW_CHUNK) ? (cw_total - j0) : PACK_CW_CHUNK);
+        for (int j = 0; j < jn; ++j) {
+            const int64_t c0 = (j0 + j) * 32;
+            uint32_t word = 0;
+            if (c0 + 32 <= channels) {
+                T v[32];
+#pragma unroll
+                for (int b = 0; b < 32; ++b) v[b] = __builtin_nontemporal_load(col + (c0 + b) * inner);
+#pragma unroll
+                for (int b = 0; b < 32; ++b) word |= (uint32_t)nonneg(v[b]) << b;
+            } else {
+                for (int b = 0; c0 + b < channels; ++b)
+                    word |= (uint32_t)nonneg(col[(c0 + b) * inner]) << b;
+            }
+            stage[tid * jn + j] = word;
+        }
+        __syncthreads();
+        // rows_here*jn words, contiguous per pixel only within the chunk:
+        // word t of the stage belongs to pixel t/jn, chunk word t%jn.
+        const int total = rows_here * jn;
+        for (int t = tid; t < total; t += PACK_THREADS) {
+            const int r = t / jn, j = t - r * jn;
+            dst[(a * inner + i0 + r) * cw_total + j0 + j] = stage[t];
+        }
+        __syncthreads();
+    }
+}
+
+// ---- inner == 1 (channel-last rows): lanes run along the channels ----------
+// One wave per (row, 64-channel group); the wave-wide ballot IS the two packed
+// words.  Reads are perfectly coalesced.  ROWS rows are handled per wave so
+// that several loads are in flight.
+template <typename T, int ROWS>
+__global__ __launch_bounds__(256) void pack_rows_kernel(
+    const T* __restrict__ src, int64_t rows, int64_t channels, int64_t cw_total,
+    uint32_t* __restrict__ dst)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t groups = (channels + 63) / 64;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t g = wave % groups;
+    const int64_t r0 = (wave / groups) * ROWS;
+    if (r0 >= rows) return;
+    const int64_t c = g * 64 + lane;
+    bool bit[ROWS];
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+        const int64_t r = r0 + k;
+        bit[k] = (r < rows && c < channels) ? nonneg(src[r * channels + c]) : false;
+    }
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+        const uint64_t mask = __ballot(bit[k]);
+        const int64_t r = r0 + k;
+        if (r < rows && lane < 2 && g * 2 + lane < cw_total)
+            dst[r * cw_total + g * 2 + lane] = (uint32_t)(mask >> (32 * lane));
+    }
+}
+
+// ---- anything else (small inner, e.g. 3x3 filter taps): one thread per word --
+template <typename T>
+__global__ __launch_bounds__(256) void pack_generic_kernel(
+    const T* __restrict__ src, int64_t outer, int64_t channels, int64_t inner, int64_t cw_total,
+    uint32_t* __restrict__ dst)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= outer * inner * cw_total) return;
+    const int64_t j = t % cw_total;
+    const int64_t i = (t / cw_total) % inner;
+    const int64_t a = t / (cw_total * inner);
+    uint32_t word = 0;
+    for (int b = 0; b < 32; ++b) {
+        const int64_t c = j * 32 + b;
+        if (c < channels) word |= (uint32_t)nonneg(src[(a * channels + c) * inner + i]) << b;
+    }
+    dst[t] = word;
+}
+
+template <typename T>
+hipError_t pack_dispatch(const T* src, int64_t outer, int64_t channels, int64_t inner,
+                         uint32_t* dst, hipStream_t stream)
+{
+    const int64_t cw = (channels + 31) / 32;
+    if (inner == 1) {
+        constexpr int ROWS = 8;
+        const int64_t groups = (channels + 63) / 64;
+        const int64_t waves = ((outer + ROWS - 1) / ROWS) * groups;
+        const int64_t blocks = (waves + 3) / 4;
+        hipLaunchKernelGGL((pack_rows_kernel<T, ROWS>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           src, outer, channels, cw, dst);
+    } else if (inner >= 64 && outer <= 65535) {
+        const int64_t bx = (inner + PACK_THREADS - 1) / PACK_THREADS;
+        hipLaunchKernelGGL((pack_columns_kernel<T>), dim3((unsigned)bx, (unsigned)outer),
+                           dim3(PACK_THREADS), 0, stream, src, channels, inner, cw, dst);
+    } else {
+        const int64_t total = outer * inner * cw;
+        const int64_t blocks = (total + 255) / 256;
+        hipLaunchKernelGGL((pack_generic_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           src, outer, channels, inner, cw, dst);
+    }
+    return hipGetLastError();
+}
+
+// ---- stand-alone epilogue: int32 sums [rows][c_out] -> packed bits ---------
+template <int ROWS>
+__global__ __launch_bounds__(256) void threshold_sign_pack_kernel(
+    const int32_t* __restrict__ y, const int32_t* __restrict__ thr, int64_t rows, int64_t c_out,
+    int64_t cwo, uint32_t* __restrict__ yp)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t groups = (c_out + 63) / 64;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t g = wave % groups;
+    const int64_t r0 = (wave / groups) * ROWS;
+    if (r0 >= rows) return;
+    const int64_t c = g * 64 + lane;
+    const bool cl = c < c_out;
+    const int32_t t = cl ? thr[c] : 0;
+    int32_t v[ROWS];
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+        const int64_t r = r0 + k;
+        v[k] = (r < rows && cl) ? __builtin_nontemporal_load(y + r * c_out + c) : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < ROWS; ++k) {
+        const uint64_t mask = __ballot(cl && v[k] >= t);
+        const int64_t r = r0 + k;
+        if (r < rows && lane < 2 && g * 2 + lane < cwo)
+            yp[r * cwo + g * 2 + lane] = (uint32_t)(mask >> (32 * lane));
+    }
+}
+
+__global__ __launch_bounds__(256) void diag_copy_kernel(const uint32_t* __restrict__ src,
+                                                       uint32_t* __restrict__ dst, int64_t words)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride)
+        dst[i] = src[i];
+}
+
+}  // namespace
+
+hipError_t launch_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+                       uint32_t* dst, hipStream_t stream)
+{
+    switch (dtype) {
+        case 0: return pack_dispatch(static_cast<const float*>(src), outer, channels, inner, dst, stream);
+        case 1: return pack_dispatch(static_cast<const _Float16*>(src), outer, channels, inner, dst, stream);
+        case 2: return pack_dispatch(static_cast<const int8_t*>(src), outer, channels, inner, dst, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows,
+                                      int64_t c_out, uint32_t* y_packed, hipStream_t stream)
+{
+    constexpr int ROWS = 8;
+    const int64_t groups = (c_out + 63) / 64;
+    const int64_t waves = ((rows + ROWS - 1) / ROWS) * groups;
+    const int64_t blocks = (waves + 3) / 4;
+    hipLaunchKernelGGL((threshold_sign_pack_kernel<ROWS>), dim3((unsigned)blocks), dim3(256), 0,
+                       stream, y, thr, rows, c_out, (c_out + 31) / 32, y_packed);
+    return hipGetLastError();
+}
+
+hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream)
+{
+    int64_t blocks = (words + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(diag_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, words);
+    return hipGetLastError();
+}
+
+}  // namespace bcnn

@@ -1,0 +1,339 @@
+"""Parity of the HIP library with the CPU oracle on a real MI355X (bit-exact).
+
+Every comparison is element by element on int32 sums or packed words; both
+sides receive the same seeded host tensors.  Outputs are written between
+sentinel guard bands that must stay untouched.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2010_00704_amd import binding as B
+from paper_2010_00704_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 64              # words on each side of every output
+SENTINEL = 0x5A5A5A5A
+VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU]
+VARIANT_IDS = ["auto", "valu"]
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    B.lib()
+    return torch.device("cuda:0")
+
+
+class Guarded:
+    """A device buffer of `words` 32-bit words with sentinel bands around it."""
+
+    def __init__(self, words, dev):
+        self.words = int(words)
+        self.buf = torch.full((self.words + 2 * GUARD,), SENTINEL, dtype=torch.int32, device=dev)
+
+    @property
+    def ptr(self):
+        return self.buf.data_ptr() + 4 * GUARD
+
+    def get(self, dtype=np.uint32):
+        torch.cuda.synchronize()
+        host = self.buf.cpu().numpy()
+        assert np.all(host[:GUARD] == SENTINEL), "write before the output buffer"
+        assert np.all(host[GUARD + self.words:] == SENTINEL), "write past the output buffer"
+        return host[GUARD:GUARD + self.words].view(dtype)
+
+
+def up(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def packed_view(a):
+    """uint32 numpy -> int32 torch-compatible view."""
+    return np.ascontiguousarray(a).view(np.int32)
+
+
+def oracle_pack_nchw(x):
+    n, c = x.shape[:2]
+    return oracle.pack_channels(x.reshape(n, c, -1))  # [n, h*w, cw]
+
+
+def oracle_pack_weights(w):
+    o, c = w.shape[:2]
+    return oracle.pack_channels(w.reshape(o, c, -1))  # [o, kh*kw, cw]
+
+
+def rand_pm1(rng, shape, p=0.5):
+    return np.where(rng.random(shape) < p, 1, -1).astype(np.int8)
+
+
+def gpu_conv(dev, x, w, stride, pad, thr=None, variant=B.BCNN_VARIANT_AUTO, entry="variant"):
+    """x, w logical +-1 tensors (packed on the host by the oracle's packer)."""
+    n, c, h, wd = x.shape
+    o, _, k, _ = w.shape
+    desc = B.conv_desc(n, c, h, wd, o, k, stride, pad)
+    ho, wo = B.out_shape(desc)
+    xp = up(packed_view(oracle_pack_nchw(x)), dev)
+    wp = up(packed_view(oracle_pack_weights(w)), dev)
+    if thr is None:
+        out = Guarded(n * ho * wo * o, dev)
+        if entry == "variant":
+            rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, None, out.ptr, variant)
+        else:
+            rc = B.bcnn_conv2d_binary(desc, xp, wp, out.ptr)
+        B.check(rc, "conv")
+        return out.get(np.int32).reshape(n, ho, wo, o)
+    cwo = (o + 31) // 32
+    t = up(np.asarray(thr, dtype=np.int32), dev)
+    out = Guarded(n * ho * wo * cwo, dev)
+    if entry == "variant":
+        rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, t, out.ptr, variant)
+    else:
+        rc = B.bcnn_conv2d_binary_sign_pack(desc, xp, wp, t, out.ptr)
+    B.check(rc, "conv_sign_pack")
+    return out.get(np.uint32).reshape(n, ho * wo, cwo)
+
+
+def oracle_fused(x, w, stride, pad, thr):
+    y = oracle.conv2d_pm1(x, w, stride, pad)
+    n, ho, wo, o = y.shape
+    s = oracle.threshold_sign(y, thr)                       # [n, ho, wo, o]
+    s_ncp = s.reshape(n, ho * wo, o).transpose(0, 2, 1)     # [n, o, ho*wo]
+    return y, oracle.pack_channels(s_ncp)                   # [n, ho*wo, cwo]
+
+
+# ------------------------------------------------------------------ packing
+PACK_SHAPES = [
+    # outer, channels, inner
+    (2, 64, 196), (3, 33, 300), (1, 256, 784), (2, 1, 70), (5, 31, 64), (2, 65, 129),
+    (7, 64, 9), (64, 64, 9), (3, 40, 1), (100, 256, 1), (9, 65, 1), (1, 32, 1), (2, 300, 5),
+    (13, 96, 63), (1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", PACK_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_pack_matches_oracle(dev, shape, dtype):
+    outer, c, inner = shape
+    rng = np.random.default_rng(outer * 1000 + c * 10 + inner)
+    vals = rng.standard_normal(shape).astype(np.float32)
+    vals[rng.random(shape) < 0.05] = 0.0
+    vals[rng.random(shape) < 0.02] = -0.0
+    if dtype == "i8":
+        src = np.clip(np.round(vals * 40), -128, 127).astype(np.int8)
+        as_f32 = src.astype(np.float32)
+        code = B.BCNN_I8
+    elif dtype == "f16":
+        vals[rng.random(shape) < 0.02] = np.nan
+        vals[rng.random(shape) < 0.01] = -np.inf
+        src = vals.astype(np.float16)
+        as_f32 = src.astype(np.float32)
+        code = B.BCNN_F16
+    else:
+        vals[rng.random(shape) < 0.02] = np.nan
+        vals[rng.random(shape) < 0.01] = np.inf
+        vals[rng.random(shape) < 0.01] = -1e-42  # negative denormal
+        src = vals
+        as_f32 = src
+        code = B.BCNN_F32
+    want = oracle.pack_channels(oracle.sign_f32(as_f32))
+    out = Guarded(want.size, dev)
+    B.check(B.bcnn_pack(up(src, dev), code, outer, c, inner, out.ptr), "pack")
+    np.testing.assert_array_equal(out.get().reshape(want.shape), want)
+
+
+# ------------------------------------------------------- convolution, int32
+CONV_SHAPES = [
+    # n, c, h, w, o, k, stride, pad
+    (1, 64, 14, 14, 64, 3, 1, 1),      # config 1
+    (2, 32, 5, 5, 32, 3, 1, 1), (1, 7, 6, 5, 5, 3, 1, 1), (3, 33, 9, 7, 40, 3, 2, 1),
+    (2, 96, 8, 8, 33, 1, 1, 0), (1, 256, 13, 13, 64, 1, 2, 0), (2, 128, 15, 17, 96, 3, 2, 1),
+    (1, 64, 3, 3, 32, 3, 1, 0), (1, 1, 4, 4, 1, 3, 1, 1), (5, 64, 1, 1, 70, 1, 1, 0),
+    (1, 100, 2, 2, 31, 3, 1, 1), (4, 256, 7, 7, 128, 3, 1, 1), (2, 512, 6, 6, 64, 3, 2, 0),
+    (1, 192, 20, 20, 160, 3, 1, 1), (3, 1024, 4, 4, 96, 1, 1, 0), (2, 160, 11, 11, 48, 3, 1, 0),
+    (2, 64, 30, 31, 64, 3, 2, 1), (1, 320, 9, 9, 257, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv_int32_matches_oracle(dev, shape, variant):
+    n, c, h, wd, o, k, s, p = shape
+    rng = np.random.default_rng(sum(shape) * 31 + k)
+    x = rand_pm1(rng, (n, c, h, wd), 0.4)
+    w = rand_pm1(rng, (o, c, k, k))
+    want = oracle.conv2d_pm1(x, w, s, p)
+    got = gpu_conv(dev, x, w, s, p, variant=variant)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_config1_through_the_named_entry_points(dev):
+    cfg, x, ws, _ = W.make_inputs(1)
+    want = oracle.conv2d_pm1(x, ws[0], cfg.stride, cfg.pad)
+    got = gpu_conv(dev, x, ws[0], cfg.stride, cfg.pad, entry="named")
+    np.testing.assert_array_equal(got, want)
+    thr = W.thresholds(77, cfg.c_out, W.k_total(cfg) // 8)
+    _, want_bits = oracle_fused(x, ws[0], cfg.stride, cfg.pad, thr)
+    got_bits = gpu_conv(dev, x, ws[0], cfg.stride, cfg.pad, thr=thr, entry="named")
+    np.testing.assert_array_equal(got_bits, want_bits)
+
+
+def test_conv_extreme_inputs(dev):
+    """All +1 / all -1 operands reach |y| = K at interior pixels and exercise
+    full and empty popcounts; -1 padding shows at the border."""
+    n, c, h, wd, o, k = 1, 96, 6, 6, 32, 3
+    for xs, wsgn in [(1, 1), (1, -1), (-1, 1), (-1, -1)]:
+        x = np.full((n, c, h, wd), xs, dtype=np.int8)
+        w = np.full((o, c, k, k), wsgn, dtype=np.int8)
+        got = gpu_conv(dev, x, w, 1, 1)
+        np.testing.assert_array_equal(got, oracle.conv2d_pm1(x, w, 1, 1))
+        assert abs(int(got[0, 2, 2, 0])) == c * 9
+
+
+# ------------------------------------------------ fused threshold/sign/repack
+FUSED_SHAPES = [
+    (2, 64, 9, 9, 64, 3, 1, 1), (1, 96, 7, 6, 33, 3, 2, 1), (3, 128, 5, 5, 100, 1, 1, 0),
+    (2, 256, 10, 10, 256, 3, 1, 1), (1, 40, 8, 8, 31, 3, 1, 0), (2, 64, 12, 12, 65, 3, 2, 1),
+    (1, 512, 7, 7, 64, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("tight", [False, True], ids=["k8", "tight"])
+@pytest.mark.parametrize("shape", FUSED_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_fused_epilogue_matches_oracle(dev, shape, tight, variant):
+    n, c, h, wd, o, k, s, p = shape
+    rng = np.random.default_rng(sum(shape) * 17 + int(tight))
+    x = rand_pm1(rng, (n, c, h, wd), 0.3)
+    w = rand_pm1(rng, (o, c, k, k))
+    kk = c * k * k
+    bound = int(2 * math.sqrt(kk)) if tight else kk // 8
+    thr = rng.integers(-bound, bound + 1, size=o).astype(np.int32)
+    y, want = oracle_fused(x, w, s, p, thr)
+    got = gpu_conv(dev, x, w, s, p, thr=thr, variant=variant)
+    np.testing.assert_array_equal(got, want)
+    if tight:
+        # the case is only meaningful if ties and both outcomes occur
+        assert (y == thr[None, None, None, :]).any() or (np.abs(y - thr) <= 2).any()
+        on = oracle.threshold_sign(y, thr) > 0
+        assert on.any() and (~on).any()
+    # fused == unfused on the GPU: int32 sums, then the stand-alone epilogue
+    y_gpu = gpu_conv(dev, x, w, s, p, variant=variant)
+    rows = y_gpu.size // o
+    out = Guarded(rows * ((o + 31) // 32), dev)
+    B.check(B.bcnn_threshold_sign_pack(up(y_gpu, dev), up(thr, dev), rows, o, out.ptr), "thr")
+    np.testing.assert_array_equal(out.get().reshape(want.shape), want)
+
+
+def test_threshold_extremes(dev):
+    rng = np.random.default_rng(99)
+    n, c, h, wd, o = 1, 64, 6, 6, 70
+    x = rand_pm1(rng, (n, c, h, wd))
+    w = rand_pm1(rng, (o, c, 3, 3))
+    imin, imax = np.iinfo(np.int32).min, np.iinfo(np.int32).max
+    thr = np.zeros(o, dtype=np.int32)
+    thr[0::3] = imin
+    thr[1::3] = imax
+    _, want = oracle_fused(x, w, 1, 1, thr)
+    got = gpu_conv(dev, x, w, 1, 1, thr=thr)
+    np.testing.assert_array_equal(got, want)
+    assert np.all(got[..., -1] >> (o % 32) == 0)  # tail bits of the last word are zero
+
+
+@pytest.mark.parametrize("rows,c_out", [(1, 1), (50, 32), (777, 70), (4096, 256), (33, 1000), (9, 64)])
+def test_standalone_epilogue_matches_oracle(dev, rows, c_out):
+    rng = np.random.default_rng(rows + c_out)
+    y = rng.integers(-300, 301, size=(rows, c_out)).astype(np.int32)
+    thr = rng.integers(-100, 101, size=c_out).astype(np.int32)
+    thr[0] = np.iinfo(np.int32).min
+    thr[-1] = np.iinfo(np.int32).max if c_out > 1 else thr[-1]
+    want = oracle.pack_channels(oracle.threshold_sign(y, thr).reshape(rows, c_out, 1))[:, 0, :]
+    out = Guarded(want.size, dev)
+    B.check(B.bcnn_threshold_sign_pack(up(y, dev), up(thr, dev), rows, c_out, out.ptr), "thr")
+    np.testing.assert_array_equal(out.get().reshape(want.shape), want)
+
+
+# ------------------------------------------------------------- layer chains
+def _oracle_chain(x, ws, ts, stride, pad):
+    """Oracle layer by layer: sums -> threshold sign -> next layer's +-1 input."""
+    cur = x
+    packed = None
+    for w, t in zip(ws, ts):
+        y = oracle.conv2d_pm1(cur, w, stride, pad)
+        s = oracle.threshold_sign(y, t)                      # [n, ho, wo, o]
+        n, ho, wo, o = s.shape
+        packed = oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))
+        cur = np.ascontiguousarray(s.transpose(0, 3, 1, 2))  # NCHW for the next layer
+    return packed
+
+
+def _gpu_chain(dev, cfg_n, c, h, wd, o, k, stride, pad, xp, wps, thrs, variant):
+    cur = xp
+    hh, ww, cc = h, wd, c
+    for wp, t in zip(wps, thrs):
+        desc = B.conv_desc(cfg_n, cc, hh, ww, o, k, stride, pad)
+        cur = B.conv2d_binary_sign_pack(desc, cur, wp, t, variant=variant)
+        hh, ww = B.out_shape(desc)
+        cc = o
+    torch.cuda.synchronize()
+    return cur
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+def test_small_chain_packed_handoff(dev, variant):
+    rng = np.random.default_rng(2024)
+    n, c, h, wd = 5, 128, 7, 7
+    x = rand_pm1(rng, (n, c, h, wd))
+    ws = [rand_pm1(rng, (c, c, 3, 3)) for _ in range(3)]
+    bound = int(2 * math.sqrt(c * 9))
+    ts = [rng.integers(-bound, bound + 1, size=c).astype(np.int32) for _ in range(3)]
+    want = _oracle_chain(x, ws, ts, 1, 1)
+    xp = B.pack_nchw(up(x, dev))
+    wps = [B.pack_nchw(up(w, dev)) for w in ws]
+    got = _gpu_chain(dev, n, c, h, wd, c, 3, 1, 1, xp, wps, [up(t, dev) for t in ts], variant)
+    np.testing.assert_array_equal(got.cpu().numpy().view(np.uint32), want)
+
+
+# ------------------------------------- the five benchmark shapes at full size
+def _sample_images(n):
+    return sorted(set([0, n // 2, n - 1]))
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("index", [2, 3, 4, 5])
+def test_full_size_config_on_sampled_images(dev, index, variant):
+    """Full-size launch (the one the benchmark times); the oracle evaluates
+    whole images picked from the batch (first, middle, last), every pixel and
+    channel of them, through all layers of the chain.  Inputs are packed on
+    the GPU from the real-valued tensor, so the packing kernel is covered at
+    full size too."""
+    cfg, x, ws, ts = W.make_inputs(index)
+    images = _sample_images(cfg.n)
+    x_real = W.real_with_sign(W.seeds(index)[0], x)
+    xp = B.pack_nchw(up(x_real, dev))                      # [n, h*w, cw]
+    del x_real
+    wps = [B.pack_nchw(up(w, dev)) for w in ws]
+    sub = x[images]
+    np.testing.assert_array_equal(xp[images].cpu().numpy().view(np.uint32), oracle_pack_nchw(sub))
+    for w, wp in zip(ws, wps):
+        np.testing.assert_array_equal(wp.cpu().numpy().view(np.uint32), oracle_pack_weights(w))
+    if cfg.fused:
+        thr_dev = [up(t, dev) for t in ts]
+        got = _gpu_chain(dev, cfg.n, cfg.c_in, cfg.h, cfg.w, cfg.c_out, cfg.k, cfg.stride, cfg.pad,
+                         xp, wps, thr_dev, variant)
+        want = _oracle_chain(sub, ws, ts, cfg.stride, cfg.pad)
+        np.testing.assert_array_equal(got[images].cpu().numpy().view(np.uint32), want)
+    else:
+        desc = B.conv_desc(cfg.n, cfg.c_in, cfg.h, cfg.w, cfg.c_out, cfg.k, cfg.stride, cfg.pad)
+        got = B.conv2d_binary(desc, xp, wps[0], variant=variant)
+        torch.cuda.synchronize()
+        want = oracle.conv2d_pm1(sub, ws[0], cfg.stride, cfg.pad)
+        np.testing.assert_array_equal(got[images].cpu().numpy(), want)
+        # properties that hold for every element at any size
+        kk = W.k_total(cfg)
+        assert int(got.abs().max()) <= kk
+        assert int(((got - kk) % 2).abs().max()) == 0
