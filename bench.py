@@ -1,0 +1,278 @@
+#!/usr/bin/env python3
+"""Throughput of the binary-convolution hot path on one MI355X.
+
+One step = one pass of the whole hot path over the five synthetic layer shapes:
+for each shape, sign+pack of the real-valued NCHW input (bcnn_pack), then the
+binary convolution (int32 sums for shapes 1-2, fused threshold/sign/repack for
+3-5, shape 5 being a chain of four layers with packed hand-off).  Weights are
+packed once, outside the timed region, as at inference.  All inputs are
+resident in HBM before the clock starts.
+
+Prints ONE JSON line.  `value` is total binary ops per step / step time
+(1 binary multiply-accumulate = 2 binary ops, padded taps counted).
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# VALU xor+popcount peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-ops/s;
+# one v_xor_b32 + one v_bcnt_u32_b32 (2 lane-ops) do 32 multiply-accumulates
+# = 64 binary ops  ->  39.3e12 / 2 * 64 = 1258 T binary ops/s.
+VALU_PEAK_TBOPS = 256 * 64 * 2.4e9 * 32 / 1e12
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma_i8", "mfma_fp4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-aux", action="store_true", help="skip the stand-alone kernel measurements")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (images shard over the batch "
+                 "dimension with no exchange; no multi-GPU figure is produced). Use --gpus 1.")
+    import numpy as np
+    import torch
+
+    from paper_2010_00704_amd import binding as B
+    from paper_2010_00704_amd import workloads as W
+
+    B.lib()  # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    variant = {"auto": B.BCNN_VARIANT_AUTO, "valu": B.BCNN_VARIANT_VALU,
+               "mfma_i8": B.BCNN_VARIANT_MFMA_I8, "mfma_fp4": B.BCNN_VARIANT_MFMA_FP4}[args.variant]
+
+    # ---------------------------------------------------------------- inputs
+    work = []
+    for index in range(1, 6):
+        cfg, x, ws, ts = W.make_inputs(index)
+        x_real = torch.from_numpy(W.real_with_sign(W.seeds(index)[0], x)).to(dev)
+        del x
+        wps = [B.pack_nchw(torch.from_numpy(w).to(dev)) for w in ws]
+        thr = [torch.from_numpy(t).to(dev) if t is not None else None for t in ts]
+        ho, wo = W.out_hw(cfg)
+        cw = (cfg.c_in + 31) // 32
+        cwo = (cfg.c_out + 31) // 32
+        xp = torch.empty((cfg.n, cfg.h * cfg.w, cw), dtype=torch.int32, device=dev)
+        descs, outs = [], []
+        c, h, w_ = cfg.c_in, cfg.h, cfg.w
+        for _ in range(cfg.layers):
+            d = B.conv_desc(cfg.n, c, h, w_, cfg.c_out, cfg.k, cfg.stride, cfg.pad)
+            descs.append(d)
+            h, w_ = B.out_shape(d)
+            c = cfg.c_out
+            if cfg.fused:
+                outs.append(torch.empty((cfg.n, h * w_, cwo), dtype=torch.int32, device=dev))
+            else:
+                outs.append(torch.empty((cfg.n, h, w_, cfg.c_out), dtype=torch.int32, device=dev))
+        work.append(dict(cfg=cfg, x_real=x_real, xp=xp, wps=wps, thr=thr, descs=descs, outs=outs,
+                         ev=None, pack_ms=0.0, conv_ms=0.0))
+    torch.cuda.synchronize()
+
+    def run_config(wk, timed):
+        cfg = wk["cfg"]
+        if timed:
+            wk["ev"][0].record()
+        B.check(B.bcnn_pack(wk["x_real"], B.BCNN_F32, cfg.n, cfg.c_in, cfg.h * cfg.w, wk["xp"]), "pack")
+        if timed:
+            wk["ev"][1].record()
+        cur = wk["xp"]
+        for d, wp, t, out in zip(wk["descs"], wk["wps"], wk["thr"], wk["outs"]):
+            B.check(B.bcnn_conv2d_binary_variant(d, cur, wp, t, out, variant), "conv")
+            cur = out
+        if timed:
+            wk["ev"][2].record()
+
+    def step(timed):
+        for wk in work:
+            run_config(wk, timed)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+
+    # ------------------------------------------------------------ timed region
+    # K steps enqueued back to back between two synchronisations; the wall
+    # clock around them is the step time.  Events (on torch's current stream,
+    # which is the stream every kernel is launched on) split each step into
+    # its pack and convolution parts; they are read after the region ends.
+    evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in work]
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for wk, ev in zip(work, evs[k]):
+            wk["ev"] = ev
+        step(True)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    for k in range(args.steps):
+        for wk, ev in zip(work, evs[k]):
+            wk["pack_ms"] += ev[0].elapsed_time(ev[1])
+            wk["conv_ms"] += ev[1].elapsed_time(ev[2])
+
+    total_bops = sum(W.binary_ops(wk["cfg"]) for wk in work)
+    value = total_bops / (ms_per_step * 1e-3) / 1e12
+
+    per_config = []
+    for wk in work:
+        cfg = wk["cfg"]
+        conv_ms = wk["conv_ms"] / args.steps
+        pack_ms = wk["pack_ms"] / args.steps
+        bops = W.binary_ops(cfg)
+        src_bytes = wk["x_real"].numel() * 4 + wk["xp"].numel() * 4
+        tb = bops / (conv_ms * 1e-3) / 1e12
+        per_config.append({
+            "name": cfg.name, "conv_ms": round(conv_ms, 4), "launches": cfg.layers,
+            "tbops": round(tb, 1), "frac_valu_peak": round(tb / VALU_PEAK_TBOPS, 4),
+            "pack_ms": round(pack_ms, 4),
+            "pack_gbs": round(src_bytes / (pack_ms * 1e-3) / 1e9, 1),
+        })
+
+    # ---------------------------------------------------------------- roofline
+    # Dominant kernel: the 3x3 convolution of shape 5 (four launches per step,
+    # > 60 % of the step).  Algorithmic work per launch = 2*M*N*K binary ops.
+    dom = work[4]
+    dom_ms = dom["conv_ms"] / args.steps / dom["cfg"].layers
+    dom_bops = W.binary_ops(dom["cfg"]) / dom["cfg"].layers
+    achieved = dom_bops / (dom_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "conv 3x3 c1024 7x7 n256 (shape 5, per launch)",
+        "bound": "alu", "achieved": round(achieved, 1), "peak": round(VALU_PEAK_TBOPS, 1),
+        "unit": "TBOP/s", "frac": round(achieved / VALU_PEAK_TBOPS, 4),
+        "avg_launch_ms": round(dom_ms, 4), "traffic": None,
+    }
+
+    aux = {}
+    if not args.no_aux:
+        aux = aux_measurements(torch, B, dev, work)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(np, W)
+
+    line = {
+        "metric": "binary conv TBOPS (and % of VALU popcount peak) per layer shape, 1 MI355X",
+        "value": round(value, 2), "unit": "TBOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u32 bits -> int32",
+        "data": "synthetic",
+        "config": {"workload": "all five layer shapes per step: pack + binary conv "
+                               "(cfg1-2 int32 sums, cfg3-4 fused sign-pack, cfg5 4-layer chain)",
+                   "variant": args.variant},
+        "frac_valu_peak": round(value / VALU_PEAK_TBOPS, 4),
+        "per_config": per_config,
+        "roofline": roofline,
+        "aux": aux,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+def aux_measurements(torch, B, dev, work):
+    """Stand-alone figures outside the timed steps: the measured xor+popcount
+    issue rate, and HBM rates of the pack and epilogue kernels on rotating
+    buffers larger than the last-level cache."""
+    out = {}
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+
+    # VALU issue-rate probe: blocks*256 lanes * iters * 64 pairs * 64 binary ops
+    blocks, iters = 256 * 16, 4000
+    sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
+    B.check(B.bcnn_diag_valu_peak(sink, blocks, 10), "peak")
+    a, b = ev(), ev()
+    a.record()
+    B.check(B.bcnn_diag_valu_peak(sink, blocks, iters), "peak")
+    b.record()
+    b.synchronize()
+    ms = a.elapsed_time(b)
+    tbops = blocks * 256 * iters * 64 * 64 / (ms * 1e-3) / 1e12
+    out["valu_probe_tbops"] = round(tbops, 1)
+    out["valu_probe_implied_ghz"] = round(tbops / (256 * 64 * 32) * 1e3, 3)
+
+    # pack kernel on the largest input (shape 4, 205 MB fp32), 4 rotating copies
+    wk = work[3]
+    cfg = wk["cfg"]
+    srcs = [wk["x_real"]] + [wk["x_real"].clone() for _ in range(3)]
+    reps = 12
+    for s in srcs:
+        B.check(B.bcnn_pack(s, B.BCNN_F32, cfg.n, cfg.c_in, cfg.h * cfg.w, wk["xp"]), "pack")
+    a, b = ev(), ev()
+    a.record()
+    for r in range(reps):
+        B.check(B.bcnn_pack(srcs[r % 4], B.BCNN_F32, cfg.n, cfg.c_in, cfg.h * cfg.w, wk["xp"]), "pack")
+    b.record()
+    b.synchronize()
+    ms = a.elapsed_time(b) / reps
+    nbytes = srcs[0].numel() * 4 + wk["xp"].numel() * 4
+    out["pack_f32_gbs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    out["pack_f32_frac_hbm"] = round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    del srcs
+
+    # stand-alone epilogue on shape 4's int32 sums (102.8 MB), 4 rotating copies
+    rows, c_out = cfg.n * 28 * 28, cfg.c_out
+    ys = [torch.randint(-300, 300, (rows, c_out), dtype=torch.int32, device=dev) for _ in range(4)]
+    yp = torch.empty((rows, c_out // 32), dtype=torch.int32, device=dev)
+    thr = wk["thr"][0]
+    for y in ys:
+        B.check(B.bcnn_threshold_sign_pack(y, thr, rows, c_out, yp), "thr")
+    a, b = ev(), ev()
+    a.record()
+    for r in range(reps):
+        B.check(B.bcnn_threshold_sign_pack(ys[r % 4], thr, rows, c_out, yp), "thr")
+    b.record()
+    b.synchronize()
+    ms = a.elapsed_time(b) / reps
+    nbytes = ys[0].numel() * 4 + yp.numel() * 4
+    out["epilogue_gbs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    out["epilogue_frac_hbm"] = round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+
+    # plain copy of the same size for reference (what a streaming kernel reaches here)
+    dst = torch.empty_like(ys[0])
+    B.check(B.bcnn_diag_copy_u32(ys[0], dst, ys[0].numel()), "copy")
+    a, b = ev(), ev()
+    a.record()
+    for r in range(reps):
+        B.check(B.bcnn_diag_copy_u32(ys[r % 4], dst, ys[0].numel()), "copy")
+    b.record()
+    b.synchronize()
+    ms = a.elapsed_time(b) / reps
+    out["copy_gbs_read_plus_write"] = round(2 * ys[0].numel() * 4 / (ms * 1e-3) / 1e9, 1)
+    return out
+
+
+def cpu_baseline(np, W):
+    """The CPU oracle, as it stands, on a bounded sample: shape 3 (3x3, c256,
+    28x28, fused epilogue), all 64 images."""
+    import oracle
+    cfg, x, ws, ts = W.make_inputs(3)
+    oracle.conv2d_pm1(x[:1], ws[0], cfg.stride, cfg.pad)  # load + first touch
+    t0 = time.perf_counter()
+    y = oracle.conv2d_pm1(x, ws[0], cfg.stride, cfg.pad)
+    s = oracle.threshold_sign(y, ts[0])
+    n, ho, wo, o = s.shape
+    oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))
+    dt = time.perf_counter() - t0
+    bops = 2 * n * ho * wo * o * W.k_total(cfg)
+    return {"value": round(bops / dt / 1e12, 6), "unit": "TBOPS", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "shape 3 (n=64,c=256,28x28,3x3,s1,p1, fused epilogue), whole batch"}
+
+
+if __name__ == "__main__":
+    main()
