@@ -27,6 +27,7 @@ if ROOT not in sys.path:
 # = 64 binary ops  ->  39.3e12 / 2 * 64 = 1258 T binary ops/s.
 VALU_PEAK_TBOPS = 256 * 64 * 2.4e9 * 32 / 1e12
 HBM_PEAK_GBS = 8000.0
+MFMA_FP4_PEAK_TFLOPS = 10100.0  # dense fp4 matrix rate of MI355X
 
 
 def parse():
@@ -151,12 +152,22 @@ def main():
     dom_ms = dom["conv_ms"] / args.steps / dom["cfg"].layers
     dom_bops = W.binary_ops(dom["cfg"]) / dom["cfg"].layers
     achieved = dom_bops / (dom_ms * 1e-3) / 1e12
-    roofline = {
-        "kernel": "conv 3x3 c1024 7x7 n256 (shape 5, per launch)",
-        "bound": "alu", "achieved": round(achieved, 1), "peak": round(VALU_PEAK_TBOPS, 1),
-        "unit": "TBOP/s", "frac": round(achieved / VALU_PEAK_TBOPS, 4),
-        "avg_launch_ms": round(dom_ms, 4), "traffic": None,
-    }
+    on_mfma = args.variant in ("auto", "mfma_fp4")
+    if on_mfma:
+        # fp4 matrix-core path: one binary multiply-accumulate is one fp4 FMA = 2 FLOP
+        roofline = {
+            "kernel": "conv_mfma_fp4_kernel, 3x3 c1024 7x7 n256 (shape 5, per launch)",
+            "bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_FP4_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
+            "avg_launch_ms": round(dom_ms, 4), "traffic": None,
+        }
+    else:
+        roofline = {
+            "kernel": "conv_valu_kernel, 3x3 c1024 7x7 n256 (shape 5, per launch)",
+            "bound": "alu", "achieved": round(achieved, 1), "peak": round(VALU_PEAK_TBOPS, 1),
+            "unit": "TBOP/s", "frac": round(achieved / VALU_PEAK_TBOPS, 4),
+            "avg_launch_ms": round(dom_ms, 4), "traffic": None,
+        }
 
     aux = {}
     if not args.no_aux:

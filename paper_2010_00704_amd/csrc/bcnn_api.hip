@@ -87,11 +87,21 @@ int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w,
     hipError_t e;
     switch (variant) {
         case BCNN_VARIANT_AUTO:
+            // The matrix-core path wins wherever its 128 x 256 tiles are
+            // reasonably full; small or ragged problems stay on the vector ALUs.
+            if (conv_mfma_fp4_supported(s, x, w) && s.c_out >= 64 && s.m >= 1024)
+                e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, st);
+            else
+                e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, st);
+            break;
         case BCNN_VARIANT_VALU:
             e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, st);
             break;
-        case BCNN_VARIANT_MFMA_I8:
         case BCNN_VARIANT_MFMA_FP4:
+            if (!conv_mfma_fp4_supported(s, x, w)) return BCNN_ERR_UNSUPPORTED;
+            e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, st);
+            break;
+        case BCNN_VARIANT_MFMA_I8:
             return BCNN_ERR_UNSUPPORTED;
         default:
             return BCNN_ERR_INVALID_ARG;

@@ -27,6 +27,10 @@ hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int6
                                       int64_t c_out, uint32_t* y_packed, hipStream_t stream);
 hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                             const int32_t* thr, void* out, hipStream_t stream);
+// fp4 matrix-core variant; `supported` says whether it covers the shape/alignment.
+bool conv_mfma_fp4_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
+hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
+                                const int32_t* thr, void* out, hipStream_t stream);
 hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
 
 }  // namespace bcnn
