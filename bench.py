@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma_i8", "mfma_fp4"])
+    ap.add_argument("--shapes", default="1,2,3,4,5",
+                    help="comma list of layer shapes in the step (default all five; a subset is for profiling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-aux", action="store_true", help="skip the stand-alone kernel measurements")
     return ap.parse_args()
@@ -60,7 +62,8 @@ def main():
 
     # ---------------------------------------------------------------- inputs
     work = []
-    for index in range(1, 6):
+    shapes = sorted(set(int(v) for v in args.shapes.split(",")))
+    for index in shapes:
         cfg, x, ws, ts = W.make_inputs(index)
         x_real = torch.from_numpy(W.real_with_sign(W.seeds(index)[0], x)).to(dev)
         del x
@@ -148,7 +151,7 @@ def main():
     # ---------------------------------------------------------------- roofline
     # Dominant kernel: the 3x3 convolution of shape 5 (four launches per step,
     # > 60 % of the step).  Algorithmic work per launch = 2*M*N*K binary ops.
-    dom = work[4]
+    dom = work[-1] if 5 in shapes else max(work, key=lambda wk: wk["conv_ms"])
     dom_ms = dom["conv_ms"] / args.steps / dom["cfg"].layers
     dom_bops = W.binary_ops(dom["cfg"]) / dom["cfg"].layers
     achieved = dom_bops / (dom_ms * 1e-3) / 1e12
@@ -156,21 +159,21 @@ def main():
     if on_mfma:
         # fp4 matrix-core path: one binary multiply-accumulate is one fp4 FMA = 2 FLOP
         roofline = {
-            "kernel": "conv_mfma_fp4_kernel, 3x3 c1024 7x7 n256 (shape 5, per launch)",
+            "kernel": "conv_mfma_fp4_kernel on " + dom["cfg"].name + " (per launch)",
             "bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_FP4_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
             "avg_launch_ms": round(dom_ms, 4), "traffic": None,
         }
     else:
         roofline = {
-            "kernel": "conv_valu_kernel, 3x3 c1024 7x7 n256 (shape 5, per launch)",
+            "kernel": "conv_valu_kernel on " + dom["cfg"].name + " (per launch)",
             "bound": "alu", "achieved": round(achieved, 1), "peak": round(VALU_PEAK_TBOPS, 1),
             "unit": "TBOP/s", "frac": round(achieved / VALU_PEAK_TBOPS, 4),
             "avg_launch_ms": round(dom_ms, 4), "traffic": None,
         }
 
     aux = {}
-    if not args.no_aux:
+    if not args.no_aux and shapes == [1, 2, 3, 4, 5]:
         aux = aux_measurements(torch, B, dev, work)
 
     cpu = None
@@ -183,8 +186,9 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u32 bits -> int32",
         "data": "synthetic",
-        "config": {"workload": "all five layer shapes per step: pack + binary conv "
-                               "(cfg1-2 int32 sums, cfg3-4 fused sign-pack, cfg5 4-layer chain)",
+        "config": {"workload": ("all five layer shapes per step: pack + binary conv "
+                                "(cfg1-2 int32 sums, cfg3-4 fused sign-pack, cfg5 4-layer chain)")
+                   if shapes == [1, 2, 3, 4, 5] else "SUBSET of the layer shapes (profiling run): %s" % shapes,
                    "variant": args.variant},
         "frac_valu_peak": round(value / VALU_PEAK_TBOPS, 4),
         "per_config": per_config,

@@ -139,15 +139,28 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_fp4_kernel(
         b_slot[i] = A_UNITS + (row >> 5) * 64 + half * 32 + (row & 31);
     }
 
+    // Position of the next chunk's two 16-byte K-units (even unit: half 0, odd
+    // unit: half 1) as (filter row u, filter column v, unit within the tap).
+    // Wave-uniform and advanced incrementally, so no integer division runs in
+    // the loop; a thread picks the entry of its half.
+    struct KPos { int u, v, ut; };
+    auto advance = [&](KPos& p) {
+        if (++p.ut == a.units_per_tap) {
+            p.ut = 0;
+            if (++p.v == s.ks) { p.v = 0; ++p.u; }
+        }
+    };
+    KPos k0 = {0, 0, 0}, k1 = {0, 0, 0};
+    advance(k1);
+
     uint4 ga, gb[2];
-    auto fetch = [&](int chunk) {
+    auto fetch = [&](int chunk) {  // must be called with chunk = 0, 1, 2, ... in order
         const int uu = chunk * 2 + half;  // this thread's unit along K
         const bool real = uu < a.n_units;
         ga = real ? *reinterpret_cast<const uint4*>(wsrc + (size_t)uu * 4) : make_uint4(0, 0, 0, 0);
-        const int uc = real ? uu : 0;
-        const int tap = uc / a.units_per_tap;
-        const int off = (uc - tap * a.units_per_tap) * 4;
-        const int u = tap / s.ks, v = tap - u * s.ks;
+        const int u = half ? k1.u : k0.u;
+        const int v = half ? k1.v : k0.v;
+        const int off = (half ? k1.ut : k0.ut) * 4;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int ih = ph[i] + u, iw = pw[i] + v;
@@ -156,6 +169,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_fp4_kernel(
             const uint32_t* p = x + ((size_t)(pn[i] * s.h + ihc) * s.w + iwc) * s.cw + off;
             gb[i] = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
         }
+        advance(k0); advance(k0);
+        advance(k1); advance(k1);
     };
     auto commit = [&](int buf) {
         stage[buf][a_slot] = ga;
