@@ -113,26 +113,29 @@ struct MfmaArgs {
 };
 
 // PB = pixel blocks (of 32) per wave; the workgroup covers 2*32*PB pixels.
-template <int PB, bool FUSED>
+template <int PB, bool FUSED, bool EVEN>
 __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
     const int32_t* __restrict__ thr, void* __restrict__ out)
 {
     constexpr int WG_PX = 64 * PB;
-    constexpr int B_UNITS = WG_PX * 2;
-    constexpr int NB = (B_UNITS + 255) / 256;  // input units staged per thread and chunk
-    // One stage = the chunk's 8 K-words of every row, as 8-byte elements
-    // [K-half][word pair][row]: a lane reads the pair it needs with one
-    // ds_read_b64, lanes of a half-wave at consecutive addresses.
-    constexpr int A_ELEMS = 4 * WG_CH, B_ELEMS = 4 * WG_PX;
-    constexpr int STAGE_ELEMS = A_ELEMS + B_ELEMS;
-    __shared__ uint2 stage[2][STAGE_ELEMS + 1];  // + 1: spare element for out-of-tile rows
+    // One stage = the chunk's 8 K-words of every row of the tile, as 16-byte
+    // units (4 words = one K-half of a row).  Unit order: [block of 32 rows]
+    // [K-half][row], blocks 0..3 weights, 4.. inputs; one wave-wide load fills
+    // one block (1 KB), and lane l of a reader wave finds the words of its MFMA
+    // row at unit 64*block + l.  Three stages rotate.
+    constexpr int NBLK = 4 + 2 * PB;             // blocks per stage
+    constexpr int STAGE_BYTES = NBLK * 1024;
+    constexpr int NL = (NBLK + 3) / 4;           // loads per wave and chunk
+    __shared__ uint4 stage[3 * NBLK * 64];
     __shared__ int wpop_lds[WG_CH];
     const ConvShape& s = a.s;
     const int t = threadIdx.x;
     const int lane = t & 63;
-    const int wave = t >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wc = wave & 1, wp = wave >> 1;
+    const int hsel = lane >> 5;
+    const int j = lane & 31;
 
     // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs; give
     // each XCD a contiguous range of tiles (channel tile fastest) so that the
@@ -146,29 +149,32 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     const int o0 = ctile * WG_CH;
     const int m0 = ptile * WG_PX;
 
-    // ---- loader state.  Per chunk a thread stages one 16-byte weight unit and
-    // up to NB input units; its K-half (even or odd unit of the chunk) is fixed.
-    const int half = t & 1;
-    const int lrow = t >> 1;  // 0..127
+    // ---- loader state.  Global -> LDS directly (buffer_load ... lds: lane l
+    // of a wave writes 16 bytes at the LDS base of the instruction + 16*l, no
+    // registers in between).  Per chunk wave w loads block w (weights) and the
+    // input blocks w, w+4, ... ; lane l covers row l%32 of the block and the
+    // K-half l/32 (even or odd 16-byte unit of the chunk).  A block index past
+    // the end is clamped: the same data lands twice, which is harmless, and
+    // every wave issues the same number of loads.
     int wrow_bytes;
     {
-        int ch = o0 + 32 * (lrow >> 5) + row_to_channel(lrow & 31);
+        int ch = o0 + 32 * wave + row_to_channel(j);
         ch = ch < s.c_out ? ch : s.c_out - 1;
         wrow_bytes = ch * a.n_units * 16;
     }
-    const int a_slot = half * 2 * WG_CH + lrow;   // element of word pair 0; pair 1 is WG_CH further
-    // For input row i: word offset of the window's top-left tap (may point
-    // outside the image; only used where the tap's validity bit is set) and
-    // one validity bit per tap.
-    int rbase[NB];
-    uint32_t vmask[NB];
-    int b_slot[NB];
-    int b_pair1 = WG_PX;     // distance from a row's word pair 0 to its pair 1 (0: both go to the spare element)
+    // For input block i of this wave: word offset of the row's window top-left
+    // tap (may point outside the image; only used where the tap's validity
+    // bit is set) and one validity bit per tap.
+    int rbase[NL - 1];
+    uint32_t vmask[NL - 1];
+    int bblk[NL - 1];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        const int row = lrow + 128 * i;
-        const bool row_ok = row < WG_PX;
-        int m = m0 + (row_ok ? row : 0);
+    for (int i = 0; i < NL - 1; ++i) {
+        int b = wave + 4 * i;
+        b = b < 2 * PB ? b : 2 * PB - 1;
+        bblk[i] = b;
+        const int row = 32 * b + j;
+        int m = m0 + row;
         m = m < s.m ? m : s.m - 1;
         const int hw = s.ho * s.wo;
         const int n = m / hw;
@@ -181,72 +187,109 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
         for (int u = 0; u < s.ks; ++u)
             for (int v = 0; v < s.ks; ++v) {
                 const int ih = ph + u, iw = pw + v;
-                if (row_ok && ih >= 0 && ih < s.h && iw >= 0 && iw < s.w) vm |= 1u << (u * s.ks + v);
+                if (ih >= 0 && ih < s.h && iw >= 0 && iw < s.w) vm |= 1u << (u * s.ks + v);
             }
         vmask[i] = vm;
-        b_slot[i] = row_ok ? A_ELEMS + half * 2 * WG_PX + row : STAGE_ELEMS;
-        if (i == NB - 1) b_pair1 = row_ok ? WG_PX : 0;   // only the last row of a thread can be out of the tile
     }
 
-    // Position of this thread's next K-unit (even units for half 0, odd for
-    // half 1): tap index, filter column, unit within the tap, and the word
-    // offset relative to the window's top-left tap.  Advanced one unit at a
-    // time with selects only (per-thread values, so the compiler keeps them
-    // on the vector ALU and the loop body stays free of branches); no
-    // division runs in the loop.
+    // ---- position of the chunk to fetch next along K.
+    // Lanes 0-31 fetch the chunk's even 16-byte unit, lanes 32-63 the odd one.
+    // All of it is wave-uniform scalar arithmetic without selects or division
+    // (compare results used as 0/1 factors), so it never branches and costs
+    // the vector ALU nothing.
+    //   EVEN (units per tap even: C_in a multiple of 256): both units of a
+    //     chunk lie in one tap, 16 bytes apart, so one (tap, offset) pair
+    //     serves the wave and the lanes' halves are folded into rbase/wrow.
+    //     Past the last chunk the position stops advancing: the extra fetches
+    //     of the pipeline's tail reload the last chunk's inputs (and zeros for
+    //     the weights) into stages whose contents are never multiplied.
+    //   otherwise: the two units are tracked separately and each lane selects
+    //     its own; units past the end (K padding) read as zero.
     const int row_jump = (s.w - s.ks) * s.cw;
-    int f_unit = 0, f_tap = 0, f_v = 0, f_ut = 0, f_off = 0;
-    auto advance = [&]() {
-        const int ut1 = f_ut + 1;
-        const bool tap_done = ut1 == a.units_per_tap;
-        f_ut = tap_done ? 0 : ut1;
-        f_tap += tap_done ? 1 : 0;
-        const int v1 = f_v + (tap_done ? 1 : 0);
-        const bool row_done = v1 == s.ks;
-        f_v = row_done ? 0 : v1;
-        f_off += 4 + (row_done ? row_jump : 0);
-        f_unit += 1;
+    struct KPos { int unit, tap, v, ut, off; };
+    KPos k0 = {0, 0, 0, 0, 0}, k1 = {0, 0, 0, 0, 0};
+    auto advance1 = [&](KPos& p, int per_tap, int step_words, int go) {
+        const int ut1 = p.ut + go;
+        const int tap_done = ut1 == per_tap ? 1 : 0;
+        p.ut = ut1 * (1 - tap_done);
+        p.tap += tap_done;
+        const int v1 = p.v + tap_done;
+        const int row_done = v1 == s.ks ? 1 : 0;
+        p.v = v1 * (1 - row_done);
+        p.off += go * step_words + row_done * row_jump;
+        p.unit += go;
     };
-    if (half) advance();
-
-    // Global -> registers, one 16-byte unit per call.  Raw buffer loads: a
-    // lane whose unit must read as zero (out-of-image tap, K padding past the
-    // last real unit) gets an offset beyond the buffer and the hardware range
-    // check returns 0, so the loader has no branches.
-    const __amdgpu_buffer_rsrc_t xres =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(x), 0, a.x_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t wres =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w), 0, a.w_bytes, 0x00020000);
-    constexpr uint32_t OOB = 0xFFFFFFF0u;
-    v4i ga, gb[NB];
-    int wpop = 0;            // set weight bits at positions 4i+0..2 seen by this thread
-    // (Offsets are chosen with mask arithmetic, not ?:, which the compiler
-    // would turn into divergent branches that split the loop body.)
-    auto fetch_piece = [&](int j) {  // j = 0: weights; j = 1..NB: input rows
-        const uint32_t real = f_unit < a.n_units ? 1u : 0u;
-        if (j == 0) {
-            const uint32_t m = 0u - real;
-            const uint32_t o = ((uint32_t)(wrow_bytes + f_unit * 16) & m) | (OOB & ~m);
-            ga = __builtin_amdgcn_raw_buffer_load_b128(wres, o, 0, 0);
+    if constexpr (!EVEN) advance1(k1, a.units_per_tap, 4, 1);
+    int fetched = 0;   // chunks fetched so far (EVEN only)
+    auto advance = [&]() {
+        if constexpr (EVEN) {
+            fetched += 1;
+            // k0.unit counts chunks here; stop on the last one
+            advance1(k0, a.units_per_tap >> 1, 8, k0.unit + 1 < a.n_chunks ? 1 : 0);
         } else {
-            const int i = j - 1;
-            const uint32_t m = 0u - (real & (vmask[i] >> (f_tap & 31)));
-            const uint32_t o = (((uint32_t)(rbase[i] + f_off) << 2) & m) | (OOB & ~m);
-            gb[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, o, 0, 0);
+            advance1(k0, a.units_per_tap, 4, 1); advance1(k0, a.units_per_tap, 4, 1);
+            advance1(k1, a.units_per_tap, 4, 1); advance1(k1, a.units_per_tap, 4, 1);
         }
     };
-    // Threads whose input row lies beyond the tile write to the spare element
-    // behind the stage instead of branching around the store.
-    auto commit_piece = [&](int buf, int j) {
-        uint2* st = stage[buf];
-        if (j == 0) {
-            st[a_slot] = make_uint2((uint32_t)ga[0], (uint32_t)ga[1]);
-            st[a_slot + WG_CH] = make_uint2((uint32_t)ga[2], (uint32_t)ga[3]);
-            wpop += __builtin_popcount((uint32_t)ga[0] & 0x77777777u) + __builtin_popcount((uint32_t)ga[1] & 0x77777777u) +
-                    __builtin_popcount((uint32_t)ga[2] & 0x77777777u) + __builtin_popcount((uint32_t)ga[3] & 0x77777777u);
+    if constexpr (EVEN) {   // fold the lane's K-half into its base offsets
+        wrow_bytes += 16 * hsel;
+#pragma unroll
+        for (int i = 0; i < NL - 1; ++i) rbase[i] += 4 * hsel;
+    }
+
+    // ---- global -> LDS loads.
+    // A lane whose unit must read as zero (out-of-image tap, K padding past
+    // the last real unit) gets the offset -16, beyond any buffer: the hardware
+    // range check makes the load deliver 0, so the loader has no branches.
+    // The loads are written as inline assembly on purpose: the compiler's
+    // wait-count pass treats every later LDS read as possibly aliasing a
+    // pending global->LDS load and would force vmcnt(0) in front of it, which
+    // serialises the pipeline.  Written this way the compiler does not see
+    // them, and the explicit s_waitcnt vmcnt(N) before each barrier below is
+    // what orders them (N = loads that may still be in flight).  M0 carries
+    // the LDS destination; nothing else in this kernel uses M0.  The v_bfi
+    // between the M0 write and the load (offset = mask ? offset : -16) also
+    // fills the wait state that pair needs.
+    auto make_rsrc = [](const void* base, int bytes) -> v4i {
+        const uint64_t p = reinterpret_cast<uint64_t>(base);
+        // dword 1: address bits 47:32, stride 0; dword 3: 32-bit untyped data format
+        return v4i{(int)(uint32_t)p, (int)((uint32_t)(p >> 32) & 0xFFFFu), bytes, 0x00020000};
+    };
+    const v4i xres = make_rsrc(x, a.x_bytes);
+    const v4i wres = make_rsrc(w, a.w_bytes);
+    const uint32_t stage_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)stage;
+    auto dma16 = [&](const v4i& rsrc, uint32_t lds_byte, uint32_t offset, uint32_t mask) {
+        uint32_t tmp;
+        asm volatile("s_mov_b32 m0, %1\n\tv_bfi_b32 %0, %3, %2, -16\n\tbuffer_load_dwordx4 %0, %4, 0 offen lds"
+                     : "=&v"(tmp) : "s"(lds_byte), "v"(offset), "v"(mask), "s"(rsrc) : "memory");
+    };
+    // per chunk, before its fetch_piece calls
+    int f_real = -1, f_tap = 0, f_off = 0, f_woff = 0;
+    auto fetch_begin = [&]() {
+        if constexpr (EVEN) {
+            // weights of a chunk past the end must read as zero: the readers
+            // count the set bits of every weight word that passes through
+            f_real = -(fetched < a.n_chunks ? 1 : 0);
+            f_tap = k0.tap;
+            f_off = k0.off;
+            f_woff = wrow_bytes + k0.unit * 32;
         } else {
-            st[b_slot[j - 1]] = make_uint2((uint32_t)gb[j - 1][0], (uint32_t)gb[j - 1][1]);
-            st[b_slot[j - 1] + (j == NB ? b_pair1 : WG_PX)] = make_uint2((uint32_t)gb[j - 1][2], (uint32_t)gb[j - 1][3]);
+            const int unit = hsel ? k1.unit : k0.unit;
+            f_real = unit < a.n_units ? -1 : 0;
+            f_tap = hsel ? k1.tap : k0.tap;
+            f_off = hsel ? k1.off : k0.off;
+            f_woff = wrow_bytes + unit * 16;
+        }
+    };
+    auto fetch_piece = [&](int buf, int i) {  // i = 0: weight block; i = 1..NL-1: input blocks
+        if (i == 0) {
+            dma16(wres, stage_lds + (uint32_t)(buf * NBLK + wave) * 1024u, (uint32_t)f_woff, (uint32_t)f_real);
+        } else {
+            // validity bit of the tap, sign-extended to a mask
+            int m = __builtin_amdgcn_sbfe((int)vmask[i - 1], (uint32_t)f_tap & 31u, 1u);
+            if constexpr (!EVEN) m &= f_real;
+            dma16(xres, stage_lds + (uint32_t)(buf * NBLK + 4 + bblk[i - 1]) * 1024u,
+                  (uint32_t)(rbase[i - 1] + f_off) << 2, (uint32_t)m);
         }
     };
 
@@ -254,7 +297,6 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     //      <-> channel 32*block + 16h + r.  They start at zero; every constant
     //      and per-channel term is applied in the epilogue.
     v16f acc[CB][PB];
-    const int hsel = lane >> 5;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -272,29 +314,39 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     //   every slot : half of an input fragment two blocks ahead (fragments
     //                live in a ring of four, so few registers hold them) and
     //                a share of the next K-step's two weight fragments
-    //   K-step 0   : LDS commit of chunk c+1 (global loads issued one chunk
-    //                earlier) and LDS reads of this chunk's second word pair;
-    //                workgroup barrier at the end of the step
-    //   K-step 1   : global loads of chunk c+2
-    //   K-step 2   : LDS reads of chunk c+1's first word pair
-    //   K-step 3   : loader bookkeeping
-    // Buffer c%2 is last read in K-step 0 of chunk c (before that chunk's
-    // barrier) and next written in K-step 0 of chunk c+1 (after it).
+    //   K-step 0   : global -> LDS loads of chunk c+2; loader bookkeeping
+    //   K-step 1   : at its end, wait for this wave's loads of chunk c+1
+    //                (issued five K-steps earlier) and workgroup barrier
+    //   K-step 2   : LDS reads of chunk c+1's weight words
+    //   K-step 3   : LDS reads of chunk c+1's input words, each block's right
+    //                after that block's last use
+    // Stage c%3 holds chunk c.  All of it is read during chunk c-1, whose
+    // end every wave has reached behind chunk c's barrier; chunk c+3's loads
+    // are issued a whole chunk after that.
     constexpr int NF = CB + PB;       // words per lane and K-step: weights first, then inputs
     constexpr int NS = CB * PB;       // MFMA slots per K-step
     static_assert(CB == 2, "slot program assumes two channel blocks");
-    static_assert(NB + 1 <= NS && NF <= NS, "side work must fit the MFMA slots of a K-step");
+    static_assert(NL + 2 <= NS && NF <= NS && 2 * NL <= 15, "side work must fit the MFMA slots of a K-step");
     const Fp4Masks masks = fp4_masks();
     int fa[2][CB][4];                 // weight fragments, double buffered over K-steps
     int fb[4][4];                     // input fragments, ring over (K-step, pixel block)
-    uint2 p0[NF], p1[NF];             // this lane's words of K-steps 0,1 and 2,3 of the chunk
-    auto read_pair = [&](uint2 (&dst)[NF], int buf, int kp, int f) {
-        const int e = f < CB ? (hsel * 2 + kp) * WG_CH + 32 * (2 * wc + f) + (lane & 31)
-                             : A_ELEMS + (hsel * 2 + kp) * WG_PX + 32 * (PB * wp + (f - CB)) + (lane & 31);
-        dst[f] = stage[buf][e];
+    uint4 pw[NF];                     // this lane's four words (K-steps 0..3) of the chunk, per block
+    uint4 pwn[CB];                    // the next chunk's weight words (read before the current ones retire)
+    int wpop[CB] = {0, 0};            // set weight bits at positions 4i+0..2 of this lane's rows
+    const char* lds0 = reinterpret_cast<const char*>(stage) + lane * 16;
+    // One ds_read_b128 per block and chunk: lanes read consecutive 16-byte
+    // units, which is conflict free.  The next chunk's words replace a block's
+    // words during K-step 3, right after their last use.
+    auto read_unit = [&](uint4& dst, int buf, int f) {
+        const int blk = f < CB ? 2 * wc + f : 4 + PB * wp + (f - CB);
+        dst = *reinterpret_cast<const uint4*>(lds0 + buf * STAGE_BYTES + blk * 1024);
+    };
+    auto count_unit = [&](const uint4& q, int f) {   // well after the read, so nothing waits
+        wpop[f] += __builtin_popcount(q.x & 0x77777777u) + __builtin_popcount(q.y & 0x77777777u) +
+                   __builtin_popcount(q.z & 0x77777777u) + __builtin_popcount(q.w & 0x77777777u);
     };
     auto word_of = [&](int f, int ks) -> uint32_t {   // ks = 0..3 within the chunk
-        return ks == 0 ? p0[f].x : ks == 1 ? p0[f].y : ks == 2 ? p1[f].x : p1[f].y;
+        return ks == 0 ? pw[f].x : ks == 1 ? pw[f].y : ks == 2 ? pw[f].z : pw[f].w;
     };
     // One VGPR (8 nibbles) of a fragment; VGPR jj takes the bits 4i+jj of the
     // packed word on both sides (see the header for the values).
@@ -316,8 +368,8 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     };
     // One chunk.  On entry p0 holds its first word pair, fa[0] its K-step 0
     // weight fragments and fb[0], fb[1] its first two input fragments; on exit
-    // the same holds for the next chunk.  nbuf = stage buffer of chunk c+1.
-    auto chunk_body = [&](int nbuf) {
+    // the same holds for the next chunk.  b1/b2 = stages of chunk c+1, c+2.
+    auto chunk_body = [&](int b1, int b2) {
         static_for<4 * NS>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             constexpr int ks = i / NS, sl = i % NS;   // K-step, slot within it
@@ -336,61 +388,76 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
             static_for<(sl + 1) * 8 / NS - sl * 8 / NS>([&](auto jc) {
                 constexpr int idx = sl * 8 / NS + decltype(jc)::value;
                 constexpr int f = idx >> 2, jj = idx & 3;
-                fa[(ks + 1) & 1][f][jj] = expand_w(word_of(f, (ks + 1) & 3), jj);
+                if constexpr (ks < 3) fa[(ks + 1) & 1][f][jj] = expand_w(word_of(f, ks + 1), jj);
+                else fa[0][f][jj] = expand_w(pwn[f].x, jj);
             });
             // side work, spread over the slots of its K-step
-            if constexpr (ks == 0) {
-                constexpr int NP = 1 + NB + NF;               // commits, then reads of pair 1
-                static_for<NP>([&](auto pc) {
-                    constexpr int pidx = decltype(pc)::value;
-                    if constexpr (pidx * NS / NP == sl) {
-                        if constexpr (pidx <= NB) commit_piece(nbuf, pidx);
-                        else read_pair(p1, nbuf ^ 1, 1, pidx - 1 - NB);
-                    }
-                });
-                if constexpr (sl == NS - 1) __syncthreads();
+            if constexpr (ks == 1 && sl == NS - 1) {
+                // outstanding: this wave's loads of chunks c+1 and c+2, NL each, in order
+                asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NL) : "memory");   // chunk c+1 has landed
+                __syncthreads();
             }
-            if constexpr (ks == 1 && sl <= NB) fetch_piece(sl);
-            if constexpr (ks == 2 && sl < NF) read_pair(p0, nbuf, 0, sl);
-            if constexpr (ks == 3 && sl < 2) advance();       // on to the unit of the next fetch
+            // chunk c+1's words: weights early in K-step 2 (into the spare
+            // set), input block pb in K-step 3 right after the block's last use
+            if constexpr (ks == 2 && sl < CB) read_unit(pwn[sl], b1, sl);
+            if constexpr (ks == 3 && cb == 1) read_unit(pw[CB + pb], b1, CB + pb);
+            if constexpr (ks == 0 && sl == 0) fetch_begin();
+            if constexpr (ks == 0 && sl < NL) fetch_piece(b2, sl);       // chunk c+2
+            if constexpr (ks == 0 && sl == NL) advance();                // on to the units of the next fetch
+            if constexpr (ks == 3 && sl >= NS - CB) count_unit(pwn[sl - (NS - CB)], sl - (NS - CB));
             __builtin_amdgcn_sched_barrier(0);
         });
+#pragma unroll
+        for (int f = 0; f < CB; ++f) pw[f] = pwn[f];
     };
 
 #pragma unroll
-    for (int j = 0; j <= NB; ++j) fetch_piece(j);
+    for (int c = 0; c < 2; ++c) {                        // chunks 0, 1 -> stages 0, 1
+        fetch_begin();
 #pragma unroll
-    for (int j = 0; j <= NB; ++j) commit_piece(0, j);
-    advance(); advance();
-#pragma unroll
-    for (int j = 0; j <= NB; ++j) fetch_piece(j);   // chunk 1, committed during chunk 0
-    advance(); advance();
+        for (int i = 0; i < NL; ++i) fetch_piece(c, i);
+        advance();
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NL) : "memory");   // chunk 0 has landed
     __syncthreads();
 #pragma unroll
-    for (int f = 0; f < NF; ++f) read_pair(p0, 0, 0, f);
+    for (int f = 0; f < NF; ++f) read_unit(pw[f], 0, f);
 #pragma unroll
-    for (int f = 0; f < CB; ++f)
+    for (int f = 0; f < CB; ++f) {
+        count_unit(pw[f], f);
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) fa[0][f][jj] = expand_w(p0[f].x, jj);
+        for (int jj = 0; jj < 4; ++jj) fa[0][f][jj] = expand_w(pw[f].x, jj);
+    }
 #pragma unroll
     for (int q = 0; q < 2; ++q)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) fb[q][jj] = expand_x(p0[CB + q].x, jj);
+        for (int jj = 0; jj < 4; ++jj) fb[q][jj] = expand_x(pw[CB + q].x, jj);
 
-    for (int chunk = 0; chunk < a.n_chunks; ++chunk) chunk_body((chunk + 1) & 1);
+    {
+        int b0 = 0, b1 = 1, b2 = 2;
+        for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+            chunk_body(b1, b2);
+            const int tmp = b0; b0 = b1; b1 = b2; b2 = tmp;
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the loads of the chunks past the end
 
     // ---- epilogue
     // The accumulator holds  sum + Z - 192*n_chunks + 2*pop(channel)  (Z:
     // positions that are zero on both sides and count +1, see the launcher;
     // pop: the channel's set weight bits at positions 4i+0..2, see the
-    // header).  The two threads that streamed a weight row add their counts
-    // and the workgroup exchanges them through LDS indexed by channel.  What
+    // header).  The two lanes that read a weight row's K-halves add their
+    // counts and the workgroup exchanges them through LDS indexed by channel.  What
     // has to be subtracted per channel (plus the threshold, minus 0.5 so that
     // the result is never zero, in the fused case) is kept in sub[][].
     float sub[CB][16];
     {
-        const int both = wpop + __shfl_xor(wpop, 1, 64);
-        if (half == 0) wpop_lds[32 * (lrow >> 5) + row_to_channel(lrow & 31)] = both;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            // lanes l and l^32 read the two K-halves of the same weight row
+            const int both = wpop[cb] + __shfl_xor(wpop[cb], 32, 64);
+            if (hsel == 0) wpop_lds[64 * wc + 32 * cb + row_to_channel(j)] = both;
+        }
         __syncthreads();
         const int base = a.z - 192 * a.n_chunks;
 #pragma unroll
@@ -411,7 +478,6 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
                 }
             }
     }
-    const int j = lane & 31;
     if constexpr (FUSED) {
         // bit = (y >= thr)  <=>  acc - sub = y - thr + 0.5 > 0  <=>  sign bit clear
         uint32_t* yp = static_cast<uint32_t*>(out);
@@ -477,7 +543,10 @@ hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int
     constexpr int WG_PX = 64 * PB;
     a.n_ptiles = (a.s.m + WG_PX - 1) / WG_PX;
     const unsigned blocks = (unsigned)(a.n_ptiles * a.n_ctiles);
-    hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, FUSED>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out);
+    if (a.units_per_tap % 2 == 0)
+        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, FUSED, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out);
+    else
+        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, FUSED, false>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out);
     return hipGetLastError();
 }
 
