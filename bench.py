@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma_i8", "mfma_fp4"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma_i8", "mfma_fp4", "mfma_fp4_t4", "mfma_fp4_t7"])
     ap.add_argument("--shapes", default="1,2,3,4,5",
                     help="comma list of layer shapes in the step (default all five; a subset is for profiling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -58,7 +58,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
     variant = {"auto": B.BCNN_VARIANT_AUTO, "valu": B.BCNN_VARIANT_VALU,
-               "mfma_i8": B.BCNN_VARIANT_MFMA_I8, "mfma_fp4": B.BCNN_VARIANT_MFMA_FP4}[args.variant]
+               "mfma_i8": B.BCNN_VARIANT_MFMA_I8, "mfma_fp4": B.BCNN_VARIANT_MFMA_FP4,
+               "mfma_fp4_t4": B.BCNN_VARIANT_MFMA_FP4_T4, "mfma_fp4_t7": B.BCNN_VARIANT_MFMA_FP4_T7}[args.variant]
 
     # ---------------------------------------------------------------- inputs
     work = []
@@ -155,7 +156,7 @@ def main():
     dom_ms = dom["conv_ms"] / args.steps / dom["cfg"].layers
     dom_bops = W.binary_ops(dom["cfg"]) / dom["cfg"].layers
     achieved = dom_bops / (dom_ms * 1e-3) / 1e12
-    on_mfma = args.variant in ("auto", "mfma_fp4")
+    on_mfma = args.variant in ("auto", "mfma_fp4", "mfma_fp4_t4", "mfma_fp4_t7")
     if on_mfma:
         # fp4 matrix-core path: one binary multiply-accumulate is one fp4 FMA = 2 FLOP
         roofline = {

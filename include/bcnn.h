@@ -60,7 +60,9 @@ typedef enum {
     BCNN_VARIANT_AUTO = 0,
     BCNN_VARIANT_VALU = 1,     /* xor + popcount on the vector ALUs */
     BCNN_VARIANT_MFMA_I8 = 2,  /* +-1 expanded to int8, matrix cores */
-    BCNN_VARIANT_MFMA_FP4 = 3  /* +-1 expanded to 4-bit floats, matrix cores */
+    BCNN_VARIANT_MFMA_FP4 = 3, /* +-1 expanded to 4-bit floats, matrix cores; tile chosen by shape */
+    BCNN_VARIANT_MFMA_FP4_T4 = 4, /* the same with 2 x 4 blocks of 32 x 32 per wave forced */
+    BCNN_VARIANT_MFMA_FP4_T7 = 5  /* the same with 2 x 7 blocks forced (fused output only) */
 } bcnn_variant;
 
 typedef struct {

@@ -20,6 +20,7 @@ BCNN_ERR_DEVICE = -4
 
 BCNN_F32, BCNN_F16, BCNN_I8 = 0, 1, 2
 BCNN_VARIANT_AUTO, BCNN_VARIANT_VALU, BCNN_VARIANT_MFMA_I8, BCNN_VARIANT_MFMA_FP4 = 0, 1, 2, 3
+BCNN_VARIANT_MFMA_FP4_T4, BCNN_VARIANT_MFMA_FP4_T7 = 4, 5
 
 EXPORTS = (
     "bcnn_pack", "bcnn_conv2d_binary", "bcnn_conv2d_binary_sign_pack",

@@ -90,7 +90,7 @@ int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w,
             // The matrix-core path wins wherever its 128 x 256 tiles are
             // reasonably full; small or ragged problems stay on the vector ALUs.
             if (conv_mfma_fp4_supported(s, x, w) && s.c_out >= 64 && s.m >= 1024)
-                e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, st);
+                e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, 0, st);
             else
                 e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, st);
             break;
@@ -98,8 +98,12 @@ int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w,
             e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, st);
             break;
         case BCNN_VARIANT_MFMA_FP4:
+        case BCNN_VARIANT_MFMA_FP4_T4:
+        case BCNN_VARIANT_MFMA_FP4_T7:
             if (!conv_mfma_fp4_supported(s, x, w)) return BCNN_ERR_UNSUPPORTED;
-            e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, st);
+            if (variant == BCNN_VARIANT_MFMA_FP4_T7 && !fused) return BCNN_ERR_UNSUPPORTED;
+            e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out,
+                                     variant == BCNN_VARIANT_MFMA_FP4_T7 ? 7 : variant == BCNN_VARIANT_MFMA_FP4_T4 ? 4 : 0, st);
             break;
         case BCNN_VARIANT_MFMA_I8:
             return BCNN_ERR_UNSUPPORTED;

@@ -29,8 +29,9 @@ hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_
                             const int32_t* thr, void* out, hipStream_t stream);
 // fp4 matrix-core variant; `supported` says whether it covers the shape/alignment.
 bool conv_mfma_fp4_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
+// tile: pixel blocks per wave, 4 or 7 (7 exists for the fused kernel only), 0 = choose
 hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
-                                const int32_t* thr, void* out, hipStream_t stream);
+                                const int32_t* thr, void* out, int tile, hipStream_t stream);
 hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
 
 }  // namespace bcnn

@@ -97,11 +97,6 @@ __device__ __forceinline__ Fp4Masks fp4_masks()
     return k;
 }
 
-__device__ __forceinline__ uint32_t pick(const uint4& q, int i)
-{
-    return i == 0 ? q.x : i == 1 ? q.y : i == 2 ? q.z : q.w;
-}
-
 struct MfmaArgs {
     ConvShape s;
     int32_t n_ptiles, n_ctiles;
@@ -577,7 +572,7 @@ static double tile_cost(const ConvShape& s, int pb)
 }
 
 hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
-                                const int32_t* thr, void* out, hipStream_t stream)
+                                const int32_t* thr, void* out, int tile, hipStream_t stream)
 {
     MfmaArgs a;
     a.s = s;
@@ -591,11 +586,16 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     a.w_bytes = (int32_t)((int64_t)s.c_out * a.n_units * 16);
     // Feature maps of 7, 14, 28, 56 pixels a side make the pixel count a
     // multiple of 49: 7 pixel blocks per wave then tile it without remainder
-    // where 4 would leave a quarter of the last round idle.
-    // (Only the fused kernel has the registers for it: the int32 epilogue of
-    // a 2 x 7 tile would spill.)
+    // where 4 would leave a quarter of the last round idle.  The 2 x 7 tile
+    // runs one workgroup per CU, so nothing hides its prologue and epilogue;
+    // it pays off only for long K loops (measured: 36 chunks yes, 9 chunks no,
+    // where two co-resident 2 x 4 workgroups per CU overlap each other's
+    // ends).  Only the fused kernel has the registers for it: the int32
+    // epilogue of a 2 x 7 tile would spill.
+    // `tile` = 4 or 7 forces a tile (for tests and measurements), 0 chooses.
     if (!thr) return launch_pb<4, false>(a, x, w, thr, out, stream);
-    if (tile_cost(s, 7) < tile_cost(s, 4)) return launch_pb<7, true>(a, x, w, thr, out, stream);
+    if (tile == 7 || (tile == 0 && a.n_chunks >= 20 && tile_cost(s, 7) < tile_cost(s, 4)))
+        return launch_pb<7, true>(a, x, w, thr, out, stream);
     return launch_pb<4, true>(a, x, w, thr, out, stream);
 }
 

@@ -15,21 +15,23 @@ __device__ __forceinline__ bool nonneg(_Float16 v) { return (float)v >= 0.0f; }
 __device__ __forceinline__ bool nonneg(int8_t v) { return v >= 0; }
 
 // ---- [outer][C][inner] with inner >= 64: lanes run along `inner` ------------
-// One thread owns one inner position and builds all Cw words of that pixel.
-// For a fixed channel the 256 threads of a block read 256 consecutive
+// One thread owns one inner position and builds `cwg` consecutive words of that
+// pixel.  For a fixed channel the 256 threads of a block read 256 consecutive
 // elements; the 32 channel reads of a word are independent and all in flight.
-// The block's output is a contiguous run of 256*Cw words, staged through LDS
-// so that the stores are contiguous too.
+// The block's words are staged through LDS so that each pixel's words leave
+// in one contiguous run.  The channel words are split over blocks (cwg per
+// block) until the launch has enough blocks to fill the chip.
 constexpr int PACK_THREADS = 256;
-constexpr int PACK_CW_CHUNK = 8;  // words staged per pass: 256*8*4 B = 8 KB LDS
+constexpr int PACK_CW_CHUNK = 8;  // most words per block: 256*8*4 B = 8 KB LDS
 
 template <typename T>
 __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
-    const T* __restrict__ src, int64_t channels, int64_t inner, int64_t cw_total,
-    uint32_t* __restrict__ dst)
+    const T* __restrict__ src, int64_t channels, int64_t inner, int64_t cw_total, int cwg,
+    int groups, uint32_t* __restrict__ dst)
 {
     __shared__ uint32_t stage[PACK_THREADS * PACK_CW_CHUNK];
-    const int64_t a = blockIdx.y;
+    const int64_t a = blockIdx.y / groups;
+    const int64_t j0 = (int64_t)(blockIdx.y % groups) * cwg;
     const int64_t i0 = (int64_t)blockIdx.x * PACK_THREADS;
     const int tid = threadIdx.x;
     const int64_t i = i0 + tid;
@@ -37,33 +39,80 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
     const int64_t icl = live ? i : inner - 1;
     const T* col = src + a * channels * inner + icl;
     const int rows_here = (int)((inner - i0 < PACK_THREADS) ? (inner - i0) : PACK_THREADS);
+    const int jn = (int)((cw_total - j0 < cwg) ? (cw_total - j0) : cwg);
 
-    for (int64_t j0 = 0; j0 < cw_total; j0 += PACK_CW_CHUNK) {
-        const int jn = (int)((cw_total - j0 < PACK_CW_CHUNK) ? (cw_total - j0) : PACK_CW_CHUNK);
-        for (int j = 0; j < jn; ++j) {
-            const int64_t c0 = (j0 + j) * 32;
-            uint32_t word = 0;
-            if (c0 + 32 <= channels) {
-                T v[32];
+    for (int j = 0; j < jn; ++j) {
+        const int64_t c0 = (j0 + j) * 32;
+        uint32_t word = 0;
+        if (c0 + 32 <= channels) {
+            T v[32];
 #pragma unroll
-                for (int b = 0; b < 32; ++b) v[b] = __builtin_nontemporal_load(col + (c0 + b) * inner);
+            for (int b = 0; b < 32; ++b) v[b] = __builtin_nontemporal_load(col + (c0 + b) * inner);
 #pragma unroll
-                for (int b = 0; b < 32; ++b) word |= (uint32_t)nonneg(v[b]) << b;
-            } else {
-                for (int b = 0; c0 + b < channels; ++b)
-                    word |= (uint32_t)nonneg(col[(c0 + b) * inner]) << b;
+            for (int b = 0; b < 32; ++b) word |= (uint32_t)nonneg(v[b]) << b;
+        } else {
+            for (int b = 0; c0 + b < channels; ++b)
+                word |= (uint32_t)nonneg(col[(c0 + b) * inner]) << b;
+        }
+        stage[tid * jn + j] = word;
+    }
+    __syncthreads();
+    // rows_here*jn words: word t of the stage belongs to pixel t/jn, word t%jn of the group
+    const int total = rows_here * jn;
+    for (int t = tid; t < total; t += PACK_THREADS) {
+        const int r = t / jn, j = t - r * jn;
+        dst[(a * inner + i0 + r) * cw_total + j0 + j] = stage[t];
+    }
+}
+
+// ---- 1 < inner < 64 (7x7 feature maps, 3x3 filter taps): 2D thread tile ------
+// IP = inner rounded up to a power of two; thread (i = t % IP, q = t / IP)
+// reads element i of channel rows q, q+R, q+2R, ... (R = 256/IP rows per pass:
+// consecutive rows are contiguous in memory, so a pass reads R*inner
+// consecutive elements).  A thread ORs its rows' sign bits into partial words,
+// the R partials of a pixel meet in LDS.  A block packs up to 8 words (256
+// channels) of one `outer` index.
+template <typename T, int IP>
+__global__ __launch_bounds__(256) void pack_small_inner_kernel(
+    const T* __restrict__ src, int64_t channels, int inner, int64_t cw_total, int groups,
+    uint32_t* __restrict__ dst)
+{
+    constexpr int R = 256 / IP;          // channel rows per pass
+    constexpr int PASSES = 32 / R;       // passes per output word (R divides 32 as IP >= 8)
+    constexpr int G = 8;                 // words per block
+    __shared__ uint32_t part[G][R][IP];
+    const int64_t a = blockIdx.x / groups;
+    const int64_t j0 = (int64_t)(blockIdx.x % groups) * G;
+    const int i = threadIdx.x % IP, q = threadIdx.x / IP;
+    const bool live = i < inner;
+    const T* base = src + a * channels * inner + (live ? i : 0);
+    const int jn = (int)((cw_total - j0 < G) ? (cw_total - j0) : G);
+    for (int j = 0; j < jn; ++j) {
+        const int64_t c0 = (j0 + j) * 32;
+        uint32_t word = 0;
+        if (c0 + 32 <= channels) {
+            T v[PASSES];
+#pragma unroll
+            for (int k = 0; k < PASSES; ++k)
+                v[k] = __builtin_nontemporal_load(base + (c0 + q + R * k) * inner);
+#pragma unroll
+            for (int k = 0; k < PASSES; ++k) word |= (uint32_t)nonneg(v[k]) << (q + R * k);
+        } else {
+            for (int k = 0; k < PASSES; ++k) {
+                const int64_t c = c0 + q + R * k;
+                if (c < channels) word |= (uint32_t)nonneg(base[c * inner]) << (q + R * k);
             }
-            stage[tid * jn + j] = word;
         }
-        __syncthreads();
-        // rows_here*jn words, contiguous per pixel only within the chunk:
-        // word t of the stage belongs to pixel t/jn, chunk word t%jn.
-        const int total = rows_here * jn;
-        for (int t = tid; t < total; t += PACK_THREADS) {
-            const int r = t / jn, j = t - r * jn;
-            dst[(a * inner + i0 + r) * cw_total + j0 + j] = stage[t];
-        }
-        __syncthreads();
+        part[j][q][i] = live ? word : 0u;
+    }
+    __syncthreads();
+    // thread t -> (pixel t / jn, word t % jn): each pixel's words leave together
+    for (int t = threadIdx.x; t < inner * jn; t += 256) {
+        const int px = t / jn, j = t - px * jn;
+        uint32_t word = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) word |= part[j][r][px];
+        dst[(a * inner + px) * cw_total + j0 + j] = word;
     }
 }
 
@@ -129,11 +178,33 @@ hipError_t pack_dispatch(const T* src, int64_t outer, int64_t channels, int64_t 
         const int64_t blocks = (waves + 3) / 4;
         hipLaunchKernelGGL((pack_rows_kernel<T, ROWS>), dim3((unsigned)blocks), dim3(256), 0, stream,
                            src, outer, channels, cw, dst);
-    } else if (inner >= 64 && outer <= 65535) {
+    } else if (inner >= 64) {
         const int64_t bx = (inner + PACK_THREADS - 1) / PACK_THREADS;
-        hipLaunchKernelGGL((pack_columns_kernel<T>), dim3((unsigned)bx, (unsigned)outer),
-                           dim3(PACK_THREADS), 0, stream, src, channels, inner, cw, dst);
+        // words per block: as many as possible (up to 8) while two blocks per CU remain
+        int cwg = PACK_CW_CHUNK;
+        while (cwg > 1 && bx * outer * ((cw + cwg - 1) / cwg) < 512) cwg >>= 1;
+        const int64_t groups = (cw + cwg - 1) / cwg;
+        if (outer * groups > 65535) goto generic;
+        hipLaunchKernelGGL((pack_columns_kernel<T>), dim3((unsigned)bx, (unsigned)(outer * groups)),
+                           dim3(PACK_THREADS), 0, stream, src, channels, inner, cw, cwg, (int)groups, dst);
+    } else if (inner >= 5) {
+        const int64_t groups = (cw + 7) / 8;
+        const int64_t blocks = outer * groups;
+        if (blocks > 0x7FFFFFFF) goto generic;
+        if (inner > 32)
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 64>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, channels, (int)inner, cw, (int)groups, dst);
+        else if (inner > 16)
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 32>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, channels, (int)inner, cw, (int)groups, dst);
+        else if (inner > 8)
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 16>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, channels, (int)inner, cw, (int)groups, dst);
+        else
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 8>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, channels, (int)inner, cw, (int)groups, dst);
     } else {
+    generic:
         const int64_t total = outer * inner * cw;
         const int64_t blocks = (total + 255) / 256;
         hipLaunchKernelGGL((pack_generic_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, stream,
