@@ -501,30 +501,49 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
             }
         }
     } else {
+        // int32 sums.  In registers a lane holds 16 consecutive channels of one
+        // pixel, i.e. 64-byte pieces 1 KB apart: poor store granularity.  Each
+        // wave therefore transposes its 32 pixels x 64 channels of a pixel
+        // block through its own 8.5 KB of LDS (the stages are free now) and
+        // writes 256 contiguous bytes per pixel, four pixels per instruction.
         int32_t* y = static_cast<int32_t*>(out);
+        constexpr int ROW_WORDS = 64 + 4;                      // padded row: 64 channels
+        static_assert(4 * 32 * ROW_WORDS * 4 <= 3 * STAGE_BYTES, "transpose tiles must fit the stages");
+        __syncthreads();                                       // every wave is done with the stages
+        int32_t* tile = reinterpret_cast<int32_t*>(stage) + wave * (32 * ROW_WORDS);
         const bool vec_ok = (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0);
+        const int cgrp = lane & 15;                            // 4-channel group within the wave's 64
+        const int prow = lane >> 4;                            // pixel row within a group of four
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
-            const int m = m0 + 32 * (PB * wp + pb) + j;
-            if (m >= s.m) continue;
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                const int c0 = o0 + 64 * wc + 32 * cb + 16 * hsel;
-                int32_t* row = y + (size_t)m * s.c_out + c0;
-                if (vec_ok && c0 + 16 <= s.c_out) {
+            for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                    for (int r = 0; r < 16; r += 4) {
-                        int4 q;
-                        q.x = (int)(acc[cb][pb][r + 0] - sub[cb][r + 0]);
-                        q.y = (int)(acc[cb][pb][r + 1] - sub[cb][r + 1]);
-                        q.z = (int)(acc[cb][pb][r + 2] - sub[cb][r + 2]);
-                        q.w = (int)(acc[cb][pb][r + 3] - sub[cb][r + 3]);
-                        *reinterpret_cast<int4*>(row + r) = q;
+                for (int r = 0; r < 16; r += 4) {
+                    int4 q;
+                    q.x = (int)(acc[cb][pb][r + 0] - sub[cb][r + 0]);
+                    q.y = (int)(acc[cb][pb][r + 1] - sub[cb][r + 1]);
+                    q.z = (int)(acc[cb][pb][r + 2] - sub[cb][r + 2]);
+                    q.w = (int)(acc[cb][pb][r + 3] - sub[cb][r + 3]);
+                    *reinterpret_cast<int4*>(tile + j * ROW_WORDS + 32 * cb + 16 * hsel + r) = q;
+                }
+            // same wave wrote and reads: LDS operations of a wave complete in order
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const int px = 4 * g + prow;
+                const int4 q = *reinterpret_cast<const int4*>(tile + px * ROW_WORDS + 4 * cgrp);
+                const int m = m0 + 32 * (PB * wp + pb) + px;
+                const int c0 = o0 + 64 * wc + 4 * cgrp;
+                if (m < s.m) {
+                    int32_t* dstp = y + (size_t)m * s.c_out + c0;
+                    if (vec_ok && c0 + 4 <= s.c_out) {
+                        *reinterpret_cast<int4*>(dstp) = q;
+                    } else {
+                        if (c0 + 0 < s.c_out) dstp[0] = q.x;
+                        if (c0 + 1 < s.c_out) dstp[1] = q.y;
+                        if (c0 + 2 < s.c_out) dstp[2] = q.z;
+                        if (c0 + 3 < s.c_out) dstp[3] = q.w;
                     }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (c0 + r < s.c_out) row[r] = (int)(acc[cb][pb][r] - sub[cb][r]);
                 }
             }
         }
