@@ -163,7 +163,10 @@ def main():
             "kernel": "conv_mfma_fp4_kernel on " + dom["cfg"].name + " (per launch)",
             "bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_FP4_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
-            "avg_launch_ms": round(dom_ms, 4), "traffic": None,
+            "avg_launch_ms": round(dom_ms, 4),
+            # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
+            # profiles/bench_hbm_traffic_pmc.md (shape 5, 2x7 tile); not re-measured by this script
+            "traffic": 13.2e6 if dom["cfg"].name.startswith("cfg5") else None,
         }
     else:
         roofline = {
