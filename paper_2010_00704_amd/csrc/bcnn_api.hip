@@ -106,7 +106,9 @@ int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w,
                                      variant == BCNN_VARIANT_MFMA_FP4_T7 ? 7 : variant == BCNN_VARIANT_MFMA_FP4_T4 ? 4 : 0, st);
             break;
         case BCNN_VARIANT_MFMA_I8:
-            return BCNN_ERR_UNSUPPORTED;
+            if (!conv_mfma_i8_supported(s, x, w)) return BCNN_ERR_UNSUPPORTED;
+            e = launch_conv_mfma_i8(s, x, w, fused ? thr : nullptr, out, st);
+            break;
         default:
             return BCNN_ERR_INVALID_ARG;
     }

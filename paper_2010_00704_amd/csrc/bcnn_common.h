@@ -32,6 +32,10 @@ bool conv_mfma_fp4_supported(const ConvShape& s, const uint32_t* x, const uint32
 // tile: pixel blocks per wave, 4 or 7 (7 exists for the fused kernel only), 0 = choose
 hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                                 const int32_t* thr, void* out, int tile, hipStream_t stream);
+// int8 matrix-core variant (measurement arm, never chosen by AUTO)
+bool conv_mfma_i8_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
+hipError_t launch_conv_mfma_i8(const ConvShape& s, const uint32_t* x, const uint32_t* w,
+                               const int32_t* thr, void* out, hipStream_t stream);
 hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
 
 }  // namespace bcnn

@@ -18,8 +18,9 @@ pytestmark = pytest.mark.gpu
 
 GUARD = 64              # words on each side of every output
 SENTINEL = 0x5A5A5A5A
-VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4_T4, B.BCNN_VARIANT_MFMA_FP4_T7]
-VARIANT_IDS = ["auto", "valu", "mfma_fp4_t4", "mfma_fp4_t7"]
+VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4_T4, B.BCNN_VARIANT_MFMA_FP4_T7,
+            B.BCNN_VARIANT_MFMA_I8]
+VARIANT_IDS = ["auto", "valu", "mfma_fp4_t4", "mfma_fp4_t7", "mfma_i8"]
 
 
 def run_variant(rc, what):
