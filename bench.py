@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma_i8", "mfma_fp4", "mfma_fp4_t4", "mfma_fp4_t7"])
     ap.add_argument("--shapes", default="1,2,3,4,5",
                     help="comma list of layer shapes in the step (default all five; a subset is for profiling)")
+    ap.add_argument("--eager", action="store_true", help="time eagerly enqueued steps instead of graph replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-aux", action="store_true", help="skip the stand-alone kernel measurements")
     return ap.parse_args()
@@ -112,10 +113,52 @@ def main():
     torch.cuda.synchronize()
 
     # ------------------------------------------------------------ timed region
-    # K steps enqueued back to back between two synchronisations; the wall
-    # clock around them is the step time.  Events (on torch's current stream,
-    # which is the stream every kernel is launched on) split each step into
-    # its pack and convolution parts; they are read after the region ends.
+    # The 13 launches of a step are short (3-55 us each), so the step is
+    # captured once into a HIP graph and the timed region is K replays of it
+    # between two synchronisations, timed by the wall clock.  (--eager times K
+    # eagerly enqueued steps instead.)  The graph holds kernel nodes only.
+    # Its results are checked against the eager results before timing.
+    launch = "eager"
+    graph = None
+    if not args.eager:
+        try:
+            ref = [wk["outs"][-1].clone() for wk in work]
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step(False)                      # warm the capture stream
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step(False)
+            for _ in range(3):                   # replays with eager work and syncs in between
+                for wk in work:
+                    wk["outs"][-1].zero_()
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                for wk, r in zip(work, ref):
+                    assert torch.equal(wk["outs"][-1], r), "graph replay differs from the eager result"
+            launch = "hip_graph"
+        except Exception as e:  # capture unavailable: time the eager path and say so
+            sys.stderr.write("bench.py: graph capture failed (%s); timing eager launches\n" % (e,))
+            graph = None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if graph is not None:
+        for k in range(args.steps):
+            graph.replay()
+    else:
+        for k in range(args.steps):
+            step(False)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # Per-part breakdown and the dominant kernel's launch duration: the same K
+    # steps again, enqueued eagerly with HIP events (on torch's current stream,
+    # which is the stream every kernel is launched on) around the pack and the
+    # convolution part of every shape; read after the region ends.
     evs = [[[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in work]
            for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -125,7 +168,7 @@ def main():
             wk["ev"] = ev
         step(True)
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step_evented = (time.perf_counter() - t0) * 1e3 / args.steps
     for k in range(args.steps):
         for wk, ev in zip(work, evs[k]):
             wk["pack_ms"] += ev[0].elapsed_time(ev[1])
@@ -195,6 +238,7 @@ def main():
                    if shapes == [1, 2, 3, 4, 5] else "SUBSET of the layer shapes (profiling run): %s" % shapes,
                    "variant": args.variant},
         "frac_valu_peak": round(value / VALU_PEAK_TBOPS, 4),
+        "launch": launch, "ms_per_step_eager_with_events": round(ms_per_step_evented, 4),
         "per_config": per_config,
         "roofline": roofline,
         "aux": aux,
