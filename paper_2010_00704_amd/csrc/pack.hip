@@ -6,6 +6,8 @@
 // with many of them in flight.
 #include "bcnn_common.h"
 
+#include <type_traits>
+
 
 namespace bcnn {
 namespace {
@@ -58,6 +60,68 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
     }
     __syncthreads();
     // rows_here*jn words: word t of the stage belongs to pixel t/jn, word t%jn of the group
+    const int total = rows_here * jn;
+    for (int t = tid; t < total; t += PACK_THREADS) {
+        const int r = t / jn, j = t - r * jn;
+        dst[(a * inner + i0 + r) * cw_total + j0 + j] = stage[t];
+    }
+}
+
+// ---- fp32, inner a multiple of 4: the same with four pixels per thread ------
+// 16-byte non-temporal loads (four consecutive pixels of one channel); the 32
+// channel loads of a word are issued in two batches of 16.  This is the form
+// that gets closest to the chip's read bandwidth.
+__global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
+    const float* __restrict__ src, int64_t channels, int64_t inner, int64_t cw_total, int cwg,
+    int groups, uint32_t* __restrict__ dst)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ uint32_t stage[PACK_THREADS * 4 * PACK_CW_CHUNK];
+    const int64_t a = blockIdx.y / groups;
+    const int64_t j0 = (int64_t)(blockIdx.y % groups) * cwg;
+    const int64_t i0 = (int64_t)blockIdx.x * (PACK_THREADS * 4);
+    const int tid = threadIdx.x;
+    const int64_t i = i0 + 4 * tid;
+    const bool live = i < inner;                       // inner % 4 == 0: all four pixels or none
+    const int64_t icl = live ? i : inner - 4;
+    const float* col = src + a * channels * inner + icl;
+    const int64_t rest = inner - i0;
+    const int rows_here = (int)(rest < PACK_THREADS * 4 ? rest : PACK_THREADS * 4);
+    const int jn = (int)((cw_total - j0 < cwg) ? (cw_total - j0) : cwg);
+
+    for (int j = 0; j < jn; ++j) {
+        const int64_t c0 = (j0 + j) * 32;
+        uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+        if (c0 + 32 <= channels) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                f4 v[16];
+#pragma unroll
+                for (int b = 0; b < 16; ++b)
+                    v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(col + (c0 + 16 * half + b) * inner));
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {
+                    w0 |= (uint32_t)nonneg(v[b][0]) << (16 * half + b);
+                    w1 |= (uint32_t)nonneg(v[b][1]) << (16 * half + b);
+                    w2 |= (uint32_t)nonneg(v[b][2]) << (16 * half + b);
+                    w3 |= (uint32_t)nonneg(v[b][3]) << (16 * half + b);
+                }
+            }
+        } else {
+            for (int b = 0; c0 + b < channels; ++b) {
+                const f4 v = *reinterpret_cast<const f4*>(col + (c0 + b) * inner);
+                w0 |= (uint32_t)nonneg(v[0]) << b;
+                w1 |= (uint32_t)nonneg(v[1]) << b;
+                w2 |= (uint32_t)nonneg(v[2]) << b;
+                w3 |= (uint32_t)nonneg(v[3]) << b;
+            }
+        }
+        stage[(4 * tid + 0) * jn + j] = w0;
+        stage[(4 * tid + 1) * jn + j] = w1;
+        stage[(4 * tid + 2) * jn + j] = w2;
+        stage[(4 * tid + 3) * jn + j] = w3;
+    }
+    __syncthreads();
     const int total = rows_here * jn;
     for (int t = tid; t < total; t += PACK_THREADS) {
         const int r = t / jn, j = t - r * jn;
@@ -178,6 +242,16 @@ hipError_t pack_dispatch(const T* src, int64_t outer, int64_t channels, int64_t 
         const int64_t blocks = (waves + 3) / 4;
         hipLaunchKernelGGL((pack_rows_kernel<T, ROWS>), dim3((unsigned)blocks), dim3(256), 0, stream,
                            src, outer, channels, cw, dst);
+    } else if (std::is_same<T, float>::value && inner >= 256 && inner % 4 == 0 &&
+               (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+        const int64_t bx = (inner + PACK_THREADS * 4 - 1) / (PACK_THREADS * 4);
+        int cwg = PACK_CW_CHUNK;
+        while (cwg > 1 && bx * outer * ((cw + cwg - 1) / cwg) < 512) cwg >>= 1;
+        const int64_t groups = (cw + cwg - 1) / cwg;
+        if (outer * groups > 65535) goto generic;
+        hipLaunchKernelGGL(pack_columns4_kernel, dim3((unsigned)bx, (unsigned)(outer * groups)),
+                           dim3(PACK_THREADS), 0, stream, reinterpret_cast<const float*>(src), channels,
+                           inner, cw, cwg, (int)groups, dst);
     } else if (inner >= 64) {
         const int64_t bx = (inner + PACK_THREADS - 1) / PACK_THREADS;
         // words per block: as many as possible (up to 8) while two blocks per CU remain
@@ -243,6 +317,50 @@ __global__ __launch_bounds__(256) void threshold_sign_pack_kernel(
     }
 }
 
+// The same for c_out a multiple of 32 and 16-byte aligned sums: the tensor is
+// a flat stream of 16-byte units (4 channels of one row), a lane takes UNROLL
+// units per round with non-temporal 16-byte loads, eight neighbouring lanes
+// hold the 32 channels of one output word and combine their nibbles with three
+// DPP exchanges.
+template <int UNROLL>
+__global__ __launch_bounds__(256) void threshold_sign_pack4_kernel(
+    const int32_t* __restrict__ y, const int32_t* __restrict__ thr, int64_t units, int c_out,
+    uint32_t* __restrict__ yp)
+{
+    typedef int i4 __attribute__((ext_vector_type(4)));
+    const int lane8 = threadIdx.x & 7;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    // channel of this lane's unit, kept up to date by adding the stride modulo c_out
+    int c = (int)((u * 4) % c_out);
+    const int cstep = (int)((stride * 4) % c_out);
+    for (; u < units; u += stride * UNROLL) {
+        i4 v[UNROLL], t[UNROLL];
+        int cc = c;
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const int64_t uk = u + stride * k;
+            const bool ok = uk < units;
+            v[k] = ok ? __builtin_nontemporal_load(reinterpret_cast<const i4*>(y) + uk) : i4{0, 0, 0, 0};
+            t[k] = *reinterpret_cast<const i4*>(thr + cc);
+            cc += cstep; cc -= cc >= c_out ? c_out : 0;
+        }
+        c = cc;
+#pragma unroll
+        for (int k = 0; k < UNROLL; ++k) {
+            const int64_t uk = u + stride * k;
+            uint32_t w = ((uint32_t)(v[k][0] >= t[k][0]) | ((uint32_t)(v[k][1] >= t[k][1]) << 1) |
+                          ((uint32_t)(v[k][2] >= t[k][2]) << 2) | ((uint32_t)(v[k][3] >= t[k][3]) << 3))
+                         << (4 * lane8);
+            // OR over the 8 lanes of the word: neighbours, pairs, then the other quad
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, true);  // row_half_mirror
+            if (lane8 == 0 && uk < units) yp[uk >> 3] = w;
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void diag_copy_kernel(const uint32_t* __restrict__ src,
                                                        uint32_t* __restrict__ dst, int64_t words)
 {
@@ -267,6 +385,15 @@ hipError_t launch_pack(const void* src, int dtype, int64_t outer, int64_t channe
 hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows,
                                       int64_t c_out, uint32_t* y_packed, hipStream_t stream)
 {
+    if (c_out % 32 == 0 && ((reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(thr)) & 15) == 0) {
+        constexpr int UNROLL = 4;
+        const int64_t units = rows * (c_out / 4);
+        int64_t blocks = (units + 256 * UNROLL - 1) / (256 * UNROLL);
+        if (blocks > 4096) blocks = 4096;   // grid-stride beyond that
+        hipLaunchKernelGGL((threshold_sign_pack4_kernel<UNROLL>), dim3((unsigned)blocks), dim3(256), 0,
+                           stream, y, thr, units, (int)c_out, y_packed);
+        return hipGetLastError();
+    }
     constexpr int ROWS = 8;
     const int64_t groups = (c_out + 63) / 64;
     const int64_t waves = ((rows + ROWS - 1) / ROWS) * groups;
