@@ -225,7 +225,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(np, W)
+        cpu = cpu_baseline(np, W, shapes)
 
     line = {
         "metric": "binary conv TBOPS (and % of VALU popcount peak) per layer shape, 1 MI355X",
@@ -319,22 +319,36 @@ def aux_measurements(torch, B, dev, work):
     return out
 
 
-def cpu_baseline(np, W):
-    """The CPU oracle, as it stands, on a bounded sample: shape 3 (3x3, c256,
-    28x28, fused epilogue), all 64 images."""
+def cpu_baseline(np, W, shapes):
+    """The CPU oracle, as it stands, on one whole step of the same workload:
+    for every layer shape the full batch goes through sign -> (conv ->
+    threshold -> channel packing) per layer, on the host's threads.  Input
+    generation is outside the clock.  About 25 s of CPU work on 16 threads."""
     import oracle
-    cfg, x, ws, ts = W.make_inputs(3)
-    oracle.conv2d_pm1(x[:1], ws[0], cfg.stride, cfg.pad)  # load + first touch
-    t0 = time.perf_counter()
-    y = oracle.conv2d_pm1(x, ws[0], cfg.stride, cfg.pad)
-    s = oracle.threshold_sign(y, ts[0])
-    n, ho, wo, o = s.shape
-    oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))
-    dt = time.perf_counter() - t0
-    bops = 2 * n * ho * wo * o * W.k_total(cfg)
-    return {"value": round(bops / dt / 1e12, 6), "unit": "TBOPS", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(dt, 2),
-            "sample": "shape 3 (n=64,c=256,28x28,3x3,s1,p1, fused epilogue), whole batch"}
+    c1, x1, w1, _ = W.make_inputs(1)
+    oracle.conv2d_pm1(x1, w1[0], c1.stride, c1.pad)  # load the library, start the thread pool
+    seconds, bops = 0.0, 0
+    for index in shapes:
+        cfg, x, ws, ts = W.make_inputs(index)
+        x_real = W.real_with_sign(W.seeds(index)[0], x)
+        del x
+        t0 = time.perf_counter()
+        cur = oracle.sign_f32(x_real)
+        for w, t in zip(ws, ts):
+            y = oracle.conv2d_pm1(cur, w, cfg.stride, cfg.pad)
+            if t is None:
+                break
+            s = oracle.threshold_sign(y, t)
+            n, ho, wo, o = s.shape
+            cur = np.ascontiguousarray(s.transpose(0, 3, 1, 2))
+            oracle.pack_channels(cur.reshape(n, o, ho * wo))
+        seconds += time.perf_counter() - t0
+        bops += W.binary_ops(cfg)
+        del x_real, cur, y
+    return {"value": round(bops / seconds / 1e12, 6), "unit": "TBOPS", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(seconds, 2),
+            "sample": "one whole step: layer shapes %s at full batch, every layer (sign, conv, threshold, "
+                      "channel packing) through the oracle" % (shapes,)}
 
 
 if __name__ == "__main__":
