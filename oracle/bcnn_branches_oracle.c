@@ -1,0 +1,157 @@
+/*
+ * CPU oracle, second part: F x F binary convolution written as F*F parallel
+ * shifted binary 1x1 convolutions, each with its own real scale.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE (see bcnn_oracle.c): only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may call it, and
+ * it shares nothing with the library.
+ *
+ * What it follows (paper, Section 4.2.1): a binary convolution module adds a
+ * learnable bias, takes the sign, applies a binary 1x1 convolution and then
+ * batch norm (first paragraph); a module may hold P parallel branches, each with its own bias,
+ * binary weights and batch-norm parameters, whose results are summed (Figure 2,
+ * bottom), and the last paragraph builds an F x F binary convolution from
+ * P = F*F such branches: branch (u,v) sees the real feature map shifted by
+ * (u,v) and zero padded BEFORE its bias is added, so that
+ *
+ *   a_t[n][c][oh][ow] = a[n][c][oh*s-p+u][ow*s-p+v]   inside the image, else 0
+ *   x_t               = sign(a_t + b_t[c])             (+1 for >= 0)
+ *   y_t[n][oh][ow][o] = sum_c x_t[n][c][oh][ow] * w[o][c][u][v]
+ *   z[n][oh][ow][o]   = sum_t ( g_t[o] * y_t + h_t[o] )
+ *
+ * with t = u*F + v, g/h the per-branch batch-norm scale and bias.  A padded
+ * position therefore is the constant sign(b_t[c]) per branch and channel, not
+ * a zero operand.  Readings where the paper is silent: the stride is applied
+ * by evaluating every branch at the output positions only; branches are
+ * summed in the order t = 0 .. F*F-1.
+ *
+ * Two evaluations are offered:
+ *   oracle_branches_real : the steps above, literally, from the real tensor,
+ *                          sums in double.
+ *   oracle_branches_pm1  : the same on already binarised operands (one tensor
+ *                          per branch or one shared by all), with an explicit
+ *                          pad value per (branch, channel) from {-1, 0, +1};
+ *                          0 is the variant in which a padded tap contributes
+ *                          nothing.  z is produced twice: in double (the
+ *                          definition) and in float as the chain
+ *                            z = h[o];  z = fmaf(g_t[o], (float)y_t, z), t = 0..P-1
+ *                          which is the precision and order in which the bit
+ *                          (z >= 0) of the fused variant is decided.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+
+int oracle_out_dim(int in, int k, int stride, int pad);
+
+/* Bias, then sign (Section 4.2.1, first paragraph).  x: [outer][C][inner]
+ * float, bias: [C] float, s: same shape as x, int8.  The sum is rounded to
+ * float before the comparison; NaN gives -1. */
+void oracle_sign_bias_f32(const float *x, const float *bias, int64_t outer, int64_t C,
+                          int64_t inner, int8_t *s)
+{
+    for (int64_t a = 0; a < outer; ++a)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t i = 0; i < inner; ++i) {
+                const size_t at = (size_t)((a * C + c) * inner + i);
+                volatile float v = x[at] + bias[c];
+                s[at] = (v >= 0.0f) ? (int8_t)1 : (int8_t)-1;
+            }
+}
+
+/*
+ * Literal evaluation from the real tensor.  a: [N][C][H][W] float;
+ * b: [P][C] float;  w: [O][C][F][F] int8 +-1;  g, h: [P][O] float;
+ * z: [N][Ho][Wo][O] double.  P = F*F.  Returns 0, or -1 for an empty output.
+ */
+int oracle_branches_real(const float *a, const float *b, const int8_t *w,
+                         const float *g, const float *h,
+                         int N, int C, int H, int W, int O, int F, int stride, int pad,
+                         double *z)
+{
+    const int Ho = oracle_out_dim(H, F, stride, pad);
+    const int Wo = oracle_out_dim(W, F, stride, pad);
+    if (N < 1 || C < 1 || O < 1 || Ho < 1 || Wo < 1)
+        return -1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int oh = 0; oh < Ho; ++oh)
+            for (int ow = 0; ow < Wo; ++ow)
+                for (int o = 0; o < O; ++o) {
+                    double sum = 0.0;
+                    for (int u = 0; u < F; ++u)
+                        for (int v = 0; v < F; ++v) {
+                            const int t = u * F + v;
+                            const int ih = oh * stride - pad + u;
+                            const int iw = ow * stride - pad + v;
+                            const int inside = ih >= 0 && ih < H && iw >= 0 && iw < W;
+                            int32_t y = 0;
+                            for (int c = 0; c < C; ++c) {
+                                const float shifted =
+                                    inside ? a[(((size_t)n * C + c) * H + ih) * W + iw] : 0.0f;
+                                volatile float biased = shifted + b[(size_t)t * C + c];
+                                const int32_t xs = (biased >= 0.0f) ? 1 : -1;
+                                y += xs * (int32_t)w[(((size_t)o * C + c) * F + u) * F + v];
+                            }
+                            sum += (double)g[(size_t)t * O + o] * (double)y + (double)h[(size_t)t * O + o];
+                        }
+                    z[(((size_t)n * Ho + oh) * Wo + ow) * O + o] = sum;
+                }
+    return 0;
+}
+
+/*
+ * On binarised operands.  xb: [B][N][C][H][W] int8 +-1 with B = P (one tensor
+ * per branch) or B = 1 (shared != 0: every branch reads the same tensor);
+ * padv: [P][C] int8 from {-1, 0, +1}, the operand a tap outside the image
+ * stands for;  w: [O][C][F][F] int8 +-1;  g: [P][O] float;  h: [O] float or
+ * NULL (= 0), the sum of the branches' biases;  outputs, each may be NULL:
+ * z64 [N][Ho][Wo][O] double (exact products, double sums), z32 the float
+ * fmaf chain described at the top, y_taps [N][Ho][Wo][O][P] int32 the
+ * per-branch integer sums.
+ */
+int oracle_branches_pm1(const int8_t *xb, int shared, const int8_t *padv, const int8_t *w,
+                        const float *g, const float *h,
+                        int N, int C, int H, int W, int O, int F, int stride, int pad,
+                        double *z64, float *z32, int32_t *y_taps)
+{
+    const int Ho = oracle_out_dim(H, F, stride, pad);
+    const int Wo = oracle_out_dim(W, F, stride, pad);
+    const int P = F * F;
+    if (N < 1 || C < 1 || O < 1 || Ho < 1 || Wo < 1)
+        return -1;
+    const size_t branch_elems = (size_t)N * C * H * W;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int oh = 0; oh < Ho; ++oh)
+            for (int ow = 0; ow < Wo; ++ow)
+                for (int o = 0; o < O; ++o) {
+                    const size_t at = (((size_t)n * Ho + oh) * Wo + ow) * O + o;
+                    double sum64 = h ? (double)h[o] : 0.0;
+                    float sum32 = h ? h[o] : 0.0f;
+                    for (int u = 0; u < F; ++u)
+                        for (int v = 0; v < F; ++v) {
+                            const int t = u * F + v;
+                            const int ih = oh * stride - pad + u;
+                            const int iw = ow * stride - pad + v;
+                            const int inside = ih >= 0 && ih < H && iw >= 0 && iw < W;
+                            const int8_t *xt = xb + (shared ? 0 : (size_t)t * branch_elems);
+                            int32_t y = 0;
+                            for (int c = 0; c < C; ++c) {
+                                const int32_t xv = inside
+                                    ? (int32_t)xt[(((size_t)n * C + c) * H + ih) * W + iw]
+                                    : (int32_t)padv[(size_t)t * C + c];
+                                y += xv * (int32_t)w[(((size_t)o * C + c) * F + u) * F + v];
+                            }
+                            if (y_taps)
+                                y_taps[at * P + t] = y;
+                            sum64 += (double)g[(size_t)t * O + o] * (double)y;
+                            sum32 = fmaf(g[(size_t)t * O + o], (float)y, sum32);
+                        }
+                    if (z64)
+                        z64[at] = sum64;
+                    if (z32)
+                        z32[at] = sum32;
+                }
+    return 0;
+}

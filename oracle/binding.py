@@ -10,21 +10,21 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "bcnn_oracle.c")
+_SRCS = [os.path.join(_HERE, "bcnn_oracle.c"), os.path.join(_HERE, "bcnn_branches_oracle.c")]
 _LIB = os.path.join(_HERE, "libbcnn_oracle.so")
 _lib = None
 
 
 def build(force=False):
-    """Compile bcnn_oracle.c with gcc (-O3, OpenMP, baseline x86-64 so the
+    """Compile the oracle's C files with gcc (-O3, OpenMP, baseline x86-64 so the
     library also runs on a host other than the one that built it)."""
     global _lib
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(p) for p in _SRCS)
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
             ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-std=c11",
-             "-Wall", "-Wextra", "-o", tmp, _SRC])
+             "-ffp-contract=off", "-Wall", "-Wextra", "-o", tmp] + _SRCS + ["-lm"])
         os.replace(tmp, _LIB)
         _lib = None
     return _LIB
@@ -52,6 +52,12 @@ def _load():
     lib.oracle_pack_channels.restype = None
     lib.oracle_unpack_channels.argtypes = [vp, i64, i64, i64, vp]
     lib.oracle_unpack_channels.restype = None
+    lib.oracle_sign_bias_f32.argtypes = [vp, vp, i64, i64, i64, vp]
+    lib.oracle_sign_bias_f32.restype = None
+    lib.oracle_branches_real.argtypes = [vp] * 5 + [i32] * 8 + [vp]
+    lib.oracle_branches_real.restype = i32
+    lib.oracle_branches_pm1.argtypes = [vp, i32, vp, vp, vp, vp] + [i32] * 8 + [vp, vp, vp]
+    lib.oracle_branches_pm1.restype = i32
     _lib = lib
     return lib
 
@@ -147,3 +153,71 @@ def unpack_channels(p, channels):
     s = np.empty((outer, channels, inner), dtype=np.int8)
     _load().oracle_unpack_channels(_ptr(p), outer, channels, inner, _ptr(s))
     return s
+
+
+def sign_bias_f32(x, bias):
+    """x [outer, C, inner] float32, bias [C] float32 -> int8 +-1 of x's shape:
+    sign(x + bias[c]) with the sum rounded to float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bias = np.ascontiguousarray(bias, dtype=np.float32)
+    if x.ndim != 3 or bias.shape != (x.shape[1],):
+        raise ValueError("x must be [outer, C, inner] and bias [C]")
+    s = np.empty(x.shape, dtype=np.int8)
+    _load().oracle_sign_bias_f32(_ptr(x), _ptr(bias), x.shape[0], x.shape[1], x.shape[2], _ptr(s))
+    return s
+
+
+def branches_real(a, b, w, g, h, stride=1, pad=0):
+    """F x F binary convolution as F*F shifted 1x1 branches, from the real
+    tensor.  a [N,C,H,W] float32, b [P,C] float32, w [O,C,F,F] +-1,
+    g, h [P,O] float32 -> z [N,Ho,Wo,O] float64."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    w = _pm1(w, 4, "w")
+    n, c, hh, ww = a.shape
+    o, c2, f, f2 = w.shape
+    p = f * f
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    h = np.ascontiguousarray(h, dtype=np.float32)
+    if c2 != c or f2 != f or b.shape != (p, c) or g.shape != (p, o) or h.shape != (p, o):
+        raise ValueError("shape mismatch")
+    lib = _load()
+    ho, wo = lib.oracle_out_dim(hh, f, stride, pad), lib.oracle_out_dim(ww, f, stride, pad)
+    z = np.empty((n, max(ho, 0), max(wo, 0), o), dtype=np.float64)
+    rc = lib.oracle_branches_real(_ptr(a), _ptr(b), _ptr(w), _ptr(g), _ptr(h),
+                                  n, c, hh, ww, o, f, stride, pad, _ptr(z))
+    if rc != 0:
+        raise ValueError("oracle_branches_real failed: %d" % rc)
+    return z
+
+
+def branches_pm1(xb, padv, w, g, h=None, stride=1, pad=0, taps=False):
+    """The same on binarised operands.  xb [P,N,C,H,W] or [1,N,C,H,W] (shared by
+    all branches) +-1, padv [P,C] from {-1,0,+1}, w [O,C,F,F] +-1, g [P,O]
+    float32, h [O] float32 or None -> (z64, z32[, y_taps]) with z [N,Ho,Wo,O]
+    and y_taps [N,Ho,Wo,O,P] int32."""
+    xb = _pm1(xb, 5, "xb")
+    w = _pm1(w, 4, "w")
+    bcount, n, c, hh, ww = xb.shape
+    o, c2, f, f2 = w.shape
+    p = f * f
+    padv = np.ascontiguousarray(padv, dtype=np.int8)
+    g = np.ascontiguousarray(g, dtype=np.float32)
+    if h is not None:
+        h = np.ascontiguousarray(h, dtype=np.float32)
+    if c2 != c or f2 != f or bcount not in (1, p) or padv.shape != (p, c) or g.shape != (p, o) \
+            or (h is not None and h.shape != (o,)):
+        raise ValueError("shape mismatch")
+    lib = _load()
+    ho, wo = lib.oracle_out_dim(hh, f, stride, pad), lib.oracle_out_dim(ww, f, stride, pad)
+    shape = (n, max(ho, 0), max(wo, 0), o)
+    z64 = np.empty(shape, dtype=np.float64)
+    z32 = np.empty(shape, dtype=np.float32)
+    yt = np.empty(shape + (p,), dtype=np.int32) if taps else None
+    rc = lib.oracle_branches_pm1(_ptr(xb), 1 if bcount == 1 else 0, _ptr(padv),
+                                 _ptr(w), _ptr(g), _ptr(h) if h is not None else None,
+                                 n, c, hh, ww, o, f, stride, pad, _ptr(z64), _ptr(z32),
+                                 _ptr(yt) if taps else None)
+    if rc != 0:
+        raise ValueError("oracle_branches_pm1 failed: %d" % rc)
+    return (z64, z32, yt) if taps else (z64, z32)
