@@ -21,11 +21,13 @@ BCNN_ERR_DEVICE = -4
 BCNN_F32, BCNN_F16, BCNN_I8 = 0, 1, 2
 BCNN_VARIANT_AUTO, BCNN_VARIANT_VALU, BCNN_VARIANT_MFMA_I8, BCNN_VARIANT_MFMA_FP4 = 0, 1, 2, 3
 BCNN_VARIANT_MFMA_FP4_T4, BCNN_VARIANT_MFMA_FP4_T7 = 4, 5
+BCNN_PAD_WORDS, BCNN_PAD_ZERO = 0, 1
 
 EXPORTS = (
     "bcnn_pack", "bcnn_conv2d_binary", "bcnn_conv2d_binary_sign_pack",
     "bcnn_conv2d_binary_variant", "bcnn_threshold_sign_pack", "bcnn_out_dim",
     "bcnn_status_string", "bcnn_diag_copy_u32", "bcnn_diag_valu_peak",
+    "bcnn_pack_bias", "bcnn_conv2d_binary_branches", "bcnn_conv2d_binary_branches_sign_pack",
 )
 
 
@@ -64,6 +66,9 @@ def lib():
         L.bcnn_status_string.restype = ctypes.c_char_p
         L.bcnn_diag_copy_u32.argtypes = [vp, vp, i64, vp]
         L.bcnn_diag_valu_peak.argtypes = [vp, i32, i32, vp]
+        L.bcnn_pack_bias.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp]
+        L.bcnn_conv2d_binary_branches.argtypes = [dp, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, vp]
+        L.bcnn_conv2d_binary_branches_sign_pack.argtypes = [dp, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, vp]
         for name in EXPORTS:
             if name != "bcnn_status_string":
                 getattr(L, name).restype = ctypes.c_int
@@ -106,6 +111,27 @@ def bcnn_out_dim(size, k, stride, pad):
 
 def bcnn_pack(src, dtype, outer, channels, inner, dst, stream=None):
     return lib().bcnn_pack(_ptr(src), dtype, outer, channels, inner, _ptr(dst), _stream(stream))
+
+
+def bcnn_pack_bias(src, dtype, outer, channels, inner, bias, dst, stream=None):
+    return lib().bcnn_pack_bias(_ptr(src), dtype, outer, channels, inner, _ptr(bias), _ptr(dst),
+                                _stream(stream))
+
+
+def bcnn_conv2d_binary_branches(desc, x_packed, x_branch_stride, w_packed, pad_words, pad_mode,
+                                scale, bias, z, stream=None):
+    return lib().bcnn_conv2d_binary_branches(ctypes.byref(_desc(desc)), _ptr(x_packed),
+                                             int(x_branch_stride), _ptr(w_packed),
+                                             _ptr(pad_words), int(pad_mode), _ptr(scale), _ptr(bias),
+                                             _ptr(z), _stream(stream))
+
+
+def bcnn_conv2d_binary_branches_sign_pack(desc, x_packed, x_branch_stride, w_packed, pad_words,
+                                          pad_mode, scale, bias, z_packed, stream=None):
+    return lib().bcnn_conv2d_binary_branches_sign_pack(
+        ctypes.byref(_desc(desc)), _ptr(x_packed), int(x_branch_stride),
+        _ptr(w_packed), _ptr(pad_words), int(pad_mode), _ptr(scale), _ptr(bias), _ptr(z_packed),
+        _stream(stream))
 
 
 def bcnn_conv2d_binary(desc, x_packed, w_packed, y, stream=None):

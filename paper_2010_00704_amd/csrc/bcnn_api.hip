@@ -137,8 +137,8 @@ const char* bcnn_status_string(int status)
     }
 }
 
-int bcnn_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
-              uint32_t* dst, void* hip_stream)
+static int pack_entry(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+                      const float* bias, uint32_t* dst, void* hip_stream)
 {
     if (!src || !dst || outer < 1 || channels < 1 || inner < 1) return BCNN_ERR_INVALID_ARG;
     if (dtype != BCNN_F32 && dtype != BCNN_F16 && dtype != BCNN_I8) return BCNN_ERR_UNSUPPORTED;
@@ -148,9 +148,66 @@ int bcnn_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64
     const uintptr_t esz = dtype == BCNN_F32 ? 4 : dtype == BCNN_F16 ? 2 : 1;
     if (!bcnn::aligned(src, esz) || !bcnn::aligned(dst, 4)) return BCNN_ERR_ALIGNMENT;
     if (src == static_cast<const void*>(dst)) return BCNN_ERR_INVALID_ARG;
-    const hipError_t e = bcnn::launch_pack(src, dtype, outer, channels, inner, dst,
+    if (bias && !bcnn::aligned(bias, 4)) return BCNN_ERR_ALIGNMENT;
+    const hipError_t e = bcnn::launch_pack(src, dtype, bias, outer, channels, inner, dst,
                                            static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+int bcnn_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+              uint32_t* dst, void* hip_stream)
+{
+    return pack_entry(src, dtype, outer, channels, inner, nullptr, dst, hip_stream);
+}
+
+int bcnn_pack_bias(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+                   const float* bias, uint32_t* dst, void* hip_stream)
+{
+    if (!bias) return BCNN_ERR_INVALID_ARG;
+    return pack_entry(src, dtype, outer, channels, inner, bias, dst, hip_stream);
+}
+
+static int branches_entry(const bcnn_conv_desc* desc, const uint32_t* x, int64_t x_branch_stride,
+                          const uint32_t* w, const uint32_t* pad_words, int pad_mode,
+                          const float* scale, const float* bias, void* out, bool fused, void* hip_stream)
+{
+    bcnn::ConvShape s;
+    const int rc = bcnn::make_shape(desc, &s);
+    if (rc != BCNN_OK) return rc;
+    if (!x || !w || !scale || !out) return BCNN_ERR_INVALID_ARG;
+    if (pad_mode != BCNN_PAD_WORDS && pad_mode != BCNN_PAD_ZERO) return BCNN_ERR_INVALID_ARG;
+    const int64_t tensor_words = (int64_t)s.n * s.h * s.w * s.cw;
+    if (x_branch_stride != 0 && x_branch_stride < tensor_words) return BCNN_ERR_INVALID_ARG;
+    if (x_branch_stride > INT_MAX) return BCNN_ERR_UNSUPPORTED;
+    if (static_cast<const void*>(x) == out) return BCNN_ERR_INVALID_ARG;
+    if (!bcnn::aligned(x, 4) || !bcnn::aligned(w, 4) || !bcnn::aligned(scale, 4) || !bcnn::aligned(out, 4) ||
+        (pad_words && !bcnn::aligned(pad_words, 4)) || (bias && !bcnn::aligned(bias, 4)))
+        return BCNN_ERR_ALIGNMENT;
+    bcnn::BranchArgs a;
+    a.x = x; a.x_branch_stride = x_branch_stride; a.w = w;
+    a.pad_words = pad_mode == BCNN_PAD_WORDS ? pad_words : nullptr;
+    a.zero_pad = pad_mode == BCNN_PAD_ZERO;
+    a.scale = scale; a.bias = bias; a.out = out; a.fused = fused;
+    const hipError_t e = bcnn::launch_conv_branches(s, a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+int bcnn_conv2d_binary_branches(const bcnn_conv_desc* desc, const uint32_t* x_packed,
+                                int64_t x_branch_stride, const uint32_t* w_packed,
+                                const uint32_t* pad_words, int pad_mode, const float* scale,
+                                const float* bias, float* z, void* hip_stream)
+{
+    return branches_entry(desc, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale, bias, z,
+                          false, hip_stream);
+}
+
+int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc* desc, const uint32_t* x_packed,
+                                          int64_t x_branch_stride, const uint32_t* w_packed,
+                                          const uint32_t* pad_words, int pad_mode, const float* scale,
+                                          const float* bias, uint32_t* z_packed, void* hip_stream)
+{
+    return branches_entry(desc, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale, bias,
+                          z_packed, true, hip_stream);
 }
 
 int bcnn_conv2d_binary(const bcnn_conv_desc* desc, const uint32_t* x_packed,

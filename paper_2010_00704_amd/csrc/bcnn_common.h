@@ -21,8 +21,9 @@ struct ConvShape {
 };
 
 // Launchers, one per kernel family.  Each returns the hipError_t of its launch.
-hipError_t launch_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
-                       uint32_t* dst, hipStream_t stream);
+// bias: per-channel float added before the sign, or nullptr
+hipError_t launch_pack(const void* src, int dtype, const float* bias, int64_t outer, int64_t channels,
+                       int64_t inner, uint32_t* dst, hipStream_t stream);
 hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows,
                                       int64_t c_out, uint32_t* y_packed, hipStream_t stream);
 hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_t* w,
@@ -36,6 +37,19 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
 bool conv_mfma_i8_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
 hipError_t launch_conv_mfma_i8(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                                const int32_t* thr, void* out, hipStream_t stream);
+// F x F convolution as F*F shifted 1x1 branches with per-branch real scales.
+struct BranchArgs {
+    const uint32_t* x;        // packed activations, branch t at x + t * x_branch_stride
+    int64_t x_branch_stride;  // in words; 0 = one tensor shared by all branches
+    const uint32_t* w;        // packed weights [c_out][taps][cw]
+    const uint32_t* pad_words;  // [taps][cw] operand of a tap outside the image, or nullptr (all -1)
+    bool zero_pad;            // a tap outside the image contributes nothing
+    const float* scale;       // [taps][c_out]
+    const float* bias;        // [c_out] or nullptr
+    void* out;                // float [m][c_out], or packed bits [m][cwo] when fused
+    bool fused;
+};
+hipError_t launch_conv_branches(const ConvShape& s, const BranchArgs& a, hipStream_t stream);
 hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
 
 }  // namespace bcnn

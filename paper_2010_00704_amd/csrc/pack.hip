@@ -16,6 +16,15 @@ __device__ __forceinline__ bool nonneg(float v) { return v >= 0.0f; }
 __device__ __forceinline__ bool nonneg(_Float16 v) { return (float)v >= 0.0f; }
 __device__ __forceinline__ bool nonneg(int8_t v) { return v >= 0; }
 
+// The bit of one element: sign of the value, or (BIAS) of value + bias[channel]
+// with the sum rounded to float (Section 4.2.1: learnable bias, then sign).
+template <bool BIAS, typename T>
+__device__ __forceinline__ bool bit_of(T v, const float* __restrict__ bias, int64_t c)
+{
+    if constexpr (BIAS) return (float)v + bias[c] >= 0.0f;
+    else return nonneg(v);
+}
+
 // ---- [outer][C][inner] with inner >= 64: lanes run along `inner` ------------
 // One thread owns one inner position and builds `cwg` consecutive words of that
 // pixel.  For a fixed channel the 256 threads of a block read 256 consecutive
@@ -26,10 +35,10 @@ __device__ __forceinline__ bool nonneg(int8_t v) { return v >= 0; }
 constexpr int PACK_THREADS = 256;
 constexpr int PACK_CW_CHUNK = 8;  // most words per block: 256*8*4 B = 8 KB LDS
 
-template <typename T>
+template <typename T, bool BIAS>
 __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
-    const T* __restrict__ src, int64_t channels, int64_t inner, int64_t cw_total, int cwg,
-    int groups, uint32_t* __restrict__ dst)
+    const T* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t inner,
+    int64_t cw_total, int cwg, int groups, uint32_t* __restrict__ dst)
 {
     __shared__ uint32_t stage[PACK_THREADS * PACK_CW_CHUNK];
     const int64_t a = blockIdx.y / groups;
@@ -51,10 +60,10 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
 #pragma unroll
             for (int b = 0; b < 32; ++b) v[b] = __builtin_nontemporal_load(col + (c0 + b) * inner);
 #pragma unroll
-            for (int b = 0; b < 32; ++b) word |= (uint32_t)nonneg(v[b]) << b;
+            for (int b = 0; b < 32; ++b) word |= (uint32_t)bit_of<BIAS>(v[b], bias, c0 + b) << b;
         } else {
             for (int b = 0; c0 + b < channels; ++b)
-                word |= (uint32_t)nonneg(col[(c0 + b) * inner]) << b;
+                word |= (uint32_t)bit_of<BIAS>(col[(c0 + b) * inner], bias, c0 + b) << b;
         }
         stage[tid * jn + j] = word;
     }
@@ -71,9 +80,10 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
 // 16-byte non-temporal loads (four consecutive pixels of one channel); the 32
 // channel loads of a word are issued in two batches of 16.  This is the form
 // that gets closest to the chip's read bandwidth.
+template <bool BIAS>
 __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
-    const float* __restrict__ src, int64_t channels, int64_t inner, int64_t cw_total, int cwg,
-    int groups, uint32_t* __restrict__ dst)
+    const float* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t inner,
+    int64_t cw_total, int cwg, int groups, uint32_t* __restrict__ dst)
 {
     typedef float f4 __attribute__((ext_vector_type(4)));
     __shared__ uint32_t stage[PACK_THREADS * 4 * PACK_CW_CHUNK];
@@ -101,19 +111,19 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
                     v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(col + (c0 + 16 * half + b) * inner));
 #pragma unroll
                 for (int b = 0; b < 16; ++b) {
-                    w0 |= (uint32_t)nonneg(v[b][0]) << (16 * half + b);
-                    w1 |= (uint32_t)nonneg(v[b][1]) << (16 * half + b);
-                    w2 |= (uint32_t)nonneg(v[b][2]) << (16 * half + b);
-                    w3 |= (uint32_t)nonneg(v[b][3]) << (16 * half + b);
+                    w0 |= (uint32_t)bit_of<BIAS>(v[b][0], bias, c0 + 16 * half + b) << (16 * half + b);
+                    w1 |= (uint32_t)bit_of<BIAS>(v[b][1], bias, c0 + 16 * half + b) << (16 * half + b);
+                    w2 |= (uint32_t)bit_of<BIAS>(v[b][2], bias, c0 + 16 * half + b) << (16 * half + b);
+                    w3 |= (uint32_t)bit_of<BIAS>(v[b][3], bias, c0 + 16 * half + b) << (16 * half + b);
                 }
             }
         } else {
             for (int b = 0; c0 + b < channels; ++b) {
                 const f4 v = *reinterpret_cast<const f4*>(col + (c0 + b) * inner);
-                w0 |= (uint32_t)nonneg(v[0]) << b;
-                w1 |= (uint32_t)nonneg(v[1]) << b;
-                w2 |= (uint32_t)nonneg(v[2]) << b;
-                w3 |= (uint32_t)nonneg(v[3]) << b;
+                w0 |= (uint32_t)bit_of<BIAS>(v[0], bias, c0 + b) << b;
+                w1 |= (uint32_t)bit_of<BIAS>(v[1], bias, c0 + b) << b;
+                w2 |= (uint32_t)bit_of<BIAS>(v[2], bias, c0 + b) << b;
+                w3 |= (uint32_t)bit_of<BIAS>(v[3], bias, c0 + b) << b;
             }
         }
         stage[(4 * tid + 0) * jn + j] = w0;
@@ -136,10 +146,10 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
 // consecutive elements).  A thread ORs its rows' sign bits into partial words,
 // the R partials of a pixel meet in LDS.  A block packs up to 8 words (256
 // channels) of one `outer` index.
-template <typename T, int IP>
+template <typename T, int IP, bool BIAS>
 __global__ __launch_bounds__(256) void pack_small_inner_kernel(
-    const T* __restrict__ src, int64_t channels, int inner, int64_t cw_total, int groups,
-    uint32_t* __restrict__ dst)
+    const T* __restrict__ src, const float* __restrict__ bias, int64_t channels, int inner,
+    int64_t cw_total, int groups, uint32_t* __restrict__ dst)
 {
     constexpr int R = 256 / IP;          // channel rows per pass
     constexpr int PASSES = 32 / R;       // passes per output word (R divides 32 as IP >= 8)
@@ -160,11 +170,12 @@ __global__ __launch_bounds__(256) void pack_small_inner_kernel(
             for (int k = 0; k < PASSES; ++k)
                 v[k] = __builtin_nontemporal_load(base + (c0 + q + R * k) * inner);
 #pragma unroll
-            for (int k = 0; k < PASSES; ++k) word |= (uint32_t)nonneg(v[k]) << (q + R * k);
+            for (int k = 0; k < PASSES; ++k)
+                word |= (uint32_t)bit_of<BIAS>(v[k], bias, c0 + q + R * k) << (q + R * k);
         } else {
             for (int k = 0; k < PASSES; ++k) {
                 const int64_t c = c0 + q + R * k;
-                if (c < channels) word |= (uint32_t)nonneg(base[c * inner]) << (q + R * k);
+                if (c < channels) word |= (uint32_t)bit_of<BIAS>(base[c * inner], bias, c) << (q + R * k);
             }
         }
         part[j][q][i] = live ? word : 0u;
@@ -184,10 +195,10 @@ __global__ __launch_bounds__(256) void pack_small_inner_kernel(
 // One wave per (row, 64-channel group); the wave-wide ballot IS the two packed
 // words.  Reads are perfectly coalesced.  ROWS rows are handled per wave so
 // that several loads are in flight.
-template <typename T, int ROWS>
+template <typename T, int ROWS, bool BIAS>
 __global__ __launch_bounds__(256) void pack_rows_kernel(
-    const T* __restrict__ src, int64_t rows, int64_t channels, int64_t cw_total,
-    uint32_t* __restrict__ dst)
+    const T* __restrict__ src, const float* __restrict__ bias, int64_t rows, int64_t channels,
+    int64_t cw_total, uint32_t* __restrict__ dst)
 {
     const int lane = threadIdx.x & 63;
     const int64_t groups = (channels + 63) / 64;
@@ -200,7 +211,7 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
         const int64_t r = r0 + k;
-        bit[k] = (r < rows && c < channels) ? nonneg(src[r * channels + c]) : false;
+        bit[k] = (r < rows && c < channels) ? bit_of<BIAS>(src[r * channels + c], bias, c) : false;
     }
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
@@ -212,10 +223,10 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(
 }
 
 // ---- anything else (small inner, e.g. 3x3 filter taps): one thread per word --
-template <typename T>
+template <typename T, bool BIAS>
 __global__ __launch_bounds__(256) void pack_generic_kernel(
-    const T* __restrict__ src, int64_t outer, int64_t channels, int64_t inner, int64_t cw_total,
-    uint32_t* __restrict__ dst)
+    const T* __restrict__ src, const float* __restrict__ bias, int64_t outer, int64_t channels,
+    int64_t inner, int64_t cw_total, uint32_t* __restrict__ dst)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= outer * inner * cw_total) return;
@@ -225,13 +236,13 @@ __global__ __launch_bounds__(256) void pack_generic_kernel(
     uint32_t word = 0;
     for (int b = 0; b < 32; ++b) {
         const int64_t c = j * 32 + b;
-        if (c < channels) word |= (uint32_t)nonneg(src[(a * channels + c) * inner + i]) << b;
+        if (c < channels) word |= (uint32_t)bit_of<BIAS>(src[(a * channels + c) * inner + i], bias, c) << b;
     }
     dst[t] = word;
 }
 
-template <typename T>
-hipError_t pack_dispatch(const T* src, int64_t outer, int64_t channels, int64_t inner,
+template <typename T, bool BIAS>
+hipError_t pack_dispatch(const T* src, const float* bias, int64_t outer, int64_t channels, int64_t inner,
                          uint32_t* dst, hipStream_t stream)
 {
     const int64_t cw = (channels + 31) / 32;
@@ -240,8 +251,8 @@ hipError_t pack_dispatch(const T* src, int64_t outer, int64_t channels, int64_t 
         const int64_t groups = (channels + 63) / 64;
         const int64_t waves = ((outer + ROWS - 1) / ROWS) * groups;
         const int64_t blocks = (waves + 3) / 4;
-        hipLaunchKernelGGL((pack_rows_kernel<T, ROWS>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           src, outer, channels, cw, dst);
+        hipLaunchKernelGGL((pack_rows_kernel<T, ROWS, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           src, bias, outer, channels, cw, dst);
     } else if (std::is_same<T, float>::value && inner >= 256 && inner % 4 == 0 &&
                (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
         const int64_t bx = (inner + PACK_THREADS * 4 - 1) / (PACK_THREADS * 4);
@@ -249,8 +260,8 @@ hipError_t pack_dispatch(const T* src, int64_t outer, int64_t channels, int64_t 
         while (cwg > 1 && bx * outer * ((cw + cwg - 1) / cwg) < 512) cwg >>= 1;
         const int64_t groups = (cw + cwg - 1) / cwg;
         if (outer * groups > 65535) goto generic;
-        hipLaunchKernelGGL(pack_columns4_kernel, dim3((unsigned)bx, (unsigned)(outer * groups)),
-                           dim3(PACK_THREADS), 0, stream, reinterpret_cast<const float*>(src), channels,
+        hipLaunchKernelGGL((pack_columns4_kernel<BIAS>), dim3((unsigned)bx, (unsigned)(outer * groups)),
+                           dim3(PACK_THREADS), 0, stream, reinterpret_cast<const float*>(src), bias, channels,
                            inner, cw, cwg, (int)groups, dst);
     } else if (inner >= 64) {
         const int64_t bx = (inner + PACK_THREADS - 1) / PACK_THREADS;
@@ -259,30 +270,30 @@ hipError_t pack_dispatch(const T* src, int64_t outer, int64_t channels, int64_t 
         while (cwg > 1 && bx * outer * ((cw + cwg - 1) / cwg) < 512) cwg >>= 1;
         const int64_t groups = (cw + cwg - 1) / cwg;
         if (outer * groups > 65535) goto generic;
-        hipLaunchKernelGGL((pack_columns_kernel<T>), dim3((unsigned)bx, (unsigned)(outer * groups)),
-                           dim3(PACK_THREADS), 0, stream, src, channels, inner, cw, cwg, (int)groups, dst);
+        hipLaunchKernelGGL((pack_columns_kernel<T, BIAS>), dim3((unsigned)bx, (unsigned)(outer * groups)),
+                           dim3(PACK_THREADS), 0, stream, src, bias, channels, inner, cw, cwg, (int)groups, dst);
     } else if (inner >= 5) {
         const int64_t groups = (cw + 7) / 8;
         const int64_t blocks = outer * groups;
         if (blocks > 0x7FFFFFFF) goto generic;
         if (inner > 32)
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 64>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 64, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, (int)inner, cw, (int)groups, dst);
         else if (inner > 16)
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 32>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 32, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, (int)inner, cw, (int)groups, dst);
         else if (inner > 8)
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 16>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 16, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, (int)inner, cw, (int)groups, dst);
         else
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 8>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 8, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, (int)inner, cw, (int)groups, dst);
     } else {
     generic:
         const int64_t total = outer * inner * cw;
         const int64_t blocks = (total + 255) / 256;
-        hipLaunchKernelGGL((pack_generic_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           src, outer, channels, inner, cw, dst);
+        hipLaunchKernelGGL((pack_generic_kernel<T, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           src, bias, outer, channels, inner, cw, dst);
     }
     return hipGetLastError();
 }
@@ -371,13 +382,21 @@ __global__ __launch_bounds__(256) void diag_copy_kernel(const uint32_t* __restri
 
 }  // namespace
 
-hipError_t launch_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
-                       uint32_t* dst, hipStream_t stream)
+template <typename T>
+hipError_t pack_typed(const void* src, const float* bias, int64_t outer, int64_t channels, int64_t inner,
+                      uint32_t* dst, hipStream_t stream)
+{
+    if (bias) return pack_dispatch<T, true>(static_cast<const T*>(src), bias, outer, channels, inner, dst, stream);
+    return pack_dispatch<T, false>(static_cast<const T*>(src), nullptr, outer, channels, inner, dst, stream);
+}
+
+hipError_t launch_pack(const void* src, int dtype, const float* bias, int64_t outer, int64_t channels,
+                       int64_t inner, uint32_t* dst, hipStream_t stream)
 {
     switch (dtype) {
-        case 0: return pack_dispatch(static_cast<const float*>(src), outer, channels, inner, dst, stream);
-        case 1: return pack_dispatch(static_cast<const _Float16*>(src), outer, channels, inner, dst, stream);
-        case 2: return pack_dispatch(static_cast<const int8_t*>(src), outer, channels, inner, dst, stream);
+        case 0: return pack_typed<float>(src, bias, outer, channels, inner, dst, stream);
+        case 1: return pack_typed<_Float16>(src, bias, outer, channels, inner, dst, stream);
+        case 2: return pack_typed<int8_t>(src, bias, outer, channels, inner, dst, stream);
         default: return hipErrorInvalidValue;
     }
 }

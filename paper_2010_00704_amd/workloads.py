@@ -66,6 +66,22 @@ def real_with_sign(seed, signs):
     return _fill(signs.shape, fn, np.float32)
 
 
+def uniform_f32(seed, shape, lo, hi, steps=None):
+    """float32 tensor uniform on [lo, hi).  With ``steps`` the values lie on the
+    grid lo + k * (hi - lo) / steps, k = 0 .. steps-1 (choose lo, hi and steps so
+    that the grid is exact in float32, e.g. quarters), which makes exact ties
+    between sums of such values likely."""
+    lo32, span = np.float32(lo), np.float32(hi) - np.float32(lo)
+
+    def fn(s, n):
+        u24 = (raw_u64(seed, s, n) >> np.uint64(40)).astype(np.float64)
+        if steps is not None:
+            k = np.floor(u24 * steps / float(1 << 24))
+            return (lo32 + (k * (float(span) / steps)).astype(np.float32)).astype(np.float32)
+        return (lo32 + (u24 / float(1 << 24)).astype(np.float32) * span).astype(np.float32)
+    return _fill(shape, fn, np.float32)
+
+
 def thresholds(seed, count, bound):
     """int32 thresholds, uniform on the closed integer interval [-bound, bound]."""
     r = raw_u64(seed, 0, count) >> np.uint64(11)

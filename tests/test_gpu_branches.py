@@ -1,0 +1,252 @@
+"""Parity of the branch convolution (F x F as F*F shifted binary 1x1 branches
+with per-branch real scales; paper, Section 4.2.1, last paragraph) and of the
+bias-then-sign packing with the CPU oracle, on a real MI355X.
+
+The library evaluates z in float32 as one fused multiply-add per branch in a
+fixed order, exactly the chain the oracle's float result follows, so z is
+compared for equality (and, as a sanity check, against the oracle's double
+result within the chain's rounding bound); the fused bits and the packed words
+are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2010_00704_amd import binding as B
+from paper_2010_00704_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 64
+SENTINEL = 0x5A5A5A5A
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    B.lib()
+    return torch.device("cuda:0")
+
+
+class Guarded:
+    def __init__(self, words, dev):
+        self.words = int(words)
+        self.buf = torch.full((self.words + 2 * GUARD,), SENTINEL, dtype=torch.int32, device=dev)
+
+    @property
+    def ptr(self):
+        return self.buf.data_ptr() + 4 * GUARD
+
+    def get(self, dtype=np.uint32):
+        torch.cuda.synchronize()
+        host = self.buf.cpu().numpy()
+        assert np.all(host[:GUARD] == SENTINEL), "write before the output buffer"
+        assert np.all(host[GUARD + self.words:] == SENTINEL), "write past the output buffer"
+        return host[GUARD:GUARD + self.words].view(dtype)
+
+
+def up(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def i32(a):
+    return np.ascontiguousarray(a).view(np.int32)
+
+
+def pack_nchw(x):
+    n, c = x.shape[:2]
+    return oracle.pack_channels(x.reshape(n, c, -1))
+
+
+def pack_padv(padv):
+    """[P, C] of +-1 -> packed pad words [P, cw] (oracle's packer; inner = 1)."""
+    return oracle.pack_channels(padv[:, :, None])[:, 0, :]
+
+
+# ------------------------------------------------------------ bias, sign, pack
+PACK_BIAS_SHAPES = [
+    # outer, channels, inner   (every kernel family: rows, small inner, columns, 4-pixel columns, generic)
+    (5, 70, 1), (3, 64, 49), (2, 100, 9), (2, 33, 300), (2, 64, 784), (1, 32, 4), (3, 96, 17), (2, 256, 1024),
+]
+
+
+@pytest.mark.parametrize("outer,channels,inner", PACK_BIAS_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+def test_pack_bias(dev, outer, channels, inner, dtype):
+    seed = 7000 + outer * 131 + channels * 7 + inner
+    signs = W.pm1(seed, (outer, channels, inner))
+    if dtype == "i8":
+        mag = (W.raw_u64(seed + 1, 0, signs.size) % np.uint64(4)).astype(np.int8).reshape(signs.shape)
+        x = (signs * mag).astype(np.int8)                      # -3 .. 3, zeros included
+        bias = W.uniform_f32(seed + 2, (channels,), -3.0, 3.0, steps=12)   # halves: ties with integers
+        xt, code = torch.from_numpy(x), B.BCNN_I8
+        x_f32 = x.astype(np.float32)
+    else:
+        x = W.real_with_sign(seed, signs)
+        bias = W.uniform_f32(seed + 2, (channels,), -1.5, 1.5)
+        if dtype == "f16":
+            x = x.astype(np.float16)
+            xt, code = torch.from_numpy(x), B.BCNN_F16
+        else:
+            xt, code = torch.from_numpy(x), B.BCNN_F32
+        x_f32 = x.astype(np.float32)
+        # exact cancellations and near misses in a few places
+        flat = x_f32.reshape(outer, channels, inner)
+        for k in range(min(channels, 6)):
+            a, i = k % outer, (3 * k) % inner
+            bias[k] = -flat[a, k, i]
+    want = oracle.pack_channels(oracle.sign_bias_f32(x_f32.reshape(outer, channels, inner), bias))
+    cw = (channels + 31) // 32
+    out = Guarded(outer * inner * cw, dev)
+    B.check(B.bcnn_pack_bias(xt.to(dev), code, outer, channels, inner, up(bias, dev), out.ptr), "pack_bias")
+    got = out.get().reshape(outer, inner, cw)
+    assert np.array_equal(got, want)
+
+
+def test_pack_bias_rejects_missing_bias(dev):
+    x = torch.zeros((1, 32, 4), dtype=torch.float32, device=dev)
+    out = torch.zeros((4,), dtype=torch.int32, device=dev)
+    assert B.bcnn_pack_bias(x, B.BCNN_F32, 1, 32, 4, None, out) == B.BCNN_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------ branch convolution
+def make_case(seed, n, c, h, w, o, k, shared, grid):
+    p = k * k
+    xb = W.pm1(seed, (1 if shared else p, n, c, h, w), 0.4)
+    wt = W.pm1(seed + 1, (o, c, k, k))
+    padv = W.pm1(seed + 2, (p, c))
+    if grid:   # scales and biases on a grid of quarters: exact float sums, exact zeros of z occur
+        g = W.uniform_f32(seed + 3, (p, o), -2.0, 2.0, steps=16)
+        hb = W.uniform_f32(seed + 4, (o,), -8.0, 8.0, steps=64)
+    else:
+        g = W.uniform_f32(seed + 3, (p, o), -1.5, 1.5)
+        hb = W.uniform_f32(seed + 4, (o,), -float(c), float(c))
+    return xb, wt, padv, g, hb
+
+
+def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused):
+    bcount, n, c, h, w = xb.shape
+    o, _, k, _ = wt.shape
+    desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
+    ho, wo = B.out_shape(desc)
+    cw = (c + 31) // 32
+    xp = up(i32(np.stack([pack_nchw(xb[t]) for t in range(bcount)])), dev)
+    wp = up(i32(oracle.pack_channels(wt.reshape(o, c, -1))), dev)
+    stride_words = 0 if bcount == 1 else n * h * w * cw
+    pw = up(i32(padv_words), dev) if padv_words is not None else None
+    gt, ht = up(g, dev), (up(hb, dev) if hb is not None else None)
+    if fused:
+        cwo = (o + 31) // 32
+        out = Guarded(n * ho * wo * cwo, dev)
+        B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, xp, stride_words, wp, pw, mode, gt, ht, out.ptr),
+                "branches_sign_pack")
+        return out.get(np.uint32).reshape(n, ho * wo, cwo)
+    out = Guarded(n * ho * wo * o, dev)
+    B.check(B.bcnn_conv2d_binary_branches(desc, xp, stride_words, wp, pw, mode, gt, ht, out.ptr), "branches")
+    return out.get(np.float32).reshape(n, ho, wo, o)
+
+
+def oracle_bits(z32):
+    n, ho, wo, o = z32.shape
+    s = oracle.sign_f32(z32)
+    return oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))
+
+
+BRANCH_SHAPES = [
+    # n, c_in, h, w, c_out, k, stride, pad
+    (1, 64, 14, 14, 64, 3, 1, 1),
+    (2, 128, 9, 7, 96, 3, 1, 1),
+    (3, 33, 6, 5, 7, 3, 1, 1),       # ragged channels both ways, scalar word loads
+    (2, 100, 8, 8, 40, 3, 2, 1),
+    (2, 64, 7, 7, 33, 3, 1, 0),      # no padding
+    (1, 256, 20, 20, 64, 3, 2, 1),
+    (4, 192, 5, 5, 130, 1, 1, 0),    # F = 1: one branch
+    (1, 70, 17, 3, 31, 3, 2, 0),
+    (40, 64, 14, 14, 64, 3, 1, 1),   # enough waves for two pixels per lane
+    (2, 1, 4, 4, 1, 3, 1, 1),
+]
+MODES = ["minus", "words", "zero"]
+
+
+@pytest.mark.parametrize("shape", BRANCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("shared", [True, False], ids=["shared", "per_branch"])
+def test_branches_match_oracle(dev, shape, mode, shared):
+    n, c, h, w, o, k, stride, pad = shape
+    seed = 8000 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23))) + MODES.index(mode) + 2 * shared
+    p = k * k
+    for grid in (False, True):
+        xb, wt, padv, g, hb = make_case(seed + 50 * grid, n, c, h, w, o, k, shared, grid)
+        if mode == "minus":
+            padv_o, words, code = -np.ones((p, c), dtype=np.int8), None, B.BCNN_PAD_WORDS
+        elif mode == "words":
+            padv_o, words, code = padv, pack_padv(padv), B.BCNN_PAD_WORDS
+        else:
+            padv_o, words, code = np.zeros((p, c), dtype=np.int8), pack_padv(padv), B.BCNN_PAD_ZERO
+        z64, z32, yt = oracle.branches_pm1(xb, padv_o, wt, g, hb, stride, pad, taps=True)
+        got = gpu_branches(dev, xb, wt, words, code, g, hb, stride, pad, fused=False)
+        assert np.array_equal(got, z32)
+        mag = np.abs(hb.astype(np.float64)) + (np.abs(g.astype(np.float64)).T[None, None, None] * np.abs(yt)).sum(-1)
+        assert np.all(np.abs(got.astype(np.float64) - z64) <= p * 2.0**-24 * mag + 1e-30)
+        bits = gpu_branches(dev, xb, wt, words, code, g, hb, stride, pad, fused=True)
+        assert np.array_equal(bits, oracle_bits(z32))
+        if grid:
+            assert np.any(z32 == 0) or z32.size < 20000, "grid case should produce exact zeros of z"
+
+
+def test_null_bias_is_zero_and_unit_scales_give_the_integer_convolution(dev):
+    n, c, h, w, o, k = 2, 96, 10, 9, 64, 3
+    xb = W.pm1(9100, (1, n, c, h, w))
+    wt = W.pm1(9101, (o, c, k, k))
+    g = np.ones((9, o), dtype=np.float32)
+    got = gpu_branches(dev, xb, wt, None, B.BCNN_PAD_WORDS, g, None, 1, 1, fused=False)
+    y = oracle.conv2d_pm1(xb[0], wt, 1, 1)
+    assert np.array_equal(got, y.astype(np.float32))
+
+
+def test_branch_argument_checks(dev):
+    desc = B.conv_desc(1, 64, 8, 8, 32, 3, 1, 1)
+    x = torch.zeros((64 * 2,), dtype=torch.int32, device=dev)
+    w = torch.zeros((32 * 9 * 2,), dtype=torch.int32, device=dev)
+    g = torch.zeros((9 * 32,), dtype=torch.float32, device=dev)
+    z = torch.zeros((64 * 32,), dtype=torch.float32, device=dev)
+    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 7, g, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, x, 5, w, None, 0, g, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, None, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, g, None, None) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, g.data_ptr() + 2, None, z) == B.BCNN_ERR_ALIGNMENT
+    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, g, None, z) == B.BCNN_OK
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------ full-size shapes
+@pytest.mark.parametrize("index", [3, 4])
+def test_branches_full_size(dev, index):
+    """The launch is the full benchmark shape (3x3, 256 channels, whole batch,
+    one tensor shared by the branches, per-branch pad words); the oracle
+    evaluates the first, middle and last image."""
+    cfg = W.CONFIGS[index - 1]
+    picks = [0, cfg.n // 2, cfg.n - 1]
+    _, x_all, ws, _ = W.make_inputs(index)
+    wt = ws[0]
+    p = cfg.k * cfg.k
+    padv = W.pm1(9200 + index, (p, cfg.c_in))
+    g = W.uniform_f32(9300 + index, (p, cfg.c_out), -1.5, 1.5)
+    hb = W.uniform_f32(9400 + index, (cfg.c_out,), -40.0, 40.0)
+    desc = B.conv_desc(cfg.n, cfg.c_in, cfg.h, cfg.w, cfg.c_out, cfg.k, cfg.stride, cfg.pad)
+    ho, wo = B.out_shape(desc)
+    xp = B.pack_nchw(up(x_all, dev))
+    wp = B.pack_nchw(up(wt, dev))
+    pw = up(i32(pack_padv(padv)), dev)
+    gt, ht = up(g, dev), up(hb, dev)
+    z = torch.empty((cfg.n, ho, wo, cfg.c_out), dtype=torch.float32, device=dev)
+    zp = torch.empty((cfg.n, ho * wo, cfg.c_out // 32), dtype=torch.int32, device=dev)
+    B.check(B.bcnn_conv2d_binary_branches(desc, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, z), "branches")
+    B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, zp), "fused")
+    torch.cuda.synchronize()
+    _, z32 = oracle.branches_pm1(x_all[picks][None], padv, wt, g, hb, cfg.stride, cfg.pad)
+    got = z[picks].cpu().numpy()
+    assert np.array_equal(got, z32)
+    bits = zp[picks].cpu().numpy().view(np.uint32)
+    assert np.array_equal(bits, oracle_bits(z32))
