@@ -316,6 +316,51 @@ def aux_measurements(torch, B, dev, work):
     b.synchronize()
     ms = a.elapsed_time(b) / reps
     out["copy_gbs_read_plus_write"] = round(2 * ys[0].numel() * 4 / (ms * 1e-3) / 1e9, 1)
+    del ys, dst
+
+    # pack with a per-channel bias before the sign, same input as the pack figure above
+    from paper_2010_00704_amd import workloads as W
+    bias_c = torch.from_numpy(W.uniform_f32(4100, (cfg.c_in,), -0.75, 0.75)).to(dev)
+    srcs = [wk["x_real"]] + [wk["x_real"].clone() for _ in range(3)]
+    B.check(B.bcnn_pack_bias(srcs[0], B.BCNN_F32, cfg.n, cfg.c_in, cfg.h * cfg.w, bias_c, wk["xp"]), "pack_bias")
+    a, b = ev(), ev()
+    a.record()
+    for r in range(reps):
+        B.check(B.bcnn_pack_bias(srcs[r % 4], B.BCNN_F32, cfg.n, cfg.c_in, cfg.h * cfg.w, bias_c, wk["xp"]),
+                "pack_bias")
+    b.record()
+    b.synchronize()
+    ms = a.elapsed_time(b) / reps
+    nbytes = srcs[0].numel() * 4 + wk["xp"].numel() * 4
+    out["pack_bias_f32_gbs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    del srcs
+
+    # branch convolution (F*F shifted 1x1 branches, per-branch real scales, per-branch pad words,
+    # fused sign-pack) on the 3x3 shapes; runs on the vector ALUs, so the bound is the xor+popcount peak
+    out["branches"] = []
+    for wk in work[2:5]:
+        cfg = wk["cfg"]
+        d = wk["descs"][0]
+        taps = cfg.k * cfg.k
+        cw = (cfg.c_in + 31) // 32
+        scale = torch.from_numpy(W.uniform_f32(4200, (taps, cfg.c_out), -1.5, 1.5)).to(dev)
+        hb = torch.from_numpy(W.uniform_f32(4300, (cfg.c_out,), -40.0, 40.0)).to(dev)
+        padw = torch.randint(-2**31, 2**31 - 1, (taps, cw), dtype=torch.int32, device=dev)
+        zp = torch.empty_like(wk["outs"][0])
+        for _ in range(2):
+            B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
+                                                            scale, hb, zp), "branches")
+        a, b = ev(), ev()
+        a.record()
+        for r in range(reps):
+            B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
+                                                            scale, hb, zp), "branches")
+        b.record()
+        b.synchronize()
+        ms = a.elapsed_time(b) / reps
+        tb = W.binary_ops(cfg) / cfg.layers / (ms * 1e-3) / 1e12
+        out["branches"].append({"name": cfg.name, "ms": round(ms, 4), "tbops": round(tb, 1),
+                                "frac_valu_peak": round(tb / VALU_PEAK_TBOPS, 4)})
     return out
 
 

@@ -23,7 +23,7 @@ namespace {
 constexpr int TN = 32;
 enum { PAD_MINUS = 0, PAD_WORDS = 1, PAD_SKIP = 2 };
 
-template <int TM, int VEC, int PADMODE, bool FUSED>
+template <int TM, int VEC, int PADMODE, bool FUSED, bool FULL>
 __global__ __launch_bounds__(256) void conv_branches_kernel(
     ConvShape s, int32_t n_mtiles, int32_t n_ctiles,
     const uint32_t* __restrict__ x, int64_t x_branch_stride, const uint32_t* __restrict__ w,
@@ -36,8 +36,19 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
     const int ctile = tile % n_ctiles;
     const int mtile = tile / n_ctiles;
     if (mtile >= n_mtiles) return;
-    const int o0 = ctile * TN;
+    // FULL (c_out >= 32): every tile computes 32 real channels.  The last tile of
+    // a ragged c_out starts at c_out - 32 instead of 32*ctile and drops the
+    // `shift` channels it shares with its neighbour when it stores, so no index
+    // is ever clamped.  Otherwise (c_out < 32) rows of channels beyond c_out are
+    // clamped to the last real one so that every scalar load stays inside its
+    // tensor.
     const int o_last = s.c_out - 1;
+    const int o0 = (FULL && ctile * TN + TN > s.c_out) ? s.c_out - TN : ctile * TN;
+    const int shift = ctile * TN - o0;
+    auto chan = [&](int o) -> uint32_t {
+        if constexpr (FULL) return (uint32_t)(o0 + o);
+        else return (uint32_t)((o0 + o < o_last) ? (o0 + o) : o_last);
+    };
 
     int pn[TM], ph[TM], pw[TM];
     bool live[TM];
@@ -55,17 +66,26 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
     }
 
     float z[TM][TN];
+    if (bias) {
+        const float* bp = bias + (FULL ? o0 : 0);
 #pragma unroll
-    for (int o = 0; o < TN; ++o) {
-        const int oc = (o0 + o < o_last) ? (o0 + o) : o_last;
-        const float b = bias ? bias[oc] : 0.0f;
+        for (int o = 0; o < TN; ++o) {
+            float b;
+            if constexpr (FULL) b = bp[o];
+            else b = bias[chan(o)];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) z[i][o] = b;
+            for (int i = 0; i < TM; ++i) z[i][o] = b;
+        }
+    } else {
+#pragma unroll
+        for (int o = 0; o < TN; ++o)
+#pragma unroll
+            for (int i = 0; i < TM; ++i) z[i][o] = 0.0f;
     }
 
     const int taps = s.ks * s.ks;
     const int c_in = s.k / taps;          // real channels: the K of one branch
-    const int wrow = taps * s.cw;
+    const uint32_t wrow = (uint32_t)(taps * s.cw);
 
     for (int tap = 0; tap < taps; ++tap) {
         const int u = tap / s.ks, v = tap - u * s.ks;
@@ -85,7 +105,7 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
 #pragma unroll
             for (int o = 0; o < TN; ++o) acc[i][o] = 0;
 
-        const uint32_t* wt = w + (size_t)tap * s.cw;
+        const uint32_t* wt = w + (uint32_t)(tap * s.cw);
         for (int j0 = 0; j0 < s.cw; j0 += VEC) {
             uint32_t pwv[VEC];
 #pragma unroll
@@ -110,8 +130,7 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
             }
 #pragma unroll
             for (int o = 0; o < TN; ++o) {
-                const int oc = (o0 + o < o_last) ? (o0 + o) : o_last;
-                const uint32_t* wp = wt + (size_t)oc * wrow + j0;
+                const uint32_t* wp = wt + (chan(o) * wrow + (uint32_t)j0);
                 uint32_t wv[VEC];
                 if constexpr (VEC == 1) {
                     wv[0] = wp[0];
@@ -131,10 +150,12 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
         }
 
         // fold this branch into the float sums: y_t = c_in - 2*popcount
+        const float* gp = scale + (size_t)tap * s.c_out + (FULL ? o0 : 0);
 #pragma unroll
         for (int o = 0; o < TN; ++o) {
-            const int oc = (o0 + o < o_last) ? (o0 + o) : o_last;
-            const float g = scale[(size_t)tap * s.c_out + oc];
+            float g;
+            if constexpr (FULL) g = gp[o];
+            else g = scale[(uint32_t)(tap * s.c_out) + chan(o)];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const float y = (float)(c_in - 2 * acc[i][o]);
@@ -152,18 +173,17 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
             uint32_t word = 0;
 #pragma unroll
             for (int o = 0; o < TN; ++o) {
-                const bool on = (o0 + o <= o_last) && (z[i][o] >= 0.0f);
+                const bool on = (FULL || o0 + o <= o_last) && (z[i][o] >= 0.0f);
                 word |= (uint32_t)on << o;
             }
             if (live[i]) {
                 const int m = mtile * (64 * TM) + i * 64 + lane;
-                zp[(size_t)m * s.cwo + ctile] = word;
+                zp[(size_t)m * s.cwo + ctile] = word >> shift;
             }
         }
     } else {
         float* zo = static_cast<float*>(out);
-        const bool vec_ok = (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(zo) & 15) == 0) &&
-                            (o0 + TN <= s.c_out);
+        const bool vec_ok = FULL && (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(zo) & 15) == 0);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if (!live[i]) continue;
@@ -172,12 +192,13 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
             if (vec_ok) {
 #pragma unroll
                 for (int o = 0; o < TN; o += 4)
-                    *reinterpret_cast<float4*>(row + o) =
-                        make_float4(z[i][o], z[i][o + 1], z[i][o + 2], z[i][o + 3]);
+                    if (o >= shift)
+                        *reinterpret_cast<float4*>(row + o) =
+                            make_float4(z[i][o], z[i][o + 1], z[i][o + 2], z[i][o + 3]);
             } else {
 #pragma unroll
                 for (int o = 0; o < TN; ++o)
-                    if (o0 + o < s.c_out) row[o] = z[i][o];
+                    if (o >= shift && o0 + o < s.c_out) row[o] = z[i][o];
             }
         }
     }
@@ -190,12 +211,18 @@ hipError_t launch_mode(const ConvShape& s, const BranchArgs& a, hipStream_t stre
     const int n_mtiles = (s.m + 64 * TM - 1) / (64 * TM);
     const int64_t waves = (int64_t)n_ctiles * n_mtiles;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
-    if (a.fused)
-        hipLaunchKernelGGL((conv_branches_kernel<TM, VEC, PADMODE, true>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, a.x, a.x_branch_stride, a.w, a.pad_words, a.scale, a.bias, a.out);
-    else
-        hipLaunchKernelGGL((conv_branches_kernel<TM, VEC, PADMODE, false>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, a.x, a.x_branch_stride, a.w, a.pad_words, a.scale, a.bias, a.out);
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, stream, s, n_mtiles, n_ctiles, a.x,
+                           a.x_branch_stride, a.w, a.pad_words, a.scale, a.bias, a.out);
+    };
+    const bool full = s.c_out >= TN;
+    if (a.fused) {
+        if (full) go(conv_branches_kernel<TM, VEC, PADMODE, true, true>);
+        else go(conv_branches_kernel<TM, VEC, PADMODE, true, false>);
+    } else {
+        if (full) go(conv_branches_kernel<TM, VEC, PADMODE, false, true>);
+        else go(conv_branches_kernel<TM, VEC, PADMODE, false, false>);
+    }
     return hipGetLastError();
 }
 
