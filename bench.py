@@ -348,12 +348,12 @@ def aux_measurements(torch, B, dev, work):
         padw = torch.randint(-2**31, 2**31 - 1, (taps, cw), dtype=torch.int32, device=dev)
         zp = torch.empty_like(wk["outs"][0])
         for _ in range(2):
-            B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
+            B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, taps, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
                                                             scale, hb, zp), "branches")
         a, b = ev(), ev()
         a.record()
         for r in range(reps):
-            B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
+            B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, taps, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
                                                             scale, hb, zp), "branches")
         b.record()
         b.synchronize()

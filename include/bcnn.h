@@ -146,29 +146,33 @@ int bcnn_threshold_sign_pack(const int32_t *y, const int32_t *thr, int64_t rows,
                              uint32_t *y_packed, void *hip_stream);
 
 /*
- * F x F binary convolution as F*F parallel shifted binary 1x1 convolutions,
- * each with its own real scale (Section 4.2.1, last paragraph, on the
- * parallel-branch module of Figure 2): branch t = u*kw + v reads the
- * activations shifted by (u, v), multiplies by its 1x1 slice of the weights,
- * is scaled per output channel, and the branches are summed:
- *   y_t[n][oh][ow][o] = sum_c X_t[n][oh*s-p+u][ow*s-p+v][c] * W[o][u][v][c]
+ * Parallel binary 1x1 branches, each with its own real scale, summed (the
+ * module with P parallel branches of Figure 2, bottom), and the F x F binary
+ * convolution built from F*F such branches on shifted copies of the feature
+ * map (Section 4.2.1, last paragraph):
+ *   y_t[n][oh][ow][o] = sum_c X_t[n][oh*s-p+u][ow*s-p+v][c] * W[o][t][c]
  *   z[n][oh][ow][o]   = bias[o] + sum_t scale[t][o] * y_t[n][oh][ow][o]
  * evaluated in float32 as z = bias[o], then z = fma(scale[t][o], float(y_t), z)
  * for t = 0, 1, ... in this order (y_t is an exact integer).
+ *   branches        : number of branches.  kh = kw = 3: must be 9, branch
+ *                     t = u*kw + v reads the map shifted by (u, v).
+ *                     kh = kw = 1: any count from 1 to 1024, no shift (u = v = 0).
  *   x_packed        : device, packed activations.  Branch t reads the tensor at
  *                     x_packed + t * x_branch_stride (in uint32 words), each
  *                     [n][h][w][ceil(c_in/32)]: one binarisation per branch
  *                     (its own bias before the sign, bcnn_pack_bias).
  *                     x_branch_stride = 0: every branch reads the same tensor.
- *   w_packed        : device, packed weights [c_out][kh][kw][ceil(c_in/32)]
+ *   w_packed        : device, packed weights [c_out][branches][ceil(c_in/32)]
+ *                     (for 3x3 this is the layout [c_out][kh][kw][..] of the
+ *                     other calls)
  *   pad_mode        : BCNN_PAD_WORDS - a position outside the image stands for
  *                     the packed words pad_words[t][ceil(c_in/32)] (device; the
- *                     paper pads with 0 before the branch's bias, so the operand
+ *                     paper fills with 0 before the branch's bias, so the operand
  *                     is sign(bias_t[c]) per channel; tail bits 0); pad_words =
  *                     NULL means -1 in every channel.
  *                     BCNN_PAD_ZERO - a tap outside the image contributes
  *                     nothing to y_t (pad_words is ignored).
- *   scale           : device, float32 [kh*kw][c_out], finite
+ *   scale           : device, float32 [branches][c_out], finite
  *   bias            : device, float32 [c_out], or NULL for 0 (the sum of the
  *                     branches' batch-norm biases, and whatever the caller
  *                     folds in)
@@ -176,18 +180,18 @@ int bcnn_threshold_sign_pack(const int32_t *y, const int32_t *thr, int64_t rows,
  *   z_packed        : device, packed [n][h_out][w_out][ceil(c_out/32)],
  *                     bit = (z >= 0); must not alias x_packed.
  * Same shape limits and errors as bcnn_conv2d_binary; additionally
- * INVALID_ARG for an unknown pad_mode or a non-zero x_branch_stride smaller
- * than one tensor.
+ * INVALID_ARG for an unknown pad_mode, a branch count that does not fit the
+ * filter, or a non-zero x_branch_stride smaller than one tensor.
  */
 typedef enum { BCNN_PAD_WORDS = 0, BCNN_PAD_ZERO = 1 } bcnn_pad_mode;
 
-int bcnn_conv2d_binary_branches(const bcnn_conv_desc *desc, const uint32_t *x_packed,
-                                int64_t x_branch_stride, const uint32_t *w_packed,
+int bcnn_conv2d_binary_branches(const bcnn_conv_desc *desc, int32_t branches,
+                                const uint32_t *x_packed, int64_t x_branch_stride, const uint32_t *w_packed,
                                 const uint32_t *pad_words, int pad_mode, const float *scale,
                                 const float *bias, float *z, void *hip_stream);
 
-int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc *desc, const uint32_t *x_packed,
-                                          int64_t x_branch_stride, const uint32_t *w_packed,
+int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc *desc, int32_t branches,
+                                          const uint32_t *x_packed, int64_t x_branch_stride, const uint32_t *w_packed,
                                           const uint32_t *pad_words, int pad_mode, const float *scale,
                                           const float *bias, uint32_t *z_packed, void *hip_stream);
 

@@ -19,7 +19,10 @@
  *   y_t[n][oh][ow][o] = sum_c x_t[n][c][oh][ow] * w[o][c][u][v]
  *   z[n][oh][ow][o]   = sum_t ( g_t[o] * y_t + h_t[o] )
  *
- * with t = u*F + v, g/h the per-branch batch-norm scale and bias.  A padded
+ * with t = u*F + v, g/h the per-branch batch-norm scale and bias.  The module
+ * of Figure 2 (bottom) itself, P parallel binary 1x1 branches on the unshifted
+ * feature map, is the same sum with F = 1 and t = 0 .. P-1 (every branch reads
+ * position (oh*s, ow*s); nothing is ever outside the image).  A padded
  * position therefore is the constant sign(b_t[c]) per branch and channel, not
  * a zero operand.  Readings where the paper is silent: the stride is applied
  * by evaluating every branch at the output positions only; branches are
@@ -101,10 +104,14 @@ int oracle_branches_real(const float *a, const float *b, const int8_t *w,
 }
 
 /*
- * On binarised operands.  xb: [B][N][C][H][W] int8 +-1 with B = P (one tensor
+ * On binarised operands.  P is the number of branches: F*F for the shifted
+ * construction (branch t = u*F + v reads the map shifted by (u, v)), any
+ * P >= 1 when F = 1 (parallel branches, no shift); anything else returns -3.
+ * xb: [B][N][C][H][W] int8 +-1 with B = P (one tensor
  * per branch) or B = 1 (shared != 0: every branch reads the same tensor);
  * padv: [P][C] int8 from {-1, 0, +1}, the operand a tap outside the image
- * stands for;  w: [O][C][F][F] int8 +-1;  g: [P][O] float;  h: [O] float or
+ * stands for;  w: [O][C][P] int8 +-1 (for F > 1 this is [O][C][F][F]);
+ * g: [P][O] float;  h: [O] float or
  * NULL (= 0), the sum of the branches' biases;  outputs, each may be NULL:
  * z64 [N][Ho][Wo][O] double (exact products, double sums), z32 the float
  * fmaf chain described at the top, y_taps [N][Ho][Wo][O][P] int32 the
@@ -112,14 +119,15 @@ int oracle_branches_real(const float *a, const float *b, const int8_t *w,
  */
 int oracle_branches_pm1(const int8_t *xb, int shared, const int8_t *padv, const int8_t *w,
                         const float *g, const float *h,
-                        int N, int C, int H, int W, int O, int F, int stride, int pad,
+                        int N, int C, int H, int W, int O, int F, int P, int stride, int pad,
                         double *z64, float *z32, int32_t *y_taps)
 {
     const int Ho = oracle_out_dim(H, F, stride, pad);
     const int Wo = oracle_out_dim(W, F, stride, pad);
-    const int P = F * F;
     if (N < 1 || C < 1 || O < 1 || Ho < 1 || Wo < 1)
         return -1;
+    if (P < 1 || (F > 1 && P != F * F))
+        return -3;
     const size_t branch_elems = (size_t)N * C * H * W;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int n = 0; n < N; ++n)
@@ -129,25 +137,25 @@ int oracle_branches_pm1(const int8_t *xb, int shared, const int8_t *padv, const 
                     const size_t at = (((size_t)n * Ho + oh) * Wo + ow) * O + o;
                     double sum64 = h ? (double)h[o] : 0.0;
                     float sum32 = h ? h[o] : 0.0f;
-                    for (int u = 0; u < F; ++u)
-                        for (int v = 0; v < F; ++v) {
-                            const int t = u * F + v;
-                            const int ih = oh * stride - pad + u;
-                            const int iw = ow * stride - pad + v;
-                            const int inside = ih >= 0 && ih < H && iw >= 0 && iw < W;
-                            const int8_t *xt = xb + (shared ? 0 : (size_t)t * branch_elems);
-                            int32_t y = 0;
-                            for (int c = 0; c < C; ++c) {
-                                const int32_t xv = inside
-                                    ? (int32_t)xt[(((size_t)n * C + c) * H + ih) * W + iw]
-                                    : (int32_t)padv[(size_t)t * C + c];
-                                y += xv * (int32_t)w[(((size_t)o * C + c) * F + u) * F + v];
-                            }
-                            if (y_taps)
-                                y_taps[at * P + t] = y;
-                            sum64 += (double)g[(size_t)t * O + o] * (double)y;
-                            sum32 = fmaf(g[(size_t)t * O + o], (float)y, sum32);
+                    for (int t = 0; t < P; ++t) {
+                        const int u = (F > 1) ? t / F : 0;
+                        const int v = (F > 1) ? t % F : 0;
+                        const int ih = oh * stride - pad + u;
+                        const int iw = ow * stride - pad + v;
+                        const int inside = ih >= 0 && ih < H && iw >= 0 && iw < W;
+                        const int8_t *xt = xb + (shared ? 0 : (size_t)t * branch_elems);
+                        int32_t y = 0;
+                        for (int c = 0; c < C; ++c) {
+                            const int32_t xv = inside
+                                ? (int32_t)xt[(((size_t)n * C + c) * H + ih) * W + iw]
+                                : (int32_t)padv[(size_t)t * C + c];
+                            y += xv * (int32_t)w[((size_t)o * C + c) * P + t];
                         }
+                        if (y_taps)
+                            y_taps[at * P + t] = y;
+                        sum64 += (double)g[(size_t)t * O + o] * (double)y;
+                        sum32 = fmaf(g[(size_t)t * O + o], (float)y, sum32);
+                    }
                     if (z64)
                         z64[at] = sum64;
                     if (z32)

@@ -56,7 +56,7 @@ def _load():
     lib.oracle_sign_bias_f32.restype = None
     lib.oracle_branches_real.argtypes = [vp] * 5 + [i32] * 8 + [vp]
     lib.oracle_branches_real.restype = i32
-    lib.oracle_branches_pm1.argtypes = [vp, i32, vp, vp, vp, vp] + [i32] * 8 + [vp, vp, vp]
+    lib.oracle_branches_pm1.argtypes = [vp, i32, vp, vp, vp, vp] + [i32] * 9 + [vp, vp, vp]
     lib.oracle_branches_pm1.restype = i32
     _lib = lib
     return lib
@@ -193,14 +193,21 @@ def branches_real(a, b, w, g, h, stride=1, pad=0):
 
 def branches_pm1(xb, padv, w, g, h=None, stride=1, pad=0, taps=False):
     """The same on binarised operands.  xb [P,N,C,H,W] or [1,N,C,H,W] (shared by
-    all branches) +-1, padv [P,C] from {-1,0,+1}, w [O,C,F,F] +-1, g [P,O]
-    float32, h [O] float32 or None -> (z64, z32[, y_taps]) with z [N,Ho,Wo,O]
-    and y_taps [N,Ho,Wo,O,P] int32."""
+    all branches) +-1, padv [P,C] from {-1,0,+1}, g [P,O] float32, h [O] float32
+    or None.  w is [O,C,F,F] +-1 (shifted construction, P = F*F) or [O,C,P] (P
+    parallel 1x1 branches, no shift).  Returns (z64, z32[, y_taps]) with
+    z [N,Ho,Wo,O] and y_taps [N,Ho,Wo,O,P] int32."""
     xb = _pm1(xb, 5, "xb")
-    w = _pm1(w, 4, "w")
+    w = np.ascontiguousarray(w, dtype=np.int8)
     bcount, n, c, hh, ww = xb.shape
-    o, c2, f, f2 = w.shape
-    p = f * f
+    if w.ndim == 4:
+        o, c2, f, f2 = w.shape
+        p = f * f
+    elif w.ndim == 3:
+        o, c2, p = w.shape
+        f = f2 = 1
+    else:
+        raise ValueError("w must be [O,C,F,F] or [O,C,P]")
     padv = np.ascontiguousarray(padv, dtype=np.int8)
     g = np.ascontiguousarray(g, dtype=np.float32)
     if h is not None:
@@ -214,9 +221,10 @@ def branches_pm1(xb, padv, w, g, h=None, stride=1, pad=0, taps=False):
     z64 = np.empty(shape, dtype=np.float64)
     z32 = np.empty(shape, dtype=np.float32)
     yt = np.empty(shape + (p,), dtype=np.int32) if taps else None
-    rc = lib.oracle_branches_pm1(_ptr(xb), 1 if bcount == 1 else 0, _ptr(padv),
+    shared = 1 if (bcount == 1 and p > 1) else 0
+    rc = lib.oracle_branches_pm1(_ptr(xb), shared, _ptr(padv),
                                  _ptr(w), _ptr(g), _ptr(h) if h is not None else None,
-                                 n, c, hh, ww, o, f, stride, pad, _ptr(z64), _ptr(z32),
+                                 n, c, hh, ww, o, f, p, stride, pad, _ptr(z64), _ptr(z32),
                                  _ptr(yt) if taps else None)
     if rc != 0:
         raise ValueError("oracle_branches_pm1 failed: %d" % rc)

@@ -167,7 +167,8 @@ int bcnn_pack_bias(const void* src, int dtype, int64_t outer, int64_t channels, 
     return pack_entry(src, dtype, outer, channels, inner, bias, dst, hip_stream);
 }
 
-static int branches_entry(const bcnn_conv_desc* desc, const uint32_t* x, int64_t x_branch_stride,
+static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const uint32_t* x,
+                          int64_t x_branch_stride,
                           const uint32_t* w, const uint32_t* pad_words, int pad_mode,
                           const float* scale, const float* bias, void* out, bool fused, void* hip_stream)
 {
@@ -176,14 +177,17 @@ static int branches_entry(const bcnn_conv_desc* desc, const uint32_t* x, int64_t
     if (rc != BCNN_OK) return rc;
     if (!x || !w || !scale || !out) return BCNN_ERR_INVALID_ARG;
     if (pad_mode != BCNN_PAD_WORDS && pad_mode != BCNN_PAD_ZERO) return BCNN_ERR_INVALID_ARG;
+    if (branches < 1 || (s.ks > 1 && branches != s.ks * s.ks)) return BCNN_ERR_INVALID_ARG;
+    if (branches > 1024 || (int64_t)s.c_out * branches * s.cw > INT_MAX) return BCNN_ERR_UNSUPPORTED;
     const int64_t tensor_words = (int64_t)s.n * s.h * s.w * s.cw;
     if (x_branch_stride != 0 && x_branch_stride < tensor_words) return BCNN_ERR_INVALID_ARG;
-    if (x_branch_stride > INT_MAX) return BCNN_ERR_UNSUPPORTED;
+    if (x_branch_stride * branches > INT_MAX) return BCNN_ERR_UNSUPPORTED;
     if (static_cast<const void*>(x) == out) return BCNN_ERR_INVALID_ARG;
     if (!bcnn::aligned(x, 4) || !bcnn::aligned(w, 4) || !bcnn::aligned(scale, 4) || !bcnn::aligned(out, 4) ||
         (pad_words && !bcnn::aligned(pad_words, 4)) || (bias && !bcnn::aligned(bias, 4)))
         return BCNN_ERR_ALIGNMENT;
     bcnn::BranchArgs a;
+    a.branches = branches;
     a.x = x; a.x_branch_stride = x_branch_stride; a.w = w;
     a.pad_words = pad_mode == BCNN_PAD_WORDS ? pad_words : nullptr;
     a.zero_pad = pad_mode == BCNN_PAD_ZERO;
@@ -192,22 +196,22 @@ static int branches_entry(const bcnn_conv_desc* desc, const uint32_t* x, int64_t
     return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
 
-int bcnn_conv2d_binary_branches(const bcnn_conv_desc* desc, const uint32_t* x_packed,
+int bcnn_conv2d_binary_branches(const bcnn_conv_desc* desc, int32_t branches, const uint32_t* x_packed,
                                 int64_t x_branch_stride, const uint32_t* w_packed,
                                 const uint32_t* pad_words, int pad_mode, const float* scale,
                                 const float* bias, float* z, void* hip_stream)
 {
-    return branches_entry(desc, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale, bias, z,
-                          false, hip_stream);
+    return branches_entry(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale,
+                          bias, z, false, hip_stream);
 }
 
-int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc* desc, const uint32_t* x_packed,
-                                          int64_t x_branch_stride, const uint32_t* w_packed,
+int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc* desc, int32_t branches,
+                                          const uint32_t* x_packed, int64_t x_branch_stride, const uint32_t* w_packed,
                                           const uint32_t* pad_words, int pad_mode, const float* scale,
                                           const float* bias, uint32_t* z_packed, void* hip_stream)
 {
-    return branches_entry(desc, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale, bias,
-                          z_packed, true, hip_stream);
+    return branches_entry(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale,
+                          bias, z_packed, true, hip_stream);
 }
 
 int bcnn_conv2d_binary(const bcnn_conv_desc* desc, const uint32_t* x_packed,

@@ -37,14 +37,16 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
 bool conv_mfma_i8_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
 hipError_t launch_conv_mfma_i8(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                                const int32_t* thr, void* out, hipStream_t stream);
-// F x F convolution as F*F shifted 1x1 branches with per-branch real scales.
+// Parallel 1x1 branches with per-branch real scales; F x F convolution as F*F
+// shifted ones.
 struct BranchArgs {
+    int32_t branches;         // ks*ks (branch t reads the map shifted by tap t), or any count if ks == 1
     const uint32_t* x;        // packed activations, branch t at x + t * x_branch_stride
     int64_t x_branch_stride;  // in words; 0 = one tensor shared by all branches
-    const uint32_t* w;        // packed weights [c_out][taps][cw]
-    const uint32_t* pad_words;  // [taps][cw] operand of a tap outside the image, or nullptr (all -1)
+    const uint32_t* w;        // packed weights [c_out][branches][cw]
+    const uint32_t* pad_words;  // [branches][cw] operand of a tap outside the image, or nullptr (all -1)
     bool zero_pad;            // a tap outside the image contributes nothing
-    const float* scale;       // [taps][c_out]
+    const float* scale;       // [branches][c_out]
     const float* bias;        // [c_out] or nullptr
     void* out;                // float [m][c_out], or packed bits [m][cwo] when fused
     bool fused;

@@ -1,6 +1,7 @@
-// F x F binary convolution as F*F parallel shifted binary 1x1 convolutions,
-// each with its own real scale per output channel (BCNN paper, Section 4.2.1,
-// last paragraph, built on the parallel-branch module of Figure 2):
+// Parallel binary 1x1 branches, each with its own real scale per output channel,
+// summed (BCNN paper, Figure 2 bottom), and the F x F binary convolution built
+// from F*F such branches on shifted copies of the map (Section 4.2.1, last
+// paragraph):
 //   y_t = sum_c X_t[shifted by tap t][c] * W[o][t][c]        (integer, |y_t| <= c_in)
 //   z   = bias[o] + sum_t scale[t][o] * y_t                  (float)
 // evaluated as z = bias[o]; z = fma(scale[t][o], float(y_t), z) for t = 0, 1, ...
@@ -25,7 +26,7 @@ enum { PAD_MINUS = 0, PAD_WORDS = 1, PAD_SKIP = 2 };
 
 template <int TM, int VEC, int PADMODE, bool FUSED, bool FULL>
 __global__ __launch_bounds__(256) void conv_branches_kernel(
-    ConvShape s, int32_t n_mtiles, int32_t n_ctiles,
+    ConvShape s, int32_t taps, int32_t n_mtiles, int32_t n_ctiles,
     const uint32_t* __restrict__ x, int64_t x_branch_stride, const uint32_t* __restrict__ w,
     const uint32_t* __restrict__ pad_words, const float* __restrict__ scale,
     const float* __restrict__ bias, void* __restrict__ out)
@@ -83,12 +84,12 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
             for (int i = 0; i < TM; ++i) z[i][o] = 0.0f;
     }
 
-    const int taps = s.ks * s.ks;
-    const int c_in = s.k / taps;          // real channels: the K of one branch
+    // taps = branches: ks*ks shifted ones, or any number of unshifted ones when ks == 1
+    const int c_in = s.k / (s.ks * s.ks);  // real channels: the K of one branch
     const uint32_t wrow = (uint32_t)(taps * s.cw);
 
     for (int tap = 0; tap < taps; ++tap) {
-        const int u = tap / s.ks, v = tap - u * s.ks;
+        const int u = s.ks == 1 ? 0 : tap / s.ks, v = s.ks == 1 ? 0 : tap - u * s.ks;
         const uint32_t* xt = x + (size_t)tap * (size_t)x_branch_stride;
         const uint32_t* xp[TM];
         bool inb[TM];
@@ -212,7 +213,7 @@ hipError_t launch_mode(const ConvShape& s, const BranchArgs& a, hipStream_t stre
     const int64_t waves = (int64_t)n_ctiles * n_mtiles;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
     auto go = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, stream, s, n_mtiles, n_ctiles, a.x,
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, stream, s, a.branches, n_mtiles, n_ctiles, a.x,
                            a.x_branch_stride, a.w, a.pad_words, a.scale, a.bias, a.out);
     };
     const bool full = s.c_out >= TN;

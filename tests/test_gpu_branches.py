@@ -127,7 +127,8 @@ def make_case(seed, n, c, h, w, o, k, shared, grid):
 
 def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused):
     bcount, n, c, h, w = xb.shape
-    o, _, k, _ = wt.shape
+    o, k = wt.shape[0], (wt.shape[2] if wt.ndim == 4 else 1)
+    p = g.shape[0]
     desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
     ho, wo = B.out_shape(desc)
     cw = (c + 31) // 32
@@ -139,11 +140,11 @@ def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused):
     if fused:
         cwo = (o + 31) // 32
         out = Guarded(n * ho * wo * cwo, dev)
-        B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, xp, stride_words, wp, pw, mode, gt, ht, out.ptr),
+        B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr),
                 "branches_sign_pack")
         return out.get(np.uint32).reshape(n, ho * wo, cwo)
     out = Guarded(n * ho * wo * o, dev)
-    B.check(B.bcnn_conv2d_binary_branches(desc, xp, stride_words, wp, pw, mode, gt, ht, out.ptr), "branches")
+    B.check(B.bcnn_conv2d_binary_branches(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr), "branches")
     return out.get(np.float32).reshape(n, ho, wo, o)
 
 
@@ -195,6 +196,38 @@ def test_branches_match_oracle(dev, shape, mode, shared):
             assert np.any(z32 == 0) or z32.size < 20000, "grid case should produce exact zeros of z"
 
 
+PARALLEL_SHAPES = [
+    # n, c_in, h, w, c_out, P, stride   (1x1 branches on the unshifted map: Figure 2, bottom)
+    (2, 64, 14, 14, 64, 2, 1),
+    (1, 100, 9, 9, 70, 3, 1),
+    (3, 256, 7, 7, 96, 2, 2),
+    (2, 32, 28, 28, 32, 4, 1),
+    (1, 33, 5, 6, 5, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", PARALLEL_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("shared", [True, False], ids=["shared", "per_branch"])
+def test_parallel_branches_match_oracle(dev, shape, shared):
+    n, c, h, w, o, p, stride = shape
+    seed = 8800 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19))) + shared
+    for grid in (False, True):
+        xb = W.pm1(seed + 50 * grid, (1 if shared else p, n, c, h, w), 0.45)
+        wt = W.pm1(seed + 1, (o, c, p))
+        if grid:
+            g = W.uniform_f32(seed + 3, (p, o), -2.0, 2.0, steps=16)
+            hb = W.uniform_f32(seed + 4, (o,), -8.0, 8.0, steps=64)
+        else:
+            g = W.uniform_f32(seed + 3, (p, o), -1.5, 1.5)
+            hb = W.uniform_f32(seed + 4, (o,), -float(c), float(c))
+        padv = -np.ones((p, c), dtype=np.int8)
+        _, z32 = oracle.branches_pm1(xb, padv, wt, g, hb, stride, 0)
+        got = gpu_branches(dev, xb, wt, None, B.BCNN_PAD_WORDS, g, hb, stride, 0, fused=False)
+        assert np.array_equal(got, z32)
+        bits = gpu_branches(dev, xb, wt, None, B.BCNN_PAD_WORDS, g, hb, stride, 0, fused=True)
+        assert np.array_equal(bits, oracle_bits(z32))
+
+
 def test_null_bias_is_zero_and_unit_scales_give_the_integer_convolution(dev):
     n, c, h, w, o, k = 2, 96, 10, 9, 64, 3
     xb = W.pm1(9100, (1, n, c, h, w))
@@ -211,12 +244,14 @@ def test_branch_argument_checks(dev):
     w = torch.zeros((32 * 9 * 2,), dtype=torch.int32, device=dev)
     g = torch.zeros((9 * 32,), dtype=torch.float32, device=dev)
     z = torch.zeros((64 * 32,), dtype=torch.float32, device=dev)
-    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 7, g, None, z) == B.BCNN_ERR_INVALID_ARG
-    assert B.bcnn_conv2d_binary_branches(desc, x, 5, w, None, 0, g, None, z) == B.BCNN_ERR_INVALID_ARG
-    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, None, None, z) == B.BCNN_ERR_INVALID_ARG
-    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, g, None, None) == B.BCNN_ERR_INVALID_ARG
-    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, g.data_ptr() + 2, None, z) == B.BCNN_ERR_ALIGNMENT
-    assert B.bcnn_conv2d_binary_branches(desc, x, 0, w, None, 0, g, None, z) == B.BCNN_OK
+    assert B.bcnn_conv2d_binary_branches(desc, 9, x, 0, w, None, 7, g, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, 9, x, 5, w, None, 0, g, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, 9, x, 0, w, None, 0, None, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, 9, x, 0, w, None, 0, g, None, None) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, 9, x, 0, w, None, 0, g.data_ptr() + 2, None, z) == B.BCNN_ERR_ALIGNMENT
+    assert B.bcnn_conv2d_binary_branches(desc, 8, x, 0, w, None, 0, g, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, 0, x, 0, w, None, 0, g, None, z) == B.BCNN_ERR_INVALID_ARG
+    assert B.bcnn_conv2d_binary_branches(desc, 9, x, 0, w, None, 0, g, None, z) == B.BCNN_OK
     torch.cuda.synchronize()
 
 
@@ -242,8 +277,8 @@ def test_branches_full_size(dev, index):
     gt, ht = up(g, dev), up(hb, dev)
     z = torch.empty((cfg.n, ho, wo, cfg.c_out), dtype=torch.float32, device=dev)
     zp = torch.empty((cfg.n, ho * wo, cfg.c_out // 32), dtype=torch.int32, device=dev)
-    B.check(B.bcnn_conv2d_binary_branches(desc, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, z), "branches")
-    B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, zp), "fused")
+    B.check(B.bcnn_conv2d_binary_branches(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, z), "branches")
+    B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, zp), "fused")
     torch.cuda.synchronize()
     _, z32 = oracle.branches_pm1(x_all[picks][None], padv, wt, g, hb, cfg.stride, cfg.pad)
     got = z[picks].cpu().numpy()

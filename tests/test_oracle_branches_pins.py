@@ -181,6 +181,43 @@ def test_literal_evaluation_equals_the_binarised_one():
         assert np.allclose(z_real, z64 + hh.astype(np.float64).sum(axis=0), rtol=0, atol=1e-9)
 
 
+@pytest.mark.parametrize("p,stride", [(2, 1), (3, 2), (5, 1)])
+def test_parallel_branches_are_a_1x1_convolution_over_concatenated_channels(p, stride):
+    """P parallel 1x1 branches with unit scales: the branch tensors stacked
+    along the channel axis, convolved with the branch filters stacked the same
+    way (the plain binary convolution, pinned elsewhere); with real scales, a
+    library real-valued 1x1 convolution over the same stack."""
+    rng = np.random.default_rng(41 + p)
+    n, c, h, w, o = 2, 9, 5, 4, 6
+    xb = _rand_pm1(rng, (p, n, c, h, w))
+    wt = _rand_pm1(rng, (o, c, p))
+    padv = -np.ones((p, c), dtype=np.int8)
+    x_cat = np.concatenate([xb[t] for t in range(p)], axis=1)                 # [n, p*c, h, w]
+    w_cat = np.concatenate([wt[:, :, t] for t in range(p)], axis=1)[:, :, None, None]
+    y = oracle.conv2d_pm1(x_cat, w_cat, stride, 0)
+    z64, z32, yt = oracle.branches_pm1(xb, padv, wt, np.ones((p, o), dtype=np.float32), None, stride, 0, taps=True)
+    assert np.array_equal(z64, y.astype(np.float64)) and np.array_equal(z32, y.astype(np.float32))
+    assert yt.shape[-1] == p and np.array_equal(yt.sum(-1), y)
+    g = rng.normal(size=(p, o)).astype(np.float32)
+    hb = rng.normal(size=(o,)).astype(np.float32)
+    z64, _ = oracle.branches_pm1(xb, padv, wt, g, hb, stride, 0)
+    filt = np.concatenate([wt[:, :, t] * g[t].astype(np.float64)[:, None] for t in range(p)], axis=1)
+    want = F.conv2d(torch.from_numpy(x_cat.astype(np.float64)), torch.from_numpy(filt)[:, :, None, None],
+                    stride=stride) + torch.from_numpy(hb.astype(np.float64))[None, :, None, None]
+    assert np.allclose(z64, want.permute(0, 2, 3, 1).numpy(), rtol=0, atol=1e-9)
+    # a shared tensor: every branch reads the same pixels
+    zs, _ = oracle.branches_pm1(xb[:1], padv, wt, g, hb, stride, 0)
+    zr, _ = oracle.branches_pm1(np.repeat(xb[:1], p, axis=0), padv, wt, g, hb, stride, 0)
+    assert np.array_equal(zs, zr)
+
+
+def test_branch_count_must_fit_the_filter():
+    x = np.ones((1, 1, 2, 4, 4), dtype=np.int8)
+    with pytest.raises(ValueError):
+        oracle.branches_pm1(x, np.ones((9, 2), dtype=np.int8), np.ones((3, 2, 3, 3), dtype=np.int8),
+                            np.ones((8, 3), dtype=np.float32))
+
+
 # ----------------------------------------------------------- closed forms
 def test_closed_forms():
     rng = np.random.default_rng(23)
