@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     build,
     conv2d_pm1,
     conv2d_pm1_at,
+    module_epilogue,
     num_threads,
     out_dim,
     pack_channels,

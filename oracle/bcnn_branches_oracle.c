@@ -163,3 +163,43 @@ int oracle_branches_pm1(const int8_t *xb, int shared, const int8_t *padv, const 
                 }
     return 0;
 }
+
+/*
+ * What follows the binary convolution inside a convolution module (paper,
+ * Section 4.2.1, first paragraph): batch norm as a per-channel scale and bias,
+ * addition of the module's real identity path, PReLU with a learnable slope
+ * per channel.  y: [rows][O] int32 sums;  gamma, beta: [O];  identity:
+ * [rows][O] float or NULL (no identity path);  alpha: [O] or NULL (no
+ * activation).  Outputs, each may be NULL: r64 in double from the plain
+ * formula, r32 in float in this order of operations, one rounding each:
+ *   t = fmaf(gamma[o], (float)y, beta[o]);  t = t + identity;
+ *   r = (t >= 0) ? t : alpha[o] * t
+ * (a NaN t takes the alpha branch).  The binarisation for the next module is
+ * oracle_sign_bias_f32 on the stored r.
+ */
+void oracle_module_epilogue(const int32_t *y, const float *gamma, const float *beta,
+                            const float *identity, const float *alpha,
+                            int64_t rows, int O, double *r64, float *r32)
+{
+    for (int64_t m = 0; m < rows; ++m)
+        for (int o = 0; o < O; ++o) {
+            const size_t at = (size_t)m * O + o;
+            if (r64) {
+                double t = (double)gamma[o] * (double)y[at] + (double)beta[o];
+                if (identity)
+                    t += (double)identity[at];
+                r64[at] = (t >= 0.0 || !alpha) ? t : (double)alpha[o] * t;
+            }
+            if (r32) {
+                volatile float t = fmaf(gamma[o], (float)y[at], beta[o]);
+                if (identity)
+                    t = t + identity[at];
+                if (!(t >= 0.0f) && alpha) {
+                    volatile float a = alpha[o] * t;
+                    r32[at] = a;
+                } else {
+                    r32[at] = t;
+                }
+            }
+        }
+}

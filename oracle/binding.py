@@ -58,6 +58,8 @@ def _load():
     lib.oracle_branches_real.restype = i32
     lib.oracle_branches_pm1.argtypes = [vp, i32, vp, vp, vp, vp] + [i32] * 9 + [vp, vp, vp]
     lib.oracle_branches_pm1.restype = i32
+    lib.oracle_module_epilogue.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, vp]
+    lib.oracle_module_epilogue.restype = None
     _lib = lib
     return lib
 
@@ -229,3 +231,30 @@ def branches_pm1(xb, padv, w, g, h=None, stride=1, pad=0, taps=False):
     if rc != 0:
         raise ValueError("oracle_branches_pm1 failed: %d" % rc)
     return (z64, z32, yt) if taps else (z64, z32)
+
+
+def module_epilogue(y, gamma, beta, identity=None, alpha=None):
+    """Batch-norm scale and bias, identity addition, PReLU after a binary
+    convolution.  y [..., O] int32, gamma/beta/alpha [O] float32, identity
+    float32 of y's shape (or None) -> (r64, r32) of y's shape."""
+    y = np.ascontiguousarray(y, dtype=np.int32)
+    o = y.shape[-1]
+    gamma = np.ascontiguousarray(gamma, dtype=np.float32)
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    if gamma.shape != (o,) or beta.shape != (o,):
+        raise ValueError("gamma and beta must have one entry per output channel")
+    if identity is not None:
+        identity = np.ascontiguousarray(identity, dtype=np.float32)
+        if identity.shape != y.shape:
+            raise ValueError("identity must have the shape of y")
+    if alpha is not None:
+        alpha = np.ascontiguousarray(alpha, dtype=np.float32)
+        if alpha.shape != (o,):
+            raise ValueError("alpha must have one entry per output channel")
+    r64 = np.empty(y.shape, dtype=np.float64)
+    r32 = np.empty(y.shape, dtype=np.float32)
+    _load().oracle_module_epilogue(_ptr(y), _ptr(gamma), _ptr(beta),
+                                   _ptr(identity) if identity is not None else None,
+                                   _ptr(alpha) if alpha is not None else None,
+                                   y.size // o, o, _ptr(r64), _ptr(r32))
+    return r64, r32
