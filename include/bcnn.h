@@ -138,6 +138,39 @@ int bcnn_conv2d_binary_variant(const bcnn_conv_desc *desc, const uint32_t *x_pac
                                int variant, void *hip_stream);
 
 /*
+ * Binary convolution followed by the real-valued part of a convolution module
+ * (Section 4.2.1, first paragraph: batch norm as a per-channel scale and bias,
+ * addition of the module's real identity path, PReLU), and the binarisation
+ * the next module starts with (its bias, then sign).  Per output element, in
+ * float32 and in this order, one rounding per step:
+ *   t = fma(bn_scale[o], float(y), bn_bias[o])      y: the integer sum of
+ *   t = t + identity[m][o]                          bcnn_conv2d_binary
+ *   r = t >= 0 ? t : prelu_slope[o] * t
+ *   r is rounded to real_dtype and stored;  bit = (r_stored + next_bias[o] >= 0)
+ * All arrays are device memory.  identity == NULL: no identity path;
+ * prelu_slope == NULL: no activation; next_bias == NULL: 0.  identity and r
+ * are [n*h_out*w_out][c_out] of real_dtype (BCNN_F32 or BCNN_F16), i.e. the
+ * real stream in channel-last order; r may be the same buffer as identity
+ * (the stream is updated in place).
+ *   r             : device, real output, or NULL to skip it
+ *   x_next_packed : device, packed [n][h_out][w_out][ceil(c_out/32)], or NULL
+ *                   to skip it; at least one of the two outputs is required
+ *   variant       : BCNN_VARIANT_AUTO, _VALU or _MFMA_FP4; others UNSUPPORTED
+ */
+typedef struct {
+    const float *bn_scale;    /* [c_out] */
+    const float *bn_bias;     /* [c_out] */
+    const void *identity;     /* [m][c_out] of real_dtype, or NULL */
+    const float *prelu_slope; /* [c_out], or NULL */
+    const float *next_bias;   /* [c_out], or NULL */
+    int32_t real_dtype;       /* BCNN_F32 or BCNN_F16 */
+} bcnn_module_epilogue;
+
+int bcnn_conv2d_binary_module(const bcnn_conv_desc *desc, const uint32_t *x_packed,
+                              const uint32_t *w_packed, const bcnn_module_epilogue *ep, void *r,
+                              uint32_t *x_next_packed, int variant, void *hip_stream);
+
+/*
  * The epilogue alone (same decision as the fused call), for sums that are
  * already in memory:  y int32 [rows][c_out], thr int32 [c_out] ->
  * y_packed [rows][ceil(c_out/32)].

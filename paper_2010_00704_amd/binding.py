@@ -28,12 +28,18 @@ EXPORTS = (
     "bcnn_conv2d_binary_variant", "bcnn_threshold_sign_pack", "bcnn_out_dim",
     "bcnn_status_string", "bcnn_diag_copy_u32", "bcnn_diag_valu_peak",
     "bcnn_pack_bias", "bcnn_conv2d_binary_branches", "bcnn_conv2d_binary_branches_sign_pack",
+    "bcnn_conv2d_binary_module",
 )
 
 
 class bcnn_conv_desc(ctypes.Structure):
     _fields_ = [(name, ctypes.c_int32) for name in
                 ("n", "c_in", "h", "w", "c_out", "kh", "kw", "stride", "pad")]
+
+
+class bcnn_module_epilogue(ctypes.Structure):
+    _fields_ = [("bn_scale", ctypes.c_void_p), ("bn_bias", ctypes.c_void_p), ("identity", ctypes.c_void_p),
+                ("prelu_slope", ctypes.c_void_p), ("next_bias", ctypes.c_void_p), ("real_dtype", ctypes.c_int32)]
 
 
 class BcnnError(RuntimeError):
@@ -69,6 +75,8 @@ def lib():
         L.bcnn_pack_bias.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp]
         L.bcnn_conv2d_binary_branches.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, vp]
         L.bcnn_conv2d_binary_branches_sign_pack.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, vp]
+        L.bcnn_conv2d_binary_module.argtypes = [dp, vp, vp, ctypes.POINTER(bcnn_module_epilogue), vp, vp,
+                                                ctypes.c_int, vp]
         for name in EXPORTS:
             if name != "bcnn_status_string":
                 getattr(L, name).restype = ctypes.c_int
@@ -132,6 +140,15 @@ def bcnn_conv2d_binary_branches_sign_pack(desc, branches, x_packed, x_branch_str
         ctypes.byref(_desc(desc)), int(branches), _ptr(x_packed), int(x_branch_stride),
         _ptr(w_packed), _ptr(pad_words), int(pad_mode), _ptr(scale), _ptr(bias), _ptr(z_packed),
         _stream(stream))
+
+
+def bcnn_conv2d_binary_module(desc, x_packed, w_packed, bn_scale, bn_bias, identity, prelu_slope, next_bias,
+                              real_dtype, r, x_next_packed, variant=0, stream=None):
+    ep = bcnn_module_epilogue(_ptr(bn_scale), _ptr(bn_bias), _ptr(identity), _ptr(prelu_slope),
+                              _ptr(next_bias), int(real_dtype))
+    return lib().bcnn_conv2d_binary_module(ctypes.byref(_desc(desc)), _ptr(x_packed), _ptr(w_packed),
+                                           ctypes.byref(ep), _ptr(r), _ptr(x_next_packed), int(variant),
+                                           _stream(stream))
 
 
 def bcnn_conv2d_binary(desc, x_packed, w_packed, y, stream=None):

@@ -12,6 +12,8 @@ FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     # packed-fp32 instruction forms are kept out of all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # a*b + c is fused only where the source says fma: float results are part of the interface
+    "-ffp-contract=off",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

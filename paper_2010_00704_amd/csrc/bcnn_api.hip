@@ -90,19 +90,19 @@ int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w,
             // The matrix-core path wins wherever its 128 x 256 tiles are
             // reasonably full; small or ragged problems stay on the vector ALUs.
             if (conv_mfma_fp4_supported(s, x, w) && s.c_out >= 64 && s.m >= 1024)
-                e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, 0, st);
+                e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, nullptr, 0, st);
             else
-                e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, st);
+                e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, nullptr, st);
             break;
         case BCNN_VARIANT_VALU:
-            e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, st);
+            e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, nullptr, st);
             break;
         case BCNN_VARIANT_MFMA_FP4:
         case BCNN_VARIANT_MFMA_FP4_T4:
         case BCNN_VARIANT_MFMA_FP4_T7:
             if (!conv_mfma_fp4_supported(s, x, w)) return BCNN_ERR_UNSUPPORTED;
             if (variant == BCNN_VARIANT_MFMA_FP4_T7 && !fused) return BCNN_ERR_UNSUPPORTED;
-            e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out,
+            e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, nullptr,
                                      variant == BCNN_VARIANT_MFMA_FP4_T7 ? 7 : variant == BCNN_VARIANT_MFMA_FP4_T4 ? 4 : 0, st);
             break;
         case BCNN_VARIANT_MFMA_I8:
@@ -232,6 +232,52 @@ int bcnn_conv2d_binary_variant(const bcnn_conv_desc* desc, const uint32_t* x_pac
                                int variant, void* hip_stream)
 {
     return bcnn::conv_entry(desc, x_packed, w_packed, thr, thr != nullptr, out, variant, hip_stream);
+}
+
+int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_packed,
+                              const uint32_t* w_packed, const bcnn_module_epilogue* ep, void* r,
+                              uint32_t* x_next_packed, int variant, void* hip_stream)
+{
+    bcnn::ConvShape s;
+    const int rc = bcnn::make_shape(desc, &s);
+    if (rc != BCNN_OK) return rc;
+    if (!x_packed || !w_packed || !ep || !ep->bn_scale || !ep->bn_bias) return BCNN_ERR_INVALID_ARG;
+    if (!r && !x_next_packed) return BCNN_ERR_INVALID_ARG;
+    if (ep->real_dtype != BCNN_F32 && ep->real_dtype != BCNN_F16) return BCNN_ERR_UNSUPPORTED;
+    const uintptr_t esz = ep->real_dtype == BCNN_F32 ? 4 : 2;
+    if (static_cast<const void*>(x_packed) == static_cast<const void*>(x_next_packed) ||
+        static_cast<const void*>(x_packed) == r)
+        return BCNN_ERR_INVALID_ARG;
+    if (!bcnn::aligned(x_packed, 4) || !bcnn::aligned(w_packed, 4) || !bcnn::aligned(ep->bn_scale, 4) ||
+        !bcnn::aligned(ep->bn_bias, 4) || (ep->prelu_slope && !bcnn::aligned(ep->prelu_slope, 4)) ||
+        (ep->next_bias && !bcnn::aligned(ep->next_bias, 4)) || (ep->identity && !bcnn::aligned(ep->identity, esz)) ||
+        (r && !bcnn::aligned(r, esz)) || (x_next_packed && !bcnn::aligned(x_next_packed, 4)))
+        return BCNN_ERR_ALIGNMENT;
+    bcnn::ModuleEp m;
+    m.scale = ep->bn_scale; m.bias = ep->bn_bias; m.identity = ep->identity; m.slope = ep->prelu_slope;
+    m.next_bias = ep->next_bias; m.r = r; m.x_next = x_next_packed; m.half = ep->real_dtype == BCNN_F16;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e;
+    const bool mfma_ok = bcnn::conv_mfma_fp4_supported(s, x_packed, w_packed);
+    switch (variant) {
+        case BCNN_VARIANT_AUTO:
+            if (mfma_ok && s.c_out >= 64 && s.m >= 1024)
+                e = bcnn::launch_conv_mfma_fp4(s, x_packed, w_packed, nullptr, nullptr, &m, 0, st);
+            else
+                e = bcnn::launch_conv_valu(s, x_packed, w_packed, nullptr, nullptr, &m, st);
+            break;
+        case BCNN_VARIANT_VALU:
+            e = bcnn::launch_conv_valu(s, x_packed, w_packed, nullptr, nullptr, &m, st);
+            break;
+        case BCNN_VARIANT_MFMA_FP4:
+        case BCNN_VARIANT_MFMA_FP4_T4:
+            if (!mfma_ok) return BCNN_ERR_UNSUPPORTED;
+            e = bcnn::launch_conv_mfma_fp4(s, x_packed, w_packed, nullptr, nullptr, &m, 4, st);
+            break;
+        default:
+            return BCNN_ERR_UNSUPPORTED;
+    }
+    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
 
 int bcnn_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows, int64_t c_out,

@@ -20,19 +20,48 @@ struct ConvShape {
     int32_t k;              // c_in*ks*ks, the K of "dot = K - 2*popcount"
 };
 
+// Real-valued epilogue of a convolution module: batch-norm scale and bias,
+// identity addition, PReLU, then the next module's bias and sign.
+struct ModuleEp {
+    const float* scale;      // [c_out]
+    const float* bias;       // [c_out]
+    const void* identity;    // [m][c_out] float or half, or nullptr
+    const float* slope;      // [c_out] or nullptr (no activation)
+    const float* next_bias;  // [c_out] or nullptr (0)
+    void* r;                 // [m][c_out] float or half, or nullptr
+    uint32_t* x_next;        // [m][cwo] packed bits of sign(r + next_bias), or nullptr
+    int32_t half;            // identity and r are IEEE half instead of float
+};
+
+// One element of that epilogue: the order of operations is part of the
+// interface (one rounding per step: fma, add, multiply; then storage
+// rounding when the stream is half).  Returns the value as stored.
+template <bool HALF>
+__device__ __forceinline__ float module_value(float y, float g, float b, bool has_id, float idv,
+                                              bool has_slope, float a)
+{
+    float t = __builtin_fmaf(g, y, b);
+    if (has_id) t = t + idv;
+    if (has_slope) t = (t >= 0.0f) ? t : a * t;
+    if constexpr (HALF) t = (float)(_Float16)t;
+    return t;
+}
+
 // Launchers, one per kernel family.  Each returns the hipError_t of its launch.
 // bias: per-channel float added before the sign, or nullptr
 hipError_t launch_pack(const void* src, int dtype, const float* bias, int64_t outer, int64_t channels,
                        int64_t inner, uint32_t* dst, hipStream_t stream);
 hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows,
                                       int64_t c_out, uint32_t* y_packed, hipStream_t stream);
+// ep != nullptr: module epilogue (thr and out are ignored)
 hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_t* w,
-                            const int32_t* thr, void* out, hipStream_t stream);
+                            const int32_t* thr, void* out, const ModuleEp* ep, hipStream_t stream);
 // fp4 matrix-core variant; `supported` says whether it covers the shape/alignment.
 bool conv_mfma_fp4_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
 // tile: pixel blocks per wave, 4 or 7 (7 exists for the fused kernel only), 0 = choose
 hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
-                                const int32_t* thr, void* out, int tile, hipStream_t stream);
+                                const int32_t* thr, void* out, const ModuleEp* ep, int tile,
+                                hipStream_t stream);
 // int8 matrix-core variant (measurement arm, never chosen by AUTO)
 bool conv_mfma_i8_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
 hipError_t launch_conv_mfma_i8(const ConvShape& s, const uint32_t* x, const uint32_t* w,

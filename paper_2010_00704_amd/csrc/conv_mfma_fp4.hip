@@ -52,6 +52,8 @@
 // sign bits of a block, one cross-half exchange completes the 32-bit word.
 #include "bcnn_common.h"
 
+#include <type_traits>
+
 #include <utility>
 
 namespace bcnn {
@@ -108,11 +110,14 @@ struct MfmaArgs {
 };
 
 // PB = pixel blocks (of 32) per wave; the workgroup covers 2*32*PB pixels.
-template <int PB, bool FUSED, bool EVEN>
+enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3 };
+
+template <int PB, int OUT, bool EVEN>
 __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
-    const int32_t* __restrict__ thr, void* __restrict__ out)
+    const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep)
 {
+    constexpr bool FUSED = OUT == OUT_BITS;
     constexpr int WG_PX = 64 * PB;
     // One stage = the chunk's 8 K-words of every row of the tile, as 16-byte
     // units (4 words = one K-half of a row).  Unit order: [block of 32 rows]
@@ -501,19 +506,38 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
             }
         }
     } else {
-        // int32 sums.  In registers a lane holds 16 consecutive channels of one
-        // pixel, i.e. 64-byte pieces 1 KB apart: poor store granularity.  Each
-        // wave therefore transposes its 32 pixels x 64 channels of a pixel
-        // block through its own 8.5 KB of LDS (the stages are free now) and
-        // writes 256 contiguous bytes per pixel, four pixels per instruction.
+        // int32 sums, or the module's real-valued epilogue.  In registers a lane
+        // holds 16 consecutive channels of one pixel, i.e. 64-byte pieces 1 KB
+        // apart: poor store granularity.  Each wave therefore transposes its 32
+        // pixels x 64 channels of a pixel block through its own 8.5 KB of LDS
+        // (the stages are free now); afterwards a lane holds 4 consecutive
+        // channels of a pixel, 16 lanes one pixel's 64 channels, and a store
+        // instruction writes 256 contiguous bytes per pixel, four pixels at a time.
+        constexpr bool MODULE = OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16;
+        constexpr bool HALF = OUT == OUT_MODULE_F16;
         int32_t* y = static_cast<int32_t*>(out);
         constexpr int ROW_WORDS = 64 + 4;                      // padded row: 64 channels
         static_assert(4 * 32 * ROW_WORDS * 4 <= 3 * STAGE_BYTES, "transpose tiles must fit the stages");
         __syncthreads();                                       // every wave is done with the stages
         int32_t* tile = reinterpret_cast<int32_t*>(stage) + wave * (32 * ROW_WORDS);
-        const bool vec_ok = (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0);
         const int cgrp = lane & 15;                            // 4-channel group within the wave's 64
         const int prow = lane >> 4;                            // pixel row within a group of four
+        const int c0 = o0 + 64 * wc + 4 * cgrp;                // this lane's first channel after the transpose
+        const bool vec_ok = (s.c_out % 4 == 0) &&
+                            ((reinterpret_cast<uintptr_t>(MODULE ? ep.r : out) & (HALF ? 7 : 15)) == 0) &&
+                            (!MODULE || (reinterpret_cast<uintptr_t>(ep.identity) & (HALF ? 7 : 15)) == 0);
+        // per-channel parameters of the lane's four channels (clamped loads for a ragged c_out)
+        float pg[4], pb_[4], pa[4], pc[4];
+        if constexpr (MODULE) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int ch = c0 + k < s.c_out ? c0 + k : s.c_out - 1;
+                pg[k] = ep.scale[ch];
+                pb_[k] = ep.bias[ch];
+                pa[k] = ep.slope ? ep.slope[ch] : 1.0f;
+                pc[k] = ep.next_bias ? ep.next_bias[ch] : 0.0f;
+            }
+        }
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
 #pragma unroll
@@ -533,34 +557,85 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
                 const int px = 4 * g + prow;
                 const int4 q = *reinterpret_cast<const int4*>(tile + px * ROW_WORDS + 4 * cgrp);
                 const int m = m0 + 32 * (PB * wp + pb) + px;
-                const int c0 = o0 + 64 * wc + 4 * cgrp;
-                if (m < s.m) {
-                    int32_t* dstp = y + (size_t)m * s.c_out + c0;
-                    if (vec_ok && c0 + 4 <= s.c_out) {
-                        *reinterpret_cast<int4*>(dstp) = q;
-                    } else {
-                        if (c0 + 0 < s.c_out) dstp[0] = q.x;
-                        if (c0 + 1 < s.c_out) dstp[1] = q.y;
-                        if (c0 + 2 < s.c_out) dstp[2] = q.z;
-                        if (c0 + 3 < s.c_out) dstp[3] = q.w;
+                const bool row_ok = m < s.m;
+                if constexpr (!MODULE) {
+                    if (row_ok) {
+                        int32_t* dstp = y + (size_t)m * s.c_out + c0;
+                        if (vec_ok && c0 + 4 <= s.c_out) {
+                            *reinterpret_cast<int4*>(dstp) = q;
+                        } else {
+                            if (c0 + 0 < s.c_out) dstp[0] = q.x;
+                            if (c0 + 1 < s.c_out) dstp[1] = q.y;
+                            if (c0 + 2 < s.c_out) dstp[2] = q.z;
+                            if (c0 + 3 < s.c_out) dstp[3] = q.w;
+                        }
                     }
+                } else {
+                    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+                    typedef real_t real4 __attribute__((ext_vector_type(4)));
+                    const size_t at = (size_t)m * s.c_out + c0;
+                    const real_t* idp = static_cast<const real_t*>(ep.identity) + at;
+                    real_t* rp = static_cast<real_t*>(ep.r) + at;
+                    const bool whole = vec_ok && c0 + 4 <= s.c_out;
+                    const int qv[4] = {q.x, q.y, q.z, q.w};
+                    float idv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                    if (ep.identity && row_ok) {
+                        if (whole) {
+                            const real4 t4 = *reinterpret_cast<const real4*>(idp);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) idv[k] = (float)t4[k];
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k)
+                                if (c0 + k < s.c_out) idv[k] = (float)idp[k];
+                        }
+                    }
+                    float v[4];
+                    uint32_t nib = 0;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        v[k] = module_value<HALF>((float)qv[k], pg[k], pb_[k], ep.identity != nullptr, idv[k],
+                                                  ep.slope != nullptr, pa[k]);
+                        nib |= (uint32_t)(c0 + k < s.c_out && v[k] + pc[k] >= 0.0f) << k;
+                    }
+                    if (ep.r && row_ok) {
+                        if (whole) {
+                            real4 t4;
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) t4[k] = (real_t)v[k];
+                            *reinterpret_cast<real4*>(rp) = t4;
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k)
+                                if (c0 + k < s.c_out) rp[k] = (real_t)v[k];
+                        }
+                    }
+                    // eight neighbouring lanes hold the 32 channels of one packed word
+                    uint32_t wd = nib << (4 * (cgrp & 7));
+                    wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+                    wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+                    wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x141, 0xF, 0xF, true);  // row_half_mirror
+                    const int wi = ((o0 + 64 * wc) >> 5) + (cgrp >> 3);
+                    if (ep.x_next && row_ok && (cgrp & 7) == 0 && wi < s.cwo)
+                        ep.x_next[(size_t)m * s.cwo + wi] = wd;
                 }
             }
         }
     }
 }
 
-template <int PB, bool FUSED>
+template <int PB, int OUT>
 hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int32_t* thr,
-                     void* out, hipStream_t stream)
+                     void* out, const ModuleEp* ep, hipStream_t stream)
 {
+    const ModuleEp e = ep ? *ep : ModuleEp{};
     constexpr int WG_PX = 64 * PB;
     a.n_ptiles = (a.s.m + WG_PX - 1) / WG_PX;
     const unsigned blocks = (unsigned)(a.n_ptiles * a.n_ctiles);
     if (a.units_per_tap % 2 == 0)
-        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, FUSED, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out);
+        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e);
     else
-        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, FUSED, false>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out);
+        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, false>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e);
     return hipGetLastError();
 }
 
@@ -591,7 +666,8 @@ static double tile_cost(const ConvShape& s, int pb)
 }
 
 hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
-                                const int32_t* thr, void* out, int tile, hipStream_t stream)
+                                const int32_t* thr, void* out, const ModuleEp* ep, int tile,
+                                hipStream_t stream)
 {
     MfmaArgs a;
     a.s = s;
@@ -612,10 +688,12 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     // ends).  Only the fused kernel has the registers for it: the int32
     // epilogue of a 2 x 7 tile would spill.
     // `tile` = 4 or 7 forces a tile (for tests and measurements), 0 chooses.
-    if (!thr) return launch_pb<4, false>(a, x, w, thr, out, stream);
+    if (ep && ep->half) return launch_pb<4, OUT_MODULE_F16>(a, x, w, nullptr, nullptr, ep, stream);
+    if (ep) return launch_pb<4, OUT_MODULE_F32>(a, x, w, nullptr, nullptr, ep, stream);
+    if (!thr) return launch_pb<4, OUT_I32>(a, x, w, thr, out, nullptr, stream);
     if (tile == 7 || (tile == 0 && a.n_chunks >= 20 && tile_cost(s, 7) < tile_cost(s, 4)))
-        return launch_pb<7, true>(a, x, w, thr, out, stream);
-    return launch_pb<4, true>(a, x, w, thr, out, stream);
+        return launch_pb<7, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
+    return launch_pb<4, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
 }
 
 }  // namespace bcnn

@@ -39,12 +39,44 @@ __device__ __forceinline__ void load_words(const uint32_t* p, bool ok, uint32_t 
     }
 }
 
-template <int TM, int VEC, bool FUSED>
+enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3 };
+
+// Module epilogue for one pixel of a lane: 32 channels starting at o0.
+template <bool HALF>
+__device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp& ep, int m, int o0, int ctile,
+                                             const int32_t (&acc)[TN])
+{
+    const int o_last = s.c_out - 1;
+    const size_t row = (size_t)m * s.c_out + o0;
+    uint32_t word = 0;
+#pragma unroll
+    for (int o = 0; o < TN; ++o) {
+        const bool real = o0 + o <= o_last;
+        const int oc = real ? (o0 + o) : o_last;
+        float idv = 0.0f;
+        if (ep.identity && real)
+            idv = HALF ? (float)static_cast<const _Float16*>(ep.identity)[row + o]
+                       : static_cast<const float*>(ep.identity)[row + o];
+        const float v = module_value<HALF>((float)(s.k - 2 * acc[o]), ep.scale[oc], ep.bias[oc],
+                                           ep.identity != nullptr, idv, ep.slope != nullptr,
+                                           ep.slope ? ep.slope[oc] : 1.0f);
+        if (ep.r && real) {
+            if constexpr (HALF) static_cast<_Float16*>(ep.r)[row + o] = (_Float16)v;
+            else static_cast<float*>(ep.r)[row + o] = v;
+        }
+        const float c = ep.next_bias ? ep.next_bias[oc] : 0.0f;
+        word |= (uint32_t)(real && (v + c >= 0.0f)) << o;
+    }
+    if (ep.x_next) ep.x_next[(size_t)m * s.cwo + ctile] = word;
+}
+
+template <int TM, int VEC, int OUT>
 __global__ __launch_bounds__(256) void conv_valu_kernel(
     ConvShape s, int32_t n_mtiles, int32_t n_ctiles,
     const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
-    const int32_t* __restrict__ thr, void* __restrict__ out)
+    const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep)
 {
+    constexpr bool FUSED = OUT == OUT_BITS;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * 4 + wave;
@@ -122,7 +154,12 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
 
     // Epilogue.  dot = K - 2*popcount; padding needs no correction because
     // padded taps were real all-zero words.
-    if constexpr (FUSED) {
+    if constexpr (OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            if (live[i])
+                module_store<OUT == OUT_MODULE_F16>(s, ep, mtile * (64 * TM) + i * 64 + lane, o0, ctile, acc[i]);
+    } else if constexpr (FUSED) {
         uint32_t* yp = static_cast<uint32_t*>(out);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -168,42 +205,49 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
 
 template <int TM, int VEC>
 hipError_t launch_tm_vec(const ConvShape& s, const uint32_t* x, const uint32_t* w,
-                         const int32_t* thr, void* out, hipStream_t stream)
+                         const int32_t* thr, void* out, const ModuleEp* ep, hipStream_t stream)
 {
     const int n_ctiles = (s.c_out + TN - 1) / TN;
     const int n_mtiles = (s.m + 64 * TM - 1) / (64 * TM);
     const int64_t waves = (int64_t)n_ctiles * n_mtiles;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
-    if (thr)
-        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, true>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, x, w, thr, out);
+    const ModuleEp none = {};
+    if (ep && ep->half)
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_MODULE_F16>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out, *ep);
+    else if (ep)
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_MODULE_F32>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out, *ep);
+    else if (thr)
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_BITS>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out, none);
     else
-        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, false>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, x, w, thr, out);
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_I32>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out, none);
     return hipGetLastError();
 }
 
 template <int TM>
 hipError_t launch_tm(const ConvShape& s, const uint32_t* x, const uint32_t* w, const int32_t* thr,
-                     void* out, hipStream_t stream)
+                     void* out, const ModuleEp* ep, hipStream_t stream)
 {
     const uintptr_t bits = reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w);
-    if (s.cw % 4 == 0 && (bits & 15) == 0) return launch_tm_vec<TM, 4>(s, x, w, thr, out, stream);
-    if (s.cw % 2 == 0 && (bits & 7) == 0) return launch_tm_vec<TM, 2>(s, x, w, thr, out, stream);
-    return launch_tm_vec<TM, 1>(s, x, w, thr, out, stream);
+    if (s.cw % 4 == 0 && (bits & 15) == 0) return launch_tm_vec<TM, 4>(s, x, w, thr, out, ep, stream);
+    if (s.cw % 2 == 0 && (bits & 7) == 0) return launch_tm_vec<TM, 2>(s, x, w, thr, out, ep, stream);
+    return launch_tm_vec<TM, 1>(s, x, w, thr, out, ep, stream);
 }
 
 }  // namespace
 
 hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_t* w,
-                            const int32_t* thr, void* out, hipStream_t stream)
+                            const int32_t* thr, void* out, const ModuleEp* ep, hipStream_t stream)
 {
     // Two pixels per lane halve the scalar weight traffic per popcount; one
     // pixel per lane gives twice as many waves, which small problems need to
     // cover 1024 SIMDs.
     const int64_t waves2 = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 127) / 128);
-    if (waves2 >= 2048) return launch_tm<2>(s, x, w, thr, out, stream);
-    return launch_tm<1>(s, x, w, thr, out, stream);
+    if (waves2 >= 2048) return launch_tm<2>(s, x, w, thr, out, ep, stream);
+    return launch_tm<1>(s, x, w, thr, out, ep, stream);
 }
 
 }  // namespace bcnn

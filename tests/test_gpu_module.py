@@ -1,0 +1,230 @@
+"""Parity of the convolution-module call (binary convolution, batch-norm scale
+and bias, identity addition, PReLU, next module's bias and sign; paper, Section
+4.2.1, first paragraph) with the CPU oracle on a real MI355X.
+
+The library evaluates the real-valued part in float32 in a fixed order of
+operations (fma, add, multiply, storage rounding), the same the oracle's float
+result follows, so the real stream is compared for equality and the packed
+bits bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2010_00704_amd import binding as B
+from paper_2010_00704_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 64
+SENTINEL = 0x5A5A5A5A
+VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4]
+VARIANT_IDS = ["auto", "valu", "mfma_fp4"]
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    B.lib()
+    return torch.device("cuda:0")
+
+
+class Guarded:
+    """Device bytes between sentinel bands; `nbytes` is rounded up to words."""
+
+    def __init__(self, nbytes, dev):
+        self.words = (int(nbytes) + 3) // 4
+        self.buf = torch.full((self.words + 2 * GUARD,), SENTINEL, dtype=torch.int32, device=dev)
+
+    @property
+    def ptr(self):
+        return self.buf.data_ptr() + 4 * GUARD
+
+    def put(self, a):
+        flat = torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1))
+        self.buf.view(torch.uint8)[4 * GUARD:4 * GUARD + flat.numel()] = flat.to(self.buf.device)
+
+    def get(self, dtype, count):
+        torch.cuda.synchronize()
+        host = self.buf.cpu().numpy()
+        assert np.all(host[:GUARD] == SENTINEL), "write before the output buffer"
+        assert np.all(host[GUARD + self.words:] == SENTINEL), "write past the output buffer"
+        return host[GUARD:GUARD + self.words].view(dtype)[:count]
+
+
+def up(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def i32(a):
+    return np.ascontiguousarray(a).view(np.int32)
+
+
+def oracle_module(x, wt, stride, pad, g, b, ident, alpha, c, half):
+    y = oracle.conv2d_pm1(x, wt, stride, pad)
+    n, ho, wo, o = y.shape
+    ident32 = None if ident is None else ident.astype(np.float32).reshape(y.shape)
+    _, r32 = oracle.module_epilogue(y, g, b, ident32, alpha)
+    stored = r32.astype(np.float16) if half else r32
+    cc = c if c is not None else np.zeros(o, dtype=np.float32)
+    s = oracle.sign_bias_f32(stored.astype(np.float32).reshape(n * ho * wo, o, 1), cc)
+    bits = oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))
+    return stored.reshape(n * ho * wo, o), bits
+
+
+def make_params(seed, m, o, half, grid):
+    if grid:   # quarters: exact float arithmetic, so r + c hits 0 exactly now and then
+        g = W.uniform_f32(seed, (o,), -2.0, 2.0, steps=16)
+        b = W.uniform_f32(seed + 1, (o,), -8.0, 8.0, steps=64)
+        ident = W.uniform_f32(seed + 2, (m, o), -16.0, 16.0, steps=128)
+        alpha = W.uniform_f32(seed + 3, (o,), 0.0, 1.0, steps=4)
+        c = W.uniform_f32(seed + 4, (o,), -4.0, 4.0, steps=32)
+    else:
+        g = W.uniform_f32(seed, (o,), -1.5, 1.5)
+        b = W.uniform_f32(seed + 1, (o,), -30.0, 30.0)
+        ident = W.uniform_f32(seed + 2, (m, o), -40.0, 40.0)
+        alpha = W.uniform_f32(seed + 3, (o,), 0.05, 0.5)
+        c = W.uniform_f32(seed + 4, (o,), -10.0, 10.0)
+    if half:
+        ident = ident.astype(np.float16)
+    return g, b, ident, alpha, c
+
+
+def gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant, want_r=True, want_bits=True,
+               in_place=False):
+    n, cin, h, w = x.shape
+    o, _, k, _ = wt.shape
+    desc = B.conv_desc(n, cin, h, w, o, k, stride, pad)
+    ho, wo = B.out_shape(desc)
+    m = n * ho * wo
+    xp = up(i32(oracle.pack_channels(x.reshape(n, cin, -1))), dev)
+    wp = up(i32(oracle.pack_channels(wt.reshape(o, cin, -1))), dev)
+    esz = 2 if half else 4
+    rbuf = Guarded(m * o * esz, dev)
+    idt = None
+    if ident is not None:
+        if in_place:
+            rbuf.put(ident)
+            idt = rbuf.ptr
+        else:
+            idt = up(ident, dev)
+    cwo = (o + 31) // 32
+    bits = Guarded(m * cwo * 4, dev)
+    rc = B.bcnn_conv2d_binary_module(
+        desc, xp, wp, up(g, dev), up(b, dev), idt, up(alpha, dev) if alpha is not None else None,
+        up(c, dev) if c is not None else None, B.BCNN_F16 if half else B.BCNN_F32,
+        rbuf.ptr if want_r else None, bits.ptr if want_bits else None, variant)
+    if rc == B.BCNN_ERR_UNSUPPORTED:
+        pytest.skip("variant does not cover this shape")
+    B.check(rc, "module")
+    r = rbuf.get(np.float16 if half else np.float32, m * o).reshape(m, o) if want_r else None
+    xb = bits.get(np.uint32, m * cwo).reshape(n, ho * wo, cwo) if want_bits else None
+    return r, xb
+
+
+MODULE_SHAPES = [
+    # n, c_in, h, w, c_out, k, stride, pad
+    (2, 128, 24, 24, 128, 1, 1, 0),    # the paper's 1x1 module, matrix-core path
+    (1, 256, 33, 31, 64, 1, 1, 0),
+    (2, 128, 23, 23, 192, 3, 1, 1),
+    (3, 256, 20, 20, 100, 3, 2, 1),    # ragged c_out on the matrix-core path
+    (1, 128, 40, 40, 70, 1, 2, 0),
+    (2, 64, 14, 14, 64, 1, 1, 0),      # vector-ALU path
+    (3, 33, 9, 7, 40, 3, 1, 1),
+    (1, 100, 12, 12, 7, 1, 1, 0),
+    (40, 96, 14, 14, 96, 3, 1, 1),     # two pixels per lane on the vector-ALU path
+]
+
+
+@pytest.mark.parametrize("shape", MODULE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_module_matches_oracle(dev, shape, variant, half):
+    n, cin, h, w, o, k, stride, pad = shape
+    seed = 9500 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23))) + half
+    x = W.pm1(seed, (n, cin, h, w), 0.45)
+    wt = W.pm1(seed + 1, (o, cin, k, k))
+    ho = (h + 2 * pad - k) // stride + 1
+    wo = (w + 2 * pad - k) // stride + 1
+    m = n * ho * wo
+    for grid in (False, True):
+        g, b, ident, alpha, c = make_params(seed + 10 + 100 * grid, m, o, half, grid)
+        want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident, alpha, c, half)
+        r, bits = gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant)
+        assert np.array_equal(r, want_r)
+        assert np.array_equal(bits, want_bits)
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_module_optional_parts(dev, variant, half):
+    shape = (2, 128, 24, 24, 128, 1, 1, 0) if variant != B.BCNN_VARIANT_VALU else (2, 64, 10, 10, 70, 3, 1, 1)
+    n, cin, h, w, o, k, stride, pad = shape
+    x = W.pm1(9901, (n, cin, h, w))
+    wt = W.pm1(9902, (o, cin, k, k))
+    ho = (h + 2 * pad - k) // stride + 1
+    wo = (w + 2 * pad - k) // stride + 1
+    m = n * ho * wo
+    g, b, ident, alpha, c = make_params(9903, m, o, half, True)
+    # no identity, no activation, no next bias
+    want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, None, None, None, half)
+    r, bits = gpu_module(dev, x, wt, stride, pad, g, b, None, None, None, half, variant)
+    assert np.array_equal(r, want_r) and np.array_equal(bits, want_bits)
+    # each output alone, and the stream updated in place
+    want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident, alpha, c, half)
+    r, _ = gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant, want_bits=False)
+    assert np.array_equal(r, want_r)
+    _, bits = gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant, want_r=False)
+    assert np.array_equal(bits, want_bits)
+    r, bits = gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant, in_place=True)
+    assert np.array_equal(r, want_r) and np.array_equal(bits, want_bits)
+
+
+def test_module_argument_checks(dev):
+    desc = B.conv_desc(1, 64, 8, 8, 32, 1, 1, 0)
+    x = torch.zeros((64 * 2,), dtype=torch.int32, device=dev)
+    w = torch.zeros((32 * 2,), dtype=torch.int32, device=dev)
+    g = torch.ones((32,), dtype=torch.float32, device=dev)
+    r = torch.zeros((64 * 32,), dtype=torch.float32, device=dev)
+    bits = torch.zeros((64,), dtype=torch.int32, device=dev)
+    f = B.bcnn_conv2d_binary_module
+    assert f(desc, x, w, g, g, None, None, None, B.BCNN_F32, None, None) == B.BCNN_ERR_INVALID_ARG
+    assert f(desc, x, w, None, g, None, None, None, B.BCNN_F32, r, bits) == B.BCNN_ERR_INVALID_ARG
+    assert f(desc, x, w, g, g, None, None, None, B.BCNN_I8, r, bits) == B.BCNN_ERR_UNSUPPORTED
+    assert f(desc, x, w, g, g, None, None, None, B.BCNN_F32, r, x) == B.BCNN_ERR_INVALID_ARG
+    assert f(desc, x, w, g, g, None, None, None, B.BCNN_F32, r.data_ptr() + 2, bits) == B.BCNN_ERR_ALIGNMENT
+    assert f(desc, x, w, g, g, None, None, None, B.BCNN_F32, r, bits, B.BCNN_VARIANT_MFMA_I8) == B.BCNN_ERR_UNSUPPORTED
+    assert f(desc, x, w, g, g, None, None, None, B.BCNN_F32, r, bits) == B.BCNN_OK
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_module_full_size_1x1(dev, half):
+    """The 1x1 benchmark shape as the paper's module (256 -> 256 channels, 56x56,
+    batch 32, identity path included), launched at full size; the oracle
+    evaluates the first, middle and last image."""
+    cfg = W.CONFIGS[1]
+    picks = [0, cfg.n // 2, cfg.n - 1]
+    _, x_all, ws, _ = W.make_inputs(2)
+    wt = ws[0]
+    hw = cfg.h * cfg.w
+    m = cfg.n * hw
+    g, b, _, alpha, c = make_params(9950, 1, cfg.c_out, half, False)
+    ident = W.uniform_f32(9960, (m, cfg.c_out), -40.0, 40.0)
+    if half:
+        ident = ident.astype(np.float16)
+    desc = B.conv_desc(cfg.n, cfg.c_in, cfg.h, cfg.w, cfg.c_out, cfg.k, cfg.stride, cfg.pad)
+    xp = B.pack_nchw(up(x_all, dev))
+    wp = B.pack_nchw(up(wt, dev))
+    stream_t = up(ident, dev)                 # updated in place
+    bits = torch.empty((cfg.n, hw, cfg.c_out // 32), dtype=torch.int32, device=dev)
+    B.check(B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), stream_t, up(alpha, dev), up(c, dev),
+                                        B.BCNN_F16 if half else B.BCNN_F32, stream_t, bits), "module")
+    torch.cuda.synchronize()
+    got_r = stream_t.cpu().numpy().reshape(cfg.n, hw, cfg.c_out)[picks]
+    got_bits = bits.cpu().numpy().view(np.uint32)[picks]
+    id_pick = ident.reshape(cfg.n, hw, cfg.c_out)[picks].reshape(-1, cfg.c_out)
+    want_r, want_bits = oracle_module(x_all[picks], wt, cfg.stride, cfg.pad, g, b, id_pick, alpha, c, half)
+    assert np.array_equal(got_r.reshape(-1, cfg.c_out), want_r)
+    assert np.array_equal(got_bits, want_bits)
