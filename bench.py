@@ -361,6 +361,35 @@ def aux_measurements(torch, B, dev, work):
         tb = W.binary_ops(cfg) / cfg.layers / (ms * 1e-3) / 1e12
         out["branches"].append({"name": cfg.name, "ms": round(ms, 4), "tbops": round(tb, 1),
                                 "frac_valu_peak": round(tb / VALU_PEAK_TBOPS, 4)})
+
+    # convolution module (1x1 binary convolution + batch norm + identity + PReLU -> real stream in place,
+    # + next bias, sign, pack) on the 1x1 shape; HBM bound: real stream read + written per element
+    wk = work[1]
+    cfg, d = wk["cfg"], wk["descs"][0]
+    m_rows = cfg.n * cfg.h * cfg.w
+    par = [torch.from_numpy(W.uniform_f32(4400 + k, (cfg.c_out,), lo, hi)).to(dev)
+           for k, (lo, hi) in enumerate([(-1.5, 1.5), (-30.0, 30.0), (0.05, 0.5), (-10.0, 10.0)])]
+    xn = torch.empty((cfg.n, cfg.h * cfg.w, cfg.c_out // 32), dtype=torch.int32, device=dev)
+    out["module_1x1"] = []
+    for name, tdt, code, esz in (("f32", torch.float32, B.BCNN_F32, 4), ("f16", torch.float16, B.BCNN_F16, 2)):
+        streams = [(torch.rand((m_rows, cfg.c_out), device=dev) * 80 - 40).to(tdt) for _ in range(4)]
+        for st in streams:
+            B.check(B.bcnn_conv2d_binary_module(d, wk["xp"], wk["wps"][0], par[0], par[1], st, par[2], par[3],
+                                                code, st, xn), "module")
+        a, b = ev(), ev()
+        a.record()
+        for r in range(reps):
+            st = streams[r % 4]
+            B.check(B.bcnn_conv2d_binary_module(d, wk["xp"], wk["wps"][0], par[0], par[1], st, par[2], par[3],
+                                                code, st, xn), "module")
+        b.record()
+        b.synchronize()
+        ms = a.elapsed_time(b) / reps
+        nbytes = 2 * m_rows * cfg.c_out * esz + wk["xp"].numel() * 4 + xn.numel() * 4
+        out["module_1x1"].append({"real": name, "ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                                  "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                  "tbops": round(W.binary_ops(cfg) / (ms * 1e-3) / 1e12, 1)})
+        del streams
     return out
 
 

@@ -538,6 +538,36 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
                 pc[k] = ep.next_bias ? ep.next_bias[ch] : 0.0f;
             }
         }
+        // The identity vectors of a pixel block are fetched one block ahead of
+        // their use and before any store of that block: the real stream may be
+        // updated in place, so the compiler must not be left to order these
+        // loads against the stores, and issued together they overlap.
+        using real_t = typename std::conditional<HALF, _Float16, float>::type;
+        typedef real_t real4 __attribute__((ext_vector_type(4)));
+        constexpr int AHEAD = HALF ? 2 : 1;                    // blocks in flight ahead of the one in work
+        real4 ids[AHEAD + 1][8];
+        auto load_ids = [&](int pb, real4 (&dst)[8]) {
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const int m = m0 + 32 * (PB * wp + pb) + 4 * g + prow;
+                real4 t4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
+                if (ep.identity && m < s.m) {
+                    const real_t* idp = static_cast<const real_t*>(ep.identity) + (size_t)m * s.c_out + c0;
+                    if (vec_ok && c0 + 4 <= s.c_out) {
+                        t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(idp));
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+                            if (c0 + k < s.c_out) t4[k] = idp[k];
+                    }
+                }
+                dst[g] = t4;
+            }
+        };
+        if constexpr (MODULE) {
+#pragma unroll
+            for (int k = 0; k < AHEAD && k < PB; ++k) load_ids(k, ids[k]);
+        }
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
 #pragma unroll
@@ -551,6 +581,9 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
                     q.w = (int)(acc[cb][pb][r + 3] - sub[cb][r + 3]);
                     *reinterpret_cast<int4*>(tile + j * ROW_WORDS + 32 * cb + 16 * hsel + r) = q;
                 }
+            if constexpr (MODULE) {
+                if (pb + AHEAD < PB) load_ids(pb + AHEAD, ids[(pb + AHEAD) % (AHEAD + 1)]);
+            }
             // same wave wrote and reads: LDS operations of a wave complete in order
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
@@ -571,31 +604,15 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
                         }
                     }
                 } else {
-                    using real_t = typename std::conditional<HALF, _Float16, float>::type;
-                    typedef real_t real4 __attribute__((ext_vector_type(4)));
-                    const size_t at = (size_t)m * s.c_out + c0;
-                    const real_t* idp = static_cast<const real_t*>(ep.identity) + at;
-                    real_t* rp = static_cast<real_t*>(ep.r) + at;
+                    real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + c0;
                     const bool whole = vec_ok && c0 + 4 <= s.c_out;
                     const int qv[4] = {q.x, q.y, q.z, q.w};
-                    float idv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-                    if (ep.identity && row_ok) {
-                        if (whole) {
-                            const real4 t4 = *reinterpret_cast<const real4*>(idp);
-#pragma unroll
-                            for (int k = 0; k < 4; ++k) idv[k] = (float)t4[k];
-                        } else {
-#pragma unroll
-                            for (int k = 0; k < 4; ++k)
-                                if (c0 + k < s.c_out) idv[k] = (float)idp[k];
-                        }
-                    }
                     float v[4];
                     uint32_t nib = 0;
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
-                        v[k] = module_value<HALF>((float)qv[k], pg[k], pb_[k], ep.identity != nullptr, idv[k],
-                                                  ep.slope != nullptr, pa[k]);
+                        v[k] = module_value<HALF>((float)qv[k], pg[k], pb_[k], ep.identity != nullptr,
+                                                  (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
                         nib |= (uint32_t)(c0 + k < s.c_out && v[k] + pc[k] >= 0.0f) << k;
                     }
                     if (ep.r && row_ok) {
