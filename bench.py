@@ -254,6 +254,28 @@ def aux_measurements(torch, B, dev, work):
     out = {}
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
 
+    def graph_ms(launch, reps):
+        """Average time of one launch(r), r = 0..reps-1, replayed from a HIP graph
+        (kernel nodes only), so that the host's launch cost is not in the figure."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            launch(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for r in range(reps):
+                launch(r)
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        g.replay()
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / reps
+
     # VALU issue-rate probe: blocks*256 lanes * iters * 64 pairs * 64 binary ops
     blocks, iters = 256 * 16, 4000
     sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
@@ -350,14 +372,8 @@ def aux_measurements(torch, B, dev, work):
         for _ in range(2):
             B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, taps, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
                                                             scale, hb, zp), "branches")
-        a, b = ev(), ev()
-        a.record()
-        for r in range(reps):
-            B.check(B.bcnn_conv2d_binary_branches_sign_pack(d, taps, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS,
-                                                            scale, hb, zp), "branches")
-        b.record()
-        b.synchronize()
-        ms = a.elapsed_time(b) / reps
+        ms = graph_ms(lambda r: B.check(B.bcnn_conv2d_binary_branches_sign_pack(
+            d, taps, wk["xp"], 0, wk["wps"][0], padw, B.BCNN_PAD_WORDS, scale, hb, zp), "branches"), reps)
         tb = W.binary_ops(cfg) / cfg.layers / (ms * 1e-3) / 1e12
         out["branches"].append({"name": cfg.name, "ms": round(ms, 4), "tbops": round(tb, 1),
                                 "frac_valu_peak": round(tb / VALU_PEAK_TBOPS, 4)})
@@ -376,19 +392,40 @@ def aux_measurements(torch, B, dev, work):
         for st in streams:
             B.check(B.bcnn_conv2d_binary_module(d, wk["xp"], wk["wps"][0], par[0], par[1], st, par[2], par[3],
                                                 code, st, xn), "module")
-        a, b = ev(), ev()
-        a.record()
-        for r in range(reps):
-            st = streams[r % 4]
-            B.check(B.bcnn_conv2d_binary_module(d, wk["xp"], wk["wps"][0], par[0], par[1], st, par[2], par[3],
-                                                code, st, xn), "module")
-        b.record()
-        b.synchronize()
-        ms = a.elapsed_time(b) / reps
+        ms = graph_ms(lambda r: B.check(B.bcnn_conv2d_binary_module(
+            d, wk["xp"], wk["wps"][0], par[0], par[1], streams[r % 4], par[2], par[3], code, streams[r % 4], xn),
+            "module"), reps)
         nbytes = 2 * m_rows * cfg.c_out * esz + wk["xp"].numel() * 4 + xn.numel() * 4
         out["module_1x1"].append({"real": name, "ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                   "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                                   "tbops": round(W.binary_ops(cfg) / (ms * 1e-3) / 1e12, 1)})
+        del streams
+
+    # the 1x1 modules of the paper's network (its Table 1), batch 32, fp16 real stream updated in place
+    out["table1_modules_n32_f16"] = []
+    for name, ch, side in W.TABLE1_MODULES:
+        nb = 32
+        d = B.conv_desc(nb, ch, side, side, ch, 1, 1, 0)
+        rows = nb * side * side
+        cw = (ch + 31) // 32
+        xp = torch.randint(-2**31, 2**31 - 1, (rows, cw), dtype=torch.int32, device=dev)
+        wp = torch.randint(-2**31, 2**31 - 1, (ch, cw), dtype=torch.int32, device=dev)
+        par = [torch.from_numpy(W.uniform_f32(4500 + k, (ch,), lo, hi)).to(dev)
+               for k, (lo, hi) in enumerate([(-1.5, 1.5), (-30.0, 30.0), (0.05, 0.5), (-10.0, 10.0)])]
+        nbuf = 4 if rows * ch * 2 > (64 << 20) else 1
+        streams = [(torch.rand((rows, ch), device=dev) * 80 - 40).to(torch.float16) for _ in range(nbuf)]
+        xn = torch.empty((rows, cw), dtype=torch.int32, device=dev)
+        for st in streams:
+            B.check(B.bcnn_conv2d_binary_module(d, xp, wp, par[0], par[1], st, par[2], par[3], B.BCNN_F16, st, xn),
+                    "module")
+        ms = graph_ms(lambda r: B.check(B.bcnn_conv2d_binary_module(
+            d, xp, wp, par[0], par[1], streams[r % nbuf], par[2], par[3], B.BCNN_F16, streams[r % nbuf], xn),
+            "module"), reps)
+        nbytes = 2 * rows * ch * 2 + 2 * rows * cw * 4
+        out["table1_modules_n32_f16"].append({
+            "level": name, "c": ch, "side": side, "ms": round(ms, 4),
+            "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "tbops": round(2.0 * rows * ch * ch / (ms * 1e-3) / 1e12, 1)})
         del streams
     return out
 

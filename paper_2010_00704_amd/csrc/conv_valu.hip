@@ -13,17 +13,22 @@
 // channel), so borders need no correction term.  Per VEC input words a lane
 // issues VEC*TM*TN xor+popcount pairs, so vector loads are <1% of the
 // instruction stream and latency is hidden by the other waves of the SIMD.
+//
+// Channel tiles.  With c_out >= 32 (FULL) every tile computes 32 real channels:
+// the last tile of a ragged c_out starts at c_out - 32 instead of 32*ctile and
+// drops the `shift` channels it shares with its neighbour when it stores, so no
+// index is ever clamped and per-channel parameters are plain contiguous scalar
+// loads.  With c_out < 32 rows beyond c_out are clamped to the last real one so
+// that every scalar load stays inside its tensor.
 #include "bcnn_common.h"
+
+#include <type_traits>
 
 namespace bcnn {
 namespace {
 
 constexpr int TN = 32;
-
-template <int VEC> struct WordVec;
-template <> struct WordVec<1> { using type = uint32_t; };
-template <> struct WordVec<2> { using type = uint2; };
-template <> struct WordVec<4> { using type = uint4; };
+enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3 };
 
 template <int VEC>
 __device__ __forceinline__ void load_words(const uint32_t* p, bool ok, uint32_t (&out)[VEC])
@@ -39,44 +44,92 @@ __device__ __forceinline__ void load_words(const uint32_t* p, bool ok, uint32_t 
     }
 }
 
-enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3 };
+// Where a tile's channels live: channel of accumulator o, and whether the tile
+// stores it.
+template <bool FULL>
+struct Tile {
+    int o0, shift, o_last;
+    __device__ __forceinline__ uint32_t chan(int o) const
+    {
+        if constexpr (FULL) return (uint32_t)(o0 + o);
+        else return (uint32_t)((o0 + o < o_last) ? (o0 + o) : o_last);
+    }
+    __device__ __forceinline__ bool stores(int o) const
+    {
+        if constexpr (FULL) return o >= shift;
+        else return o0 + o <= o_last;
+    }
+};
 
-// Module epilogue for one pixel of a lane: 32 channels starting at o0.
-template <bool HALF>
-__device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp& ep, int m, int o0, int ctile,
-                                             const int32_t (&acc)[TN])
+// Module epilogue for one pixel of a lane.  The lane's 32 values are contiguous
+// in the real stream (128 or 64 bytes); when everything is 16-byte aligned
+// they move as 16-byte vectors, all loads before any store (the stream may be
+// updated in place).
+template <bool HALF, bool FULL>
+__device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp& ep, const Tile<FULL>& t,
+                                             int m, int ctile, const int32_t (&acc)[TN])
 {
-    const int o_last = s.c_out - 1;
-    const size_t row = (size_t)m * s.c_out + o0;
+    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+    constexpr int PER = HALF ? 8 : 4;                  // elements per 16-byte vector
+    typedef real_t realv __attribute__((ext_vector_type(PER)));
+    const size_t row = (size_t)m * s.c_out + t.o0;
+    const real_t* idp = static_cast<const real_t*>(ep.identity) + row;
+    real_t* rp = static_cast<real_t*>(ep.r) + row;
+    const bool vec = FULL && (s.c_out % PER == 0) &&
+                     ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & 15) == 0;
+    float idv[TN];
+#pragma unroll
+    for (int o = 0; o < TN; ++o) idv[o] = 0.0f;
+    if (ep.identity) {
+        if (vec) {
+#pragma unroll
+            for (int q = 0; q < TN / PER; ++q) {
+                const realv v = __builtin_nontemporal_load(reinterpret_cast<const realv*>(idp) + q);
+#pragma unroll
+                for (int k = 0; k < PER; ++k) idv[q * PER + k] = (float)v[k];
+            }
+        } else {
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                if (FULL || t.stores(o)) idv[o] = (float)idp[o];
+        }
+    }
+    const int ob = FULL ? t.o0 : 0;                    // FULL: plain offsets from the tile's first channel
+    float v[TN];
     uint32_t word = 0;
 #pragma unroll
     for (int o = 0; o < TN; ++o) {
-        const bool real = o0 + o <= o_last;
-        const int oc = real ? (o0 + o) : o_last;
-        float idv = 0.0f;
-        if (ep.identity && real)
-            idv = HALF ? (float)static_cast<const _Float16*>(ep.identity)[row + o]
-                       : static_cast<const float*>(ep.identity)[row + o];
-        const float v = module_value<HALF>((float)(s.k - 2 * acc[o]), ep.scale[oc], ep.bias[oc],
-                                           ep.identity != nullptr, idv, ep.slope != nullptr,
-                                           ep.slope ? ep.slope[oc] : 1.0f);
-        if (ep.r && real) {
-            if constexpr (HALF) static_cast<_Float16*>(ep.r)[row + o] = (_Float16)v;
-            else static_cast<float*>(ep.r)[row + o] = v;
-        }
-        const float c = ep.next_bias ? ep.next_bias[oc] : 0.0f;
-        word |= (uint32_t)(real && (v + c >= 0.0f)) << o;
+        const int oc = FULL ? o : (int)t.chan(o);
+        v[o] = module_value<HALF>((float)(s.k - 2 * acc[o]), (ep.scale + ob)[oc], (ep.bias + ob)[oc],
+                                  ep.identity != nullptr, idv[o], ep.slope != nullptr,
+                                  ep.slope ? (ep.slope + ob)[oc] : 1.0f);
+        const float c = ep.next_bias ? (ep.next_bias + ob)[oc] : 0.0f;
+        word |= (uint32_t)((FULL || t.stores(o)) && (v[o] + c >= 0.0f)) << o;
     }
-    if (ep.x_next) ep.x_next[(size_t)m * s.cwo + ctile] = word;
+    if (ep.r) {
+        if (vec) {
+#pragma unroll
+            for (int q = 0; q < TN / PER; ++q) {
+                realv u;
+#pragma unroll
+                for (int k = 0; k < PER; ++k) u[k] = (real_t)v[q * PER + k];
+                if (q * PER >= t.shift) reinterpret_cast<realv*>(rp)[q] = u;
+            }
+        } else {
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                if (t.stores(o)) rp[o] = (real_t)v[o];
+        }
+    }
+    if (ep.x_next) ep.x_next[(size_t)m * s.cwo + ctile] = word >> t.shift;
 }
 
-template <int TM, int VEC, int OUT>
+template <int TM, int VEC, int OUT, bool FULL>
 __global__ __launch_bounds__(256) void conv_valu_kernel(
     ConvShape s, int32_t n_mtiles, int32_t n_ctiles,
     const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
     const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep)
 {
-    constexpr bool FUSED = OUT == OUT_BITS;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * 4 + wave;
@@ -84,7 +137,10 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
     const int ctile = tile % n_ctiles;
     const int mtile = tile / n_ctiles;
     if (mtile >= n_mtiles) return;
-    const int o0 = ctile * TN;
+    Tile<FULL> t;
+    t.o_last = s.c_out - 1;
+    t.o0 = (FULL && ctile * TN + TN > s.c_out) ? s.c_out - TN : ctile * TN;
+    t.shift = ctile * TN - t.o0;
 
     int pn[TM], ph[TM], pw[TM];
     bool live[TM];
@@ -108,10 +164,7 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
         for (int o = 0; o < TN; ++o) acc[i][o] = 0;
 
     const int taps = s.ks * s.ks;
-    const int wrow = taps * s.cw;  // words per output channel
-    // Rows of channels beyond c_out are clamped to the last real channel so
-    // that every scalar load stays inside the weight tensor.
-    const int o_last = s.c_out - 1;
+    const uint32_t wrow = (uint32_t)(taps * s.cw);  // words per output channel
 
     for (int tap = 0; tap < taps; ++tap) {
         const int u = tap / s.ks, v = tap - u * s.ks;
@@ -124,24 +177,23 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
             const int ihc = inb[i] ? ih : 0, iwc = inb[i] ? iw : 0;
             xp[i] = x + ((size_t)(pn[i] * s.h + ihc) * s.w + iwc) * s.cw;
         }
-        const uint32_t* wt = w + (size_t)tap * s.cw;
+        const uint32_t* wt = w + (uint32_t)(tap * s.cw);
         for (int j0 = 0; j0 < s.cw; j0 += VEC) {
             uint32_t xv[TM][VEC];
 #pragma unroll
             for (int i = 0; i < TM; ++i) load_words<VEC>(xp[i] + j0, inb[i], xv[i]);
 #pragma unroll
             for (int o = 0; o < TN; ++o) {
-                const int oc = (o0 + o < o_last) ? (o0 + o) : o_last;
-                const uint32_t* wp = wt + (size_t)oc * wrow + j0;
+                const uint32_t* wp = wt + (t.chan(o) * wrow + (uint32_t)j0);
                 uint32_t wv[VEC];
                 if constexpr (VEC == 1) {
                     wv[0] = wp[0];
                 } else if constexpr (VEC == 2) {
-                    const uint2 t = *reinterpret_cast<const uint2*>(wp);
-                    wv[0] = t.x; wv[1] = t.y;
+                    const uint2 q = *reinterpret_cast<const uint2*>(wp);
+                    wv[0] = q.x; wv[1] = q.y;
                 } else {
-                    const uint4 t = *reinterpret_cast<const uint4*>(wp);
-                    wv[0] = t.x; wv[1] = t.y; wv[2] = t.z; wv[3] = t.w;
+                    const uint4 q = *reinterpret_cast<const uint4*>(wp);
+                    wv[0] = q.x; wv[1] = q.y; wv[2] = q.z; wv[3] = q.w;
                 }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -158,32 +210,34 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             if (live[i])
-                module_store<OUT == OUT_MODULE_F16>(s, ep, mtile * (64 * TM) + i * 64 + lane, o0, ctile, acc[i]);
-    } else if constexpr (FUSED) {
+                module_store<OUT == OUT_MODULE_F16, FULL>(s, ep, t, mtile * (64 * TM) + i * 64 + lane, ctile, acc[i]);
+    } else if constexpr (OUT == OUT_BITS) {
         uint32_t* yp = static_cast<uint32_t*>(out);
+        const int32_t* tp = thr + (FULL ? t.o0 : 0);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             uint32_t word = 0;
 #pragma unroll
             for (int o = 0; o < TN; ++o) {
-                const int oc = (o0 + o < o_last) ? (o0 + o) : o_last;
-                const bool on = (o0 + o <= o_last) && (s.k - 2 * acc[i][o] >= thr[oc]);
+                int32_t th;
+                if constexpr (FULL) th = tp[o];
+                else th = tp[t.chan(o)];
+                const bool on = (FULL || t.stores(o)) && (s.k - 2 * acc[i][o] >= th);
                 word |= (uint32_t)on << o;
             }
             if (live[i]) {
                 const int m = mtile * (64 * TM) + i * 64 + lane;
-                yp[(size_t)m * s.cwo + ctile] = word;
+                yp[(size_t)m * s.cwo + ctile] = word >> t.shift;
             }
         }
     } else {
         int32_t* y = static_cast<int32_t*>(out);
-        const bool vec_ok = (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0) &&
-                            (o0 + TN <= s.c_out);
+        const bool vec_ok = FULL && (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(y) & 15) == 0);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if (!live[i]) continue;
             const int m = mtile * (64 * TM) + i * 64 + lane;
-            int32_t* row = y + (size_t)m * s.c_out + o0;
+            int32_t* row = y + (size_t)m * s.c_out + t.o0;
             if (vec_ok) {
 #pragma unroll
                 for (int o = 0; o < TN; o += 4) {
@@ -192,39 +246,43 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
                     q.y = s.k - 2 * acc[i][o + 1];
                     q.z = s.k - 2 * acc[i][o + 2];
                     q.w = s.k - 2 * acc[i][o + 3];
-                    *reinterpret_cast<int4*>(row + o) = q;
+                    if (o >= t.shift) *reinterpret_cast<int4*>(row + o) = q;
                 }
             } else {
 #pragma unroll
                 for (int o = 0; o < TN; ++o)
-                    if (o0 + o < s.c_out) row[o] = s.k - 2 * acc[i][o];
+                    if (t.stores(o)) row[o] = s.k - 2 * acc[i][o];
             }
         }
     }
+}
+
+template <int TM, int VEC, int OUT>
+hipError_t launch_out(const ConvShape& s, const uint32_t* x, const uint32_t* w, const int32_t* thr,
+                      void* out, const ModuleEp& ep, hipStream_t stream)
+{
+    const int n_ctiles = (s.c_out + TN - 1) / TN;
+    const int n_mtiles = (s.m + 64 * TM - 1) / (64 * TM);
+    const int64_t waves = (int64_t)n_ctiles * n_mtiles;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    if (s.c_out >= TN)
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT, true>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out, ep);
+    else
+        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT, false>), dim3(blocks), dim3(256), 0, stream,
+                           s, n_mtiles, n_ctiles, x, w, thr, out, ep);
+    return hipGetLastError();
 }
 
 template <int TM, int VEC>
 hipError_t launch_tm_vec(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                          const int32_t* thr, void* out, const ModuleEp* ep, hipStream_t stream)
 {
-    const int n_ctiles = (s.c_out + TN - 1) / TN;
-    const int n_mtiles = (s.m + 64 * TM - 1) / (64 * TM);
-    const int64_t waves = (int64_t)n_ctiles * n_mtiles;
-    const unsigned blocks = (unsigned)((waves + 3) / 4);
     const ModuleEp none = {};
-    if (ep && ep->half)
-        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_MODULE_F16>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, x, w, thr, out, *ep);
-    else if (ep)
-        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_MODULE_F32>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, x, w, thr, out, *ep);
-    else if (thr)
-        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_BITS>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, x, w, thr, out, none);
-    else
-        hipLaunchKernelGGL((conv_valu_kernel<TM, VEC, OUT_I32>), dim3(blocks), dim3(256), 0, stream,
-                           s, n_mtiles, n_ctiles, x, w, thr, out, none);
-    return hipGetLastError();
+    if (ep && ep->half) return launch_out<TM, VEC, OUT_MODULE_F16>(s, x, w, thr, out, *ep, stream);
+    if (ep) return launch_out<TM, VEC, OUT_MODULE_F32>(s, x, w, thr, out, *ep, stream);
+    if (thr) return launch_out<TM, VEC, OUT_BITS>(s, x, w, thr, out, none, stream);
+    return launch_out<TM, VEC, OUT_I32>(s, x, w, thr, out, none, stream);
 }
 
 template <int TM>

@@ -103,6 +103,16 @@ CONFIGS = (
 )
 
 
+# The binary 1x1 convolution modules of the paper's network, one per level of its
+# Table 1 (channels = RC, map = H/S x W/S; C_in = C_out because of the identity
+# path), per image.  A second workload: tiny K at many pixels (stem) to large K
+# at 49 pixels (level 5).
+TABLE1_MODULES = (
+    ("stem", 32, 224), ("level1", 64, 112), ("level2", 128, 56),
+    ("level3", 256, 28), ("level4", 512, 14), ("level5", 1024, 7),
+)
+
+
 def out_hw(cfg):
     ho = (cfg.h + 2 * cfg.pad - cfg.k) // cfg.stride + 1
     wo = (cfg.w + 2 * cfg.pad - cfg.k) // cfg.stride + 1

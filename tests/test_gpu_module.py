@@ -181,6 +181,23 @@ def test_module_optional_parts(dev, variant, half):
     assert np.array_equal(r, want_r) and np.array_equal(bits, want_bits)
 
 
+@pytest.mark.parametrize("level", W.TABLE1_MODULES, ids=lambda t: t[0])
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_module_table1_shapes(dev, level, half):
+    """The 1x1 modules of the paper's network (Table 1), two images each."""
+    _, ch, side = level
+    n = 2
+    seed = 9700 + ch + half
+    x = W.pm1(seed, (n, ch, side, side), 0.5)
+    wt = W.pm1(seed + 1, (ch, ch, 1, 1))
+    m = n * side * side
+    g, b, ident, alpha, c = make_params(seed + 2, m, ch, half, False)
+    want_r, want_bits = oracle_module(x, wt, 1, 0, g, b, ident, alpha, c, half)
+    r, bits = gpu_module(dev, x, wt, 1, 0, g, b, ident, alpha, c, half, B.BCNN_VARIANT_AUTO, in_place=True)
+    assert np.array_equal(r, want_r)
+    assert np.array_equal(bits, want_bits)
+
+
 def test_module_argument_checks(dev):
     desc = B.conv_desc(1, 64, 8, 8, 32, 1, 1, 0)
     x = torch.zeros((64 * 2,), dtype=torch.int32, device=dev)
