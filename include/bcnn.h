@@ -212,6 +212,9 @@ int bcnn_threshold_sign_pack(const int32_t *y, const int32_t *thr, int64_t rows,
  *   z               : device, float32 [n][h_out][w_out][c_out]
  *   z_packed        : device, packed [n][h_out][w_out][ceil(c_out/32)],
  *                     bit = (z >= 0); must not alias x_packed.
+ *   variant         : BCNN_VARIANT_AUTO, _VALU or _MFMA_FP4 (the matrix-core
+ *                     kernel needs c_in a multiple of 256; UNSUPPORTED otherwise);
+ *                     all variants give identical results
  * Same shape limits and errors as bcnn_conv2d_binary; additionally
  * INVALID_ARG for an unknown pad_mode, a branch count that does not fit the
  * filter, or a non-zero x_branch_stride smaller than one tensor.
@@ -221,12 +224,13 @@ typedef enum { BCNN_PAD_WORDS = 0, BCNN_PAD_ZERO = 1 } bcnn_pad_mode;
 int bcnn_conv2d_binary_branches(const bcnn_conv_desc *desc, int32_t branches,
                                 const uint32_t *x_packed, int64_t x_branch_stride, const uint32_t *w_packed,
                                 const uint32_t *pad_words, int pad_mode, const float *scale,
-                                const float *bias, float *z, void *hip_stream);
+                                const float *bias, float *z, int variant, void *hip_stream);
 
 int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc *desc, int32_t branches,
                                           const uint32_t *x_packed, int64_t x_branch_stride, const uint32_t *w_packed,
                                           const uint32_t *pad_words, int pad_mode, const float *scale,
-                                          const float *bias, uint32_t *z_packed, void *hip_stream);
+                                          const float *bias, uint32_t *z_packed, int variant,
+                                          void *hip_stream);
 
 /* floor((in + 2*pad - k)/stride) + 1, or 0 if the window does not fit. Host only. */
 int bcnn_out_dim(int32_t in, int32_t k, int32_t stride, int32_t pad);

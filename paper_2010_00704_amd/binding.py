@@ -73,8 +73,8 @@ def lib():
         L.bcnn_diag_copy_u32.argtypes = [vp, vp, i64, vp]
         L.bcnn_diag_valu_peak.argtypes = [vp, i32, i32, vp]
         L.bcnn_pack_bias.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp]
-        L.bcnn_conv2d_binary_branches.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, vp]
-        L.bcnn_conv2d_binary_branches_sign_pack.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, vp]
+        L.bcnn_conv2d_binary_branches.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp]
+        L.bcnn_conv2d_binary_branches_sign_pack.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp]
         L.bcnn_conv2d_binary_module.argtypes = [dp, vp, vp, ctypes.POINTER(bcnn_module_epilogue), vp, vp,
                                                 ctypes.c_int, vp]
         for name in EXPORTS:
@@ -127,19 +127,19 @@ def bcnn_pack_bias(src, dtype, outer, channels, inner, bias, dst, stream=None):
 
 
 def bcnn_conv2d_binary_branches(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode,
-                                scale, bias, z, stream=None):
+                                scale, bias, z, variant=0, stream=None):
     return lib().bcnn_conv2d_binary_branches(ctypes.byref(_desc(desc)), int(branches), _ptr(x_packed),
                                              int(x_branch_stride), _ptr(w_packed),
                                              _ptr(pad_words), int(pad_mode), _ptr(scale), _ptr(bias),
-                                             _ptr(z), _stream(stream))
+                                             _ptr(z), int(variant), _stream(stream))
 
 
 def bcnn_conv2d_binary_branches_sign_pack(desc, branches, x_packed, x_branch_stride, w_packed, pad_words,
-                                          pad_mode, scale, bias, z_packed, stream=None):
+                                          pad_mode, scale, bias, z_packed, variant=0, stream=None):
     return lib().bcnn_conv2d_binary_branches_sign_pack(
         ctypes.byref(_desc(desc)), int(branches), _ptr(x_packed), int(x_branch_stride),
         _ptr(w_packed), _ptr(pad_words), int(pad_mode), _ptr(scale), _ptr(bias), _ptr(z_packed),
-        _stream(stream))
+        int(variant), _stream(stream))
 
 
 def bcnn_conv2d_binary_module(desc, x_packed, w_packed, bn_scale, bn_bias, identity, prelu_slope, next_bias,

@@ -170,7 +170,8 @@ int bcnn_pack_bias(const void* src, int dtype, int64_t outer, int64_t channels, 
 static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const uint32_t* x,
                           int64_t x_branch_stride,
                           const uint32_t* w, const uint32_t* pad_words, int pad_mode,
-                          const float* scale, const float* bias, void* out, bool fused, void* hip_stream)
+                          const float* scale, const float* bias, void* out, bool fused, int variant,
+                          void* hip_stream)
 {
     bcnn::ConvShape s;
     const int rc = bcnn::make_shape(desc, &s);
@@ -192,26 +193,44 @@ static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const ui
     a.pad_words = pad_mode == BCNN_PAD_WORDS ? pad_words : nullptr;
     a.zero_pad = pad_mode == BCNN_PAD_ZERO;
     a.scale = scale; a.bias = bias; a.out = out; a.fused = fused;
-    const hipError_t e = bcnn::launch_conv_branches(s, a, static_cast<hipStream_t>(hip_stream));
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const bool mfma_ok = bcnn::conv_branches_mfma_supported(s, a);
+    hipError_t e;
+    switch (variant) {
+        case BCNN_VARIANT_AUTO:
+            if (mfma_ok && s.c_out >= 64 && s.m >= 1024) e = bcnn::launch_conv_branches_mfma(s, a, st);
+            else e = bcnn::launch_conv_branches(s, a, st);
+            break;
+        case BCNN_VARIANT_VALU:
+            e = bcnn::launch_conv_branches(s, a, st);
+            break;
+        case BCNN_VARIANT_MFMA_FP4:
+            if (!mfma_ok) return BCNN_ERR_UNSUPPORTED;
+            e = bcnn::launch_conv_branches_mfma(s, a, st);
+            break;
+        default:
+            return BCNN_ERR_UNSUPPORTED;
+    }
     return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
 
 int bcnn_conv2d_binary_branches(const bcnn_conv_desc* desc, int32_t branches, const uint32_t* x_packed,
                                 int64_t x_branch_stride, const uint32_t* w_packed,
                                 const uint32_t* pad_words, int pad_mode, const float* scale,
-                                const float* bias, float* z, void* hip_stream)
+                                const float* bias, float* z, int variant, void* hip_stream)
 {
     return branches_entry(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale,
-                          bias, z, false, hip_stream);
+                          bias, z, false, variant, hip_stream);
 }
 
 int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc* desc, int32_t branches,
                                           const uint32_t* x_packed, int64_t x_branch_stride, const uint32_t* w_packed,
                                           const uint32_t* pad_words, int pad_mode, const float* scale,
-                                          const float* bias, uint32_t* z_packed, void* hip_stream)
+                                          const float* bias, uint32_t* z_packed, int variant,
+                                          void* hip_stream)
 {
     return branches_entry(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale,
-                          bias, z_packed, true, hip_stream);
+                          bias, z_packed, true, variant, hip_stream);
 }
 
 int bcnn_conv2d_binary(const bcnn_conv_desc* desc, const uint32_t* x_packed,

@@ -81,6 +81,9 @@ struct BranchArgs {
     bool fused;
 };
 hipError_t launch_conv_branches(const ConvShape& s, const BranchArgs& a, hipStream_t stream);
+// the same on the matrix cores; `supported` says whether it covers the call
+bool conv_branches_mfma_supported(const ConvShape& s, const BranchArgs& a);
+hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& a, hipStream_t stream);
 hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
 
 }  // namespace bcnn

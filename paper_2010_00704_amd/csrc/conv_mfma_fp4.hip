@@ -107,17 +107,40 @@ struct MfmaArgs {
     int32_t n_chunks;       // ceil(n_units / 2)
     int32_t z;              // 256 * n_chunks - K: positions that count +1 on their own
     int32_t x_bytes, w_bytes;  // sizes of the packed tensors, for the buffer descriptors
+    int32_t row_jump;       // words added to the input offset when a filter row is complete
+    int32_t tap_step;       // words added when a tap (branch) is complete: 0 for the plain convolution
+    int32_t taps;           // filter taps = branches
+    int32_t chunks_per_tap; // branch mode: cw / 8
 };
 
+// Branch mode (see the section in front of the fold below): per-branch scales,
+// bias, what a tap outside the image stands for.
+struct BranchEp {
+    const float* scale;         // [taps][c_out]
+    const float* bias;          // [c_out] or nullptr
+    const uint32_t* pad_words;  // [taps][cw] (pad_mode 1)
+    int32_t pad_mode;           // 0: -1 everywhere, 1: pad_words, 2: the tap contributes nothing
+};
+constexpr int PAD_LDS_WORDS = 9 * 64;   // pad words kept in LDS: taps * cw <= this
+constexpr int MAX_BRANCHES = 16;        // scales kept in LDS: taps <= this
+
 // PB = pixel blocks (of 32) per wave; the workgroup covers 2*32*PB pixels.
-enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3 };
+// Branch outputs come in three flavours of what a tap outside the image stands
+// for: -1 everywhere (nothing to do), the branch's pad words, or nothing at all.
+enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3,
+       OUT_BRANCH_F32 = 4, OUT_BRANCH_BITS = 5,                 // + 2 * pad mode
+       OUT_BRANCH_F32_WORDS = 6, OUT_BRANCH_BITS_WORDS = 7, OUT_BRANCH_F32_SKIP = 8, OUT_BRANCH_BITS_SKIP = 9 };
 
 template <int PB, int OUT, bool EVEN>
-__global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
+__global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH_F32) ? 2 : 1)) void conv_mfma_fp4_kernel(
     MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
-    const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep)
+    const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep, BranchEp bp)
 {
     constexpr bool FUSED = OUT == OUT_BITS;
+    constexpr bool BRANCH = OUT >= OUT_BRANCH_F32;
+    constexpr bool BRANCH_BITS = BRANCH && (OUT & 1);
+    constexpr int PADMODE = BRANCH ? (OUT - OUT_BRANCH_F32) / 2 : 0;   // 0: -1, 1: pad words, 2: skip
+    static_assert(!BRANCH || EVEN, "branch mode needs whole chunks per tap");
     constexpr int WG_PX = 64 * PB;
     // One stage = the chunk's 8 K-words of every row of the tile, as 16-byte
     // units (4 words = one K-half of a row).  Unit order: [block of 32 rows]
@@ -129,6 +152,9 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     constexpr int NL = (NBLK + 3) / 4;           // loads per wave and chunk
     __shared__ uint4 stage[3 * NBLK * 64];
     __shared__ int wpop_lds[WG_CH];
+    __shared__ int tapcnt_lds[BRANCH ? 2 : 1][2][WG_CH];        // per tap: [parity][pop | pad count][channel]
+    __shared__ uint32_t pad_lds[BRANCH ? PAD_LDS_WORDS + 8 : 1];
+    __shared__ float scale_lds[BRANCH ? MAX_BRANCHES : 1][WG_CH];   // scale[tap][channel of the tile]
     const ConvShape& s = a.s;
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -183,7 +209,7 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
         const int ph = oh * s.stride - s.pad;
         const int pw = (r - oh * s.wo) * s.stride - s.pad;
         rbase[i] = ((n * s.h + ph) * s.w + pw) * s.cw;
-        uint32_t vm = 0;
+        uint32_t vm = s.ks == 1 ? 0xFFFFFFFFu : 0u;   // 1x1: no padding, every branch is inside
         for (int u = 0; u < s.ks; ++u)
             for (int v = 0; v < s.ks; ++v) {
                 const int ih = ph + u, iw = pw + v;
@@ -205,7 +231,7 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     //     the weights) into stages whose contents are never multiplied.
     //   otherwise: the two units are tracked separately and each lane selects
     //     its own; units past the end (K padding) read as zero.
-    const int row_jump = (s.w - s.ks) * s.cw;
+    const int row_jump = a.row_jump;
     struct KPos { int unit, tap, v, ut, off; };
     KPos k0 = {0, 0, 0, 0, 0}, k1 = {0, 0, 0, 0, 0};
     auto advance1 = [&](KPos& p, int per_tap, int step_words, int go) {
@@ -216,7 +242,7 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
         const int v1 = p.v + tap_done;
         const int row_done = v1 == s.ks ? 1 : 0;
         p.v = v1 * (1 - row_done);
-        p.off += go * step_words + row_done * row_jump;
+        p.off += go * step_words + row_done * row_jump + tap_done * a.tap_step;
         p.unit += go;
     };
     if constexpr (!EVEN) advance1(k1, a.units_per_tap, 4, 1);
@@ -293,6 +319,61 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
         }
     };
 
+    // ---- branch mode: F x F as F*F shifted binary 1x1 branches (or P parallel
+    // 1x1 branches), each with its own real scale per output channel (BCNN
+    // paper, Section 4.2.1, last paragraph; Figure 2, bottom).  A tap's chunks
+    // accumulate in `acc` as usual; when the tap is complete its exact integer
+    // sum y_t = acc - (2*pop_t(channel) - 192*chunks_per_tap) is folded into the
+    // float totals, tot = fma(scale[t][channel], y_t, tot), and acc restarts at
+    // zero.  pop_t are the weight-bit counts of that tap alone, exchanged
+    // through LDS at every fold.  A pixel whose tap lies outside the image has
+    // read all-zero words (-1 everywhere); where the tap should stand for the
+    // branch's pad words instead, its y_t is replaced by c_in - 2*popcount(pad
+    // words xor weights), which the weight readers count on the way like pop_t;
+    // where it should contribute nothing the fold is skipped for that pixel.
+    v16f tot[BRANCH ? CB : 1][BRANCH ? PB : 1];
+    uint32_t vmask_d[PB];
+    auto branch_channel = [&](int cb, int r) {
+        const int ch = o0 + 64 * wc + 32 * cb + 16 * hsel + r;
+        return ch < s.c_out ? ch : s.c_out - 1;
+    };
+    if constexpr (BRANCH) {
+        for (int i = t; i < a.taps * WG_CH; i += 256) {
+            const int tp = i / WG_CH, cl = i - tp * WG_CH;
+            const int ch = o0 + cl < s.c_out ? o0 + cl : s.c_out - 1;
+            scale_lds[tp][cl] = bp.scale[(size_t)tp * s.c_out + ch];
+        }
+        for (int i = t; i < PAD_LDS_WORDS + 8; i += 256)
+            pad_lds[i] = (PADMODE == 1 && i < a.taps * s.cw) ? bp.pad_words[i] : 0u;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float b = bp.bias ? bp.bias[branch_channel(cb, r)] : 0.0f;
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb) tot[cb][pb][r] = b;
+            }
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            int m = m0 + 32 * (PB * wp + pb) + j;
+            m = m < s.m ? m : s.m - 1;
+            const int hw = s.ho * s.wo;
+            const int n = m / hw;
+            const int r = m - n * hw;
+            const int oh = r / s.wo;
+            const int ph = oh * s.stride - s.pad;
+            const int pw_ = (r - oh * s.wo) * s.stride - s.pad;
+            (void)n;
+            uint32_t vm = s.ks == 1 ? 0xFFFFFFFFu : 0u;
+            for (int u = 0; u < s.ks; ++u)
+                for (int v = 0; v < s.ks; ++v) {
+                    const int ih = ph + u, iw = pw_ + v;
+                    if (ih >= 0 && ih < s.h && iw >= 0 && iw < s.w) vm |= 1u << (u * s.ks + v);
+                }
+            vmask_d[pb] = vm;
+        }
+    }
+
     // ---- accumulators: lane (pixel j = lane%32, half h = lane/32), register r
     //      <-> channel 32*block + 16h + r.  They start at zero; every constant
     //      and per-channel term is applied in the epilogue.
@@ -341,9 +422,23 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
         const int blk = f < CB ? 2 * wc + f : 4 + PB * wp + (f - CB);
         dst = *reinterpret_cast<const uint4*>(lds0 + buf * STAGE_BYTES + blk * 1024);
     };
+    // Branch mode keeps the counts of the chunk read ahead apart (wnext, wpadn)
+    // until the chunk loop knows which tap they belong to; wpadn counts the
+    // positions where the weights differ from the tap's pad words (padq: this
+    // lane's four pad words of that chunk).
+    int wnext[CB] = {0, 0}, wpad[CB] = {0, 0}, wpadn[CB] = {0, 0};
+    uint4 padq = make_uint4(0u, 0u, 0u, 0u);
     auto count_unit = [&](const uint4& q, int f) {   // well after the read, so nothing waits
-        wpop[f] += __builtin_popcount(q.x & 0x77777777u) + __builtin_popcount(q.y & 0x77777777u) +
-                   __builtin_popcount(q.z & 0x77777777u) + __builtin_popcount(q.w & 0x77777777u);
+        const int c = __builtin_popcount(q.x & 0x77777777u) + __builtin_popcount(q.y & 0x77777777u) +
+                      __builtin_popcount(q.z & 0x77777777u) + __builtin_popcount(q.w & 0x77777777u);
+        if constexpr (BRANCH) {
+            wnext[f] = c;
+            if constexpr (PADMODE == 1)
+                wpadn[f] = __builtin_popcount(q.x ^ padq.x) + __builtin_popcount(q.y ^ padq.y) +
+                           __builtin_popcount(q.z ^ padq.z) + __builtin_popcount(q.w ^ padq.w);
+        } else {
+            wpop[f] += c;
+        }
     };
     auto word_of = [&](int f, int ks) -> uint32_t {   // ks = 0..3 within the chunk
         return ks == 0 ? pw[f].x : ks == 1 ? pw[f].y : ks == 2 ? pw[f].z : pw[f].w;
@@ -422,9 +517,11 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     __syncthreads();
 #pragma unroll
     for (int f = 0; f < NF; ++f) read_unit(pw[f], 0, f);
+    if constexpr (PADMODE == 1) padq = *reinterpret_cast<const uint4*>(pad_lds + 4 * hsel);   // chunk 0
 #pragma unroll
     for (int f = 0; f < CB; ++f) {
         count_unit(pw[f], f);
+        if constexpr (BRANCH) { wpop[f] = wnext[f]; wpad[f] = wpadn[f]; }
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) fa[0][f][jj] = expand_w(pw[f].x, jj);
     }
@@ -435,9 +532,59 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
 
     {
         int b0 = 0, b1 = 1, b2 = 2;
+        int tap = 0, chunk_in_tap = 0, par = 0;
+        const int c_in = 256 * a.chunks_per_tap;
         for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+            if constexpr (PADMODE == 1)   // pad words of the chunk whose weights this body reads ahead
+                padq = *reinterpret_cast<const uint4*>(pad_lds + 8 * (chunk + 1) + 4 * hsel);
             chunk_body(b1, b2);
             const int tmp = b0; b0 = b1; b1 = b2; b2 = tmp;
+            if constexpr (BRANCH) {
+                chunk_in_tap += 1;
+                if (chunk_in_tap < a.chunks_per_tap) {
+#pragma unroll
+                    for (int f = 0; f < CB; ++f) { wpop[f] += wnext[f]; wpad[f] += wpadn[f]; }
+                    continue;
+                }
+                // ---- the tap is complete: fold it
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    // lanes l and l^32 read the two K-halves of the same weight row
+                    const int both = wpop[cb] + __shfl_xor(wpop[cb], 32, 64);
+                    const int bothp = wpad[cb] + __shfl_xor(wpad[cb], 32, 64);
+                    if (hsel == 0) {
+                        tapcnt_lds[par][0][64 * wc + 32 * cb + row_to_channel(j)] = both;
+                        if constexpr (PADMODE == 1) tapcnt_lds[par][1][64 * wc + 32 * cb + row_to_channel(j)] = bothp;
+                    }
+                    wpop[cb] = wnext[cb];
+                    wpad[cb] = wpadn[cb];
+                }
+                __syncthreads();
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int cl = 64 * wc + 32 * cb + 16 * hsel + r;
+                        const float corr = (float)(2 * tapcnt_lds[par][0][cl] - 192 * a.chunks_per_tap);
+                        float ypad = 0.0f;
+                        if constexpr (PADMODE == 1) ypad = (float)(c_in - 2 * tapcnt_lds[par][1][cl]);
+                        const float g = scale_lds[tap][cl];
+#pragma unroll
+                        for (int pb = 0; pb < PB; ++pb) {
+                            const bool inb = PADMODE == 0 || ((vmask_d[pb] >> tap) & 1u);
+                            float y = acc[cb][pb][r] - corr;
+                            if constexpr (PADMODE == 1) y = inb ? y : ypad;
+                            const float zn = __builtin_fmaf(g, y, tot[cb][pb][r]);
+                            if constexpr (PADMODE == 2) tot[cb][pb][r] = inb ? zn : tot[cb][pb][r];
+                            else tot[cb][pb][r] = zn;
+                            acc[cb][pb][r] = 0.0f;
+                        }
+                        if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the live set small
+                    }
+                tap += 1;
+                chunk_in_tap = 0;
+                par ^= 1;
+            }
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the loads of the chunks past the end
@@ -451,7 +598,7 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
     // has to be subtracted per channel (plus the threshold, minus 0.5 so that
     // the result is never zero, in the fused case) is kept in sub[][].
     float sub[CB][16];
-    {
+    if constexpr (!BRANCH) {
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             // lanes l and l^32 read the two K-halves of the same weight row
@@ -478,19 +625,27 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
                 }
             }
     }
-    if constexpr (FUSED) {
+    if constexpr (FUSED || BRANCH_BITS) {
         // bit = (y >= thr)  <=>  acc - sub = y - thr + 0.5 > 0  <=>  sign bit clear
+        // (branch mode: bit = (z >= 0), a real comparison because z may be -0)
         uint32_t* yp = static_cast<uint32_t*>(out);
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
             uint32_t part[CB];
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb) {
-                uint32_t sg = 0;
+                if constexpr (BRANCH) {
+                    uint32_t bits = 0;
 #pragma unroll
-                for (int r = 15; r >= 0; --r)  // r = 0 ends in bit 0
-                    sg = __builtin_amdgcn_alignbit(sg, __float_as_uint(acc[cb][pb][r] - sub[cb][r]), 31);
-                part[cb] = ~sg & 0xFFFFu;     // bit r = (sum >= thr) for channel 16h + r
+                    for (int r = 0; r < 16; ++r) bits |= (uint32_t)(tot[cb][pb][r] >= 0.0f) << r;
+                    part[cb] = bits;
+                } else {
+                    uint32_t sg = 0;
+#pragma unroll
+                    for (int r = 15; r >= 0; --r)  // r = 0 ends in bit 0
+                        sg = __builtin_amdgcn_alignbit(sg, __float_as_uint(acc[cb][pb][r] - sub[cb][r]), 31);
+                    part[cb] = ~sg & 0xFFFFu;     // bit r = (sum >= thr) for channel 16h + r
+                }
             }
             // lanes of half 0 finish block 0, lanes of half 1 finish block 1
             const uint32_t give = hsel ? part[0] : part[1];
@@ -575,10 +730,17 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
 #pragma unroll
                 for (int r = 0; r < 16; r += 4) {
                     int4 q;
-                    q.x = (int)(acc[cb][pb][r + 0] - sub[cb][r + 0]);
-                    q.y = (int)(acc[cb][pb][r + 1] - sub[cb][r + 1]);
-                    q.z = (int)(acc[cb][pb][r + 2] - sub[cb][r + 2]);
-                    q.w = (int)(acc[cb][pb][r + 3] - sub[cb][r + 3]);
+                    if constexpr (BRANCH) {           // float totals travel as their bit patterns
+                        q.x = __float_as_int(tot[cb][pb][r + 0]);
+                        q.y = __float_as_int(tot[cb][pb][r + 1]);
+                        q.z = __float_as_int(tot[cb][pb][r + 2]);
+                        q.w = __float_as_int(tot[cb][pb][r + 3]);
+                    } else {
+                        q.x = (int)(acc[cb][pb][r + 0] - sub[cb][r + 0]);
+                        q.y = (int)(acc[cb][pb][r + 1] - sub[cb][r + 1]);
+                        q.z = (int)(acc[cb][pb][r + 2] - sub[cb][r + 2]);
+                        q.w = (int)(acc[cb][pb][r + 3] - sub[cb][r + 3]);
+                    }
                     *reinterpret_cast<int4*>(tile + j * ROW_WORDS + 32 * cb + 16 * hsel + r) = q;
                 }
             if constexpr (MODULE) {
@@ -643,16 +805,21 @@ __global__ __launch_bounds__(256, (PB <= 4 ? 2 : 1)) void conv_mfma_fp4_kernel(
 
 template <int PB, int OUT>
 hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int32_t* thr,
-                     void* out, const ModuleEp* ep, hipStream_t stream)
+                     void* out, const ModuleEp* ep, hipStream_t stream, const BranchEp* bp = nullptr)
 {
     const ModuleEp e = ep ? *ep : ModuleEp{};
+    const BranchEp b = bp ? *bp : BranchEp{};
     constexpr int WG_PX = 64 * PB;
     a.n_ptiles = (a.s.m + WG_PX - 1) / WG_PX;
     const unsigned blocks = (unsigned)(a.n_ptiles * a.n_ctiles);
-    if (a.units_per_tap % 2 == 0)
-        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e);
-    else
-        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, false>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e);
+    if constexpr (OUT >= OUT_BRANCH_F32) {
+        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
+    } else {
+        if (a.units_per_tap % 2 == 0)
+            hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
+        else
+            hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, false>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
+    }
     return hipGetLastError();
 }
 
@@ -696,6 +863,10 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     a.z = 256 * a.n_chunks - s.k;
     a.x_bytes = (int32_t)((int64_t)s.n * s.h * s.w * s.cw * 4);
     a.w_bytes = (int32_t)((int64_t)s.c_out * a.n_units * 16);
+    a.row_jump = (s.w - s.ks) * s.cw;
+    a.tap_step = 0;
+    a.taps = s.ks * s.ks;
+    a.chunks_per_tap = 0;
     // Feature maps of 7, 14, 28, 56 pixels a side make the pixel count a
     // multiple of 49: 7 pixel blocks per wave then tile it without remainder
     // where 4 would leave a quarter of the last round idle.  The 2 x 7 tile
@@ -711,6 +882,57 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     if (tile == 7 || (tile == 0 && a.n_chunks >= 20 && tile_cost(s, 7) < tile_cost(s, 4)))
         return launch_pb<7, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
     return launch_pb<4, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
+}
+
+// ---- branch mode on the matrix cores
+static int64_t branch_x_bytes(const ConvShape& s, const BranchArgs& b)
+{
+    const int64_t one = (int64_t)s.n * s.h * s.w * s.cw * 4;
+    return b.x_branch_stride ? (int64_t)(b.branches - 1) * b.x_branch_stride * 4 + one : one;
+}
+
+bool conv_branches_mfma_supported(const ConvShape& s, const BranchArgs& b)
+{
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(b.x) | reinterpret_cast<uintptr_t>(b.w) |
+                           ((uintptr_t)b.x_branch_stride * 4u);
+    const int64_t w_bytes = (int64_t)s.c_out * b.branches * s.cw * 4;
+    // whole 256-bit chunks per branch, 16-byte aligned tensors, pad words that fit
+    // the LDS table, validity masks of 32 bits, 31-bit byte offsets
+    return s.cw % 8 == 0 && (bits & 15) == 0 && (int64_t)b.branches * s.cw <= PAD_LDS_WORDS &&
+           b.branches <= MAX_BRANCHES && branch_x_bytes(s, b) < (1ll << 31) && w_bytes < (1ll << 31);
+}
+
+hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& b, hipStream_t stream)
+{
+    MfmaArgs a;
+    a.s = s;
+    a.n_ptiles = 0;
+    a.n_ctiles = (s.c_out + WG_CH - 1) / WG_CH;
+    a.units_per_tap = s.cw / 4;
+    a.taps = b.branches;
+    a.n_units = a.taps * a.units_per_tap;
+    a.n_chunks = a.n_units / 2;
+    a.chunks_per_tap = s.cw / 8;
+    a.z = 0;
+    a.x_bytes = (int32_t)branch_x_bytes(s, b);
+    a.w_bytes = (int32_t)((int64_t)s.c_out * a.n_units * 16);
+    // 3x3: the input offset walks on through the taps of a filter row and jumps at
+    // its end; 1x1 with parallel branches: every branch starts at the same pixel
+    a.row_jump = s.ks == 1 ? 0 : (s.w - s.ks) * s.cw;
+    a.tap_step = (int32_t)b.x_branch_stride + (s.ks == 1 ? -s.cw : 0);
+    BranchEp bp;
+    bp.scale = b.scale;
+    bp.bias = b.bias;
+    bp.pad_words = b.pad_words;
+    bp.pad_mode = b.zero_pad ? 2 : (b.pad_words ? 1 : 0);
+    if (b.fused) {
+        if (bp.pad_mode == 2) return launch_pb<4, OUT_BRANCH_BITS_SKIP>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
+        if (bp.pad_mode == 1) return launch_pb<4, OUT_BRANCH_BITS_WORDS>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
+        return launch_pb<4, OUT_BRANCH_BITS>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
+    }
+    if (bp.pad_mode == 2) return launch_pb<4, OUT_BRANCH_F32_SKIP>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
+    if (bp.pad_mode == 1) return launch_pb<4, OUT_BRANCH_F32_WORDS>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
+    return launch_pb<4, OUT_BRANCH_F32>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
 }
 
 }  // namespace bcnn

@@ -125,7 +125,17 @@ def make_case(seed, n, c, h, w, o, k, shared, grid):
     return xb, wt, padv, g, hb
 
 
-def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused):
+VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4]
+VARIANT_IDS = ["auto", "valu", "mfma_fp4"]
+
+
+def run_variant(rc, what):
+    if rc == B.BCNN_ERR_UNSUPPORTED:
+        pytest.skip("variant does not cover this shape")
+    B.check(rc, what)
+
+
+def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused, variant=B.BCNN_VARIANT_AUTO):
     bcount, n, c, h, w = xb.shape
     o, k = wt.shape[0], (wt.shape[2] if wt.ndim == 4 else 1)
     p = g.shape[0]
@@ -140,11 +150,12 @@ def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused):
     if fused:
         cwo = (o + 31) // 32
         out = Guarded(n * ho * wo * cwo, dev)
-        B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr),
-                "branches_sign_pack")
+        run_variant(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr,
+                                                            variant), "branches_sign_pack")
         return out.get(np.uint32).reshape(n, ho * wo, cwo)
     out = Guarded(n * ho * wo * o, dev)
-    B.check(B.bcnn_conv2d_binary_branches(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr), "branches")
+    run_variant(B.bcnn_conv2d_binary_branches(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr, variant),
+                "branches")
     return out.get(np.float32).reshape(n, ho, wo, o)
 
 
@@ -166,6 +177,10 @@ BRANCH_SHAPES = [
     (1, 70, 17, 3, 31, 3, 2, 0),
     (40, 64, 14, 14, 64, 3, 1, 1),   # enough waves for two pixels per lane
     (2, 1, 4, 4, 1, 3, 1, 1),
+    (6, 256, 14, 14, 128, 3, 1, 1),  # c_in a multiple of 256: the matrix-core kernel covers these
+    (3, 512, 20, 19, 100, 3, 2, 1),
+    (9, 256, 13, 11, 200, 3, 1, 0),
+    (2, 768, 25, 25, 64, 3, 1, 1),
 ]
 MODES = ["minus", "words", "zero"]
 
@@ -173,7 +188,8 @@ MODES = ["minus", "words", "zero"]
 @pytest.mark.parametrize("shape", BRANCH_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("shared", [True, False], ids=["shared", "per_branch"])
-def test_branches_match_oracle(dev, shape, mode, shared):
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+def test_branches_match_oracle(dev, shape, mode, shared, variant):
     n, c, h, w, o, k, stride, pad = shape
     seed = 8000 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23))) + MODES.index(mode) + 2 * shared
     p = k * k
@@ -186,11 +202,11 @@ def test_branches_match_oracle(dev, shape, mode, shared):
         else:
             padv_o, words, code = np.zeros((p, c), dtype=np.int8), pack_padv(padv), B.BCNN_PAD_ZERO
         z64, z32, yt = oracle.branches_pm1(xb, padv_o, wt, g, hb, stride, pad, taps=True)
-        got = gpu_branches(dev, xb, wt, words, code, g, hb, stride, pad, fused=False)
+        got = gpu_branches(dev, xb, wt, words, code, g, hb, stride, pad, fused=False, variant=variant)
         assert np.array_equal(got, z32)
         mag = np.abs(hb.astype(np.float64)) + (np.abs(g.astype(np.float64)).T[None, None, None] * np.abs(yt)).sum(-1)
         assert np.all(np.abs(got.astype(np.float64) - z64) <= p * 2.0**-24 * mag + 1e-30)
-        bits = gpu_branches(dev, xb, wt, words, code, g, hb, stride, pad, fused=True)
+        bits = gpu_branches(dev, xb, wt, words, code, g, hb, stride, pad, fused=True, variant=variant)
         assert np.array_equal(bits, oracle_bits(z32))
         if grid:
             assert np.any(z32 == 0) or z32.size < 20000, "grid case should produce exact zeros of z"
@@ -203,12 +219,16 @@ PARALLEL_SHAPES = [
     (3, 256, 7, 7, 96, 2, 2),
     (2, 32, 28, 28, 32, 4, 1),
     (1, 33, 5, 6, 5, 1, 1),
+    (2, 256, 28, 28, 128, 2, 1),     # matrix-core kernel
+    (5, 512, 15, 15, 70, 3, 2),
+    (8, 256, 12, 12, 256, 5, 1),
 ]
 
 
 @pytest.mark.parametrize("shape", PARALLEL_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("shared", [True, False], ids=["shared", "per_branch"])
-def test_parallel_branches_match_oracle(dev, shape, shared):
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+def test_parallel_branches_match_oracle(dev, shape, shared, variant):
     n, c, h, w, o, p, stride = shape
     seed = 8800 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19))) + shared
     for grid in (False, True):
@@ -222,9 +242,9 @@ def test_parallel_branches_match_oracle(dev, shape, shared):
             hb = W.uniform_f32(seed + 4, (o,), -float(c), float(c))
         padv = -np.ones((p, c), dtype=np.int8)
         _, z32 = oracle.branches_pm1(xb, padv, wt, g, hb, stride, 0)
-        got = gpu_branches(dev, xb, wt, None, B.BCNN_PAD_WORDS, g, hb, stride, 0, fused=False)
+        got = gpu_branches(dev, xb, wt, None, B.BCNN_PAD_WORDS, g, hb, stride, 0, fused=False, variant=variant)
         assert np.array_equal(got, z32)
-        bits = gpu_branches(dev, xb, wt, None, B.BCNN_PAD_WORDS, g, hb, stride, 0, fused=True)
+        bits = gpu_branches(dev, xb, wt, None, B.BCNN_PAD_WORDS, g, hb, stride, 0, fused=True, variant=variant)
         assert np.array_equal(bits, oracle_bits(z32))
 
 
@@ -257,7 +277,8 @@ def test_branch_argument_checks(dev):
 
 # ------------------------------------------------------------ full-size shapes
 @pytest.mark.parametrize("index", [3, 4])
-def test_branches_full_size(dev, index):
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+def test_branches_full_size(dev, index, variant):
     """The launch is the full benchmark shape (3x3, 256 channels, whole batch,
     one tensor shared by the branches, per-branch pad words); the oracle
     evaluates the first, middle and last image."""
@@ -277,8 +298,10 @@ def test_branches_full_size(dev, index):
     gt, ht = up(g, dev), up(hb, dev)
     z = torch.empty((cfg.n, ho, wo, cfg.c_out), dtype=torch.float32, device=dev)
     zp = torch.empty((cfg.n, ho * wo, cfg.c_out // 32), dtype=torch.int32, device=dev)
-    B.check(B.bcnn_conv2d_binary_branches(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, z), "branches")
-    B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, zp), "fused")
+    run_variant(B.bcnn_conv2d_binary_branches(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, z, variant),
+                "branches")
+    run_variant(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, zp,
+                                                        variant), "fused")
     torch.cuda.synchronize()
     _, z32 = oracle.branches_pm1(x_all[picks][None], padv, wt, g, hb, cfg.stride, cfg.pad)
     got = z[picks].cpu().numpy()
