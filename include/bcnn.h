@@ -99,6 +99,21 @@ int bcnn_pack_bias(const void *src, int dtype, int64_t outer, int64_t channels, 
                    const float *bias, uint32_t *dst, void *hip_stream);
 
 /*
+ * bcnn_pack_bias on a source whose channels are replicated by bookkeeping
+ * (Section 4.2.2: a building block that widens the network sees every real
+ * channel `replication` times; the real map is not copied): the packed
+ * tensor has replication * src_channels channels, channel c is
+ *   bit = (float(src[.][c mod src_channels][.]) + bias[c] >= 0).
+ *   src  : device, contiguous [outer][src_channels][inner] of `dtype`
+ *   bias : device, float32 [replication * src_channels]
+ *   dst  : device, [outer][inner][ceil(replication * src_channels / 32)]
+ * replication = 1 is bcnn_pack_bias.
+ */
+int bcnn_pack_bias_replicated(const void *src, int dtype, int64_t outer, int64_t src_channels,
+                              int64_t inner, int32_t replication, const float *bias, uint32_t *dst,
+                              void *hip_stream);
+
+/*
  * Binary convolution, integer sums (Section 1 operator, Section 4.2.1
  * operands):
  *   y[n][oh][ow][o] = sum_{u,v,c} X~[n][oh*s-p+u][ow*s-p+v][c] * W[o][u][v][c]
@@ -151,7 +166,11 @@ int bcnn_conv2d_binary_variant(const bcnn_conv_desc *desc, const uint32_t *x_pac
  * prelu_slope == NULL: no activation; next_bias == NULL: 0.  identity and r
  * are [n*h_out*w_out][c_out] of real_dtype (BCNN_F32 or BCNN_F16), i.e. the
  * real stream in channel-last order; r may be the same buffer as identity
- * (the stream is updated in place).
+ * (the stream is updated in place).  identity_channels (0 = c_out): when the
+ * block widens the network by replicating channels (Section 4.2.2), the
+ * identity stream keeps its identity_channels channels, [m][identity_channels],
+ * and output channel o adds identity channel o mod identity_channels; r then
+ * has to be a different buffer.
  *   r             : device, real output, or NULL to skip it
  *   x_next_packed : device, packed [n][h_out][w_out][ceil(c_out/32)], or NULL
  *                   to skip it; at least one of the two outputs is required
@@ -164,6 +183,7 @@ typedef struct {
     const float *prelu_slope; /* [c_out], or NULL */
     const float *next_bias;   /* [c_out], or NULL */
     int32_t real_dtype;       /* BCNN_F32 or BCNN_F16 */
+    int32_t identity_channels; /* channels of the identity stream; 0 means c_out */
 } bcnn_module_epilogue;
 
 int bcnn_conv2d_binary_module(const bcnn_conv_desc *desc, const uint32_t *x_packed,

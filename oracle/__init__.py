@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     num_threads,
     out_dim,
     pack_channels,
+    replicate_channels,
     sign_bias_f32,
     sign_f32,
     threshold_sign,

@@ -258,3 +258,17 @@ def module_epilogue(y, gamma, beta, identity=None, alpha=None):
                                    _ptr(alpha) if alpha is not None else None,
                                    y.size // o, o, _ptr(r64), _ptr(r32))
     return r64, r32
+
+
+def replicate_channels(x, r, axis=1):
+    """Channel replication by an integer factor (paper, Section 4.2.2: a block
+    that widens the network sees every real channel R times): the tensor with
+    its channel axis repeated r times, channel k = j*C + c being a copy of
+    channel c.  Here the copy is made for real (numpy.tile): the definition
+    the library's bookkeeping is checked against."""
+    x = np.asarray(x)
+    if int(r) < 1:
+        raise ValueError("replication factor must be >= 1")
+    reps = [1] * x.ndim
+    reps[axis] = int(r)
+    return np.tile(x, reps)

@@ -28,7 +28,7 @@ EXPORTS = (
     "bcnn_conv2d_binary_variant", "bcnn_threshold_sign_pack", "bcnn_out_dim",
     "bcnn_status_string", "bcnn_diag_copy_u32", "bcnn_diag_valu_peak",
     "bcnn_pack_bias", "bcnn_conv2d_binary_branches", "bcnn_conv2d_binary_branches_sign_pack",
-    "bcnn_conv2d_binary_module",
+    "bcnn_conv2d_binary_module", "bcnn_pack_bias_replicated",
 )
 
 
@@ -39,7 +39,8 @@ class bcnn_conv_desc(ctypes.Structure):
 
 class bcnn_module_epilogue(ctypes.Structure):
     _fields_ = [("bn_scale", ctypes.c_void_p), ("bn_bias", ctypes.c_void_p), ("identity", ctypes.c_void_p),
-                ("prelu_slope", ctypes.c_void_p), ("next_bias", ctypes.c_void_p), ("real_dtype", ctypes.c_int32)]
+                ("prelu_slope", ctypes.c_void_p), ("next_bias", ctypes.c_void_p), ("real_dtype", ctypes.c_int32),
+                ("identity_channels", ctypes.c_int32)]
 
 
 class BcnnError(RuntimeError):
@@ -73,6 +74,7 @@ def lib():
         L.bcnn_diag_copy_u32.argtypes = [vp, vp, i64, vp]
         L.bcnn_diag_valu_peak.argtypes = [vp, i32, i32, vp]
         L.bcnn_pack_bias.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp]
+        L.bcnn_pack_bias_replicated.argtypes = [vp, ctypes.c_int, i64, i64, i64, i32, vp, vp, vp]
         L.bcnn_conv2d_binary_branches.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp]
         L.bcnn_conv2d_binary_branches_sign_pack.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp]
         L.bcnn_conv2d_binary_module.argtypes = [dp, vp, vp, ctypes.POINTER(bcnn_module_epilogue), vp, vp,
@@ -142,10 +144,15 @@ def bcnn_conv2d_binary_branches_sign_pack(desc, branches, x_packed, x_branch_str
         int(variant), _stream(stream))
 
 
+def bcnn_pack_bias_replicated(src, dtype, outer, src_channels, inner, replication, bias, dst, stream=None):
+    return lib().bcnn_pack_bias_replicated(_ptr(src), dtype, outer, src_channels, inner, int(replication),
+                                           _ptr(bias), _ptr(dst), _stream(stream))
+
+
 def bcnn_conv2d_binary_module(desc, x_packed, w_packed, bn_scale, bn_bias, identity, prelu_slope, next_bias,
-                              real_dtype, r, x_next_packed, variant=0, stream=None):
+                              real_dtype, r, x_next_packed, variant=0, stream=None, identity_channels=0):
     ep = bcnn_module_epilogue(_ptr(bn_scale), _ptr(bn_bias), _ptr(identity), _ptr(prelu_slope),
-                              _ptr(next_bias), int(real_dtype))
+                              _ptr(next_bias), int(real_dtype), int(identity_channels))
     return lib().bcnn_conv2d_binary_module(ctypes.byref(_desc(desc)), _ptr(x_packed), _ptr(w_packed),
                                            ctypes.byref(ep), _ptr(r), _ptr(x_next_packed), int(variant),
                                            _stream(stream))

@@ -137,10 +137,11 @@ const char* bcnn_status_string(int status)
     }
 }
 
-static int pack_entry(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
-                      const float* bias, uint32_t* dst, void* hip_stream)
+static int pack_entry(const void* src, int dtype, int64_t outer, int64_t channels, int64_t src_channels,
+                      int64_t inner, const float* bias, uint32_t* dst, void* hip_stream)
 {
     if (!src || !dst || outer < 1 || channels < 1 || inner < 1) return BCNN_ERR_INVALID_ARG;
+    if (src_channels < 1 || src_channels > channels) return BCNN_ERR_INVALID_ARG;
     if (dtype != BCNN_F32 && dtype != BCNN_F16 && dtype != BCNN_I8) return BCNN_ERR_UNSUPPORTED;
     const int64_t cw = (channels + 31) / 32;
     if (outer > INT_MAX || inner > INT_MAX || outer * inner > INT_MAX / cw) return BCNN_ERR_UNSUPPORTED;
@@ -149,7 +150,7 @@ static int pack_entry(const void* src, int dtype, int64_t outer, int64_t channel
     if (!bcnn::aligned(src, esz) || !bcnn::aligned(dst, 4)) return BCNN_ERR_ALIGNMENT;
     if (src == static_cast<const void*>(dst)) return BCNN_ERR_INVALID_ARG;
     if (bias && !bcnn::aligned(bias, 4)) return BCNN_ERR_ALIGNMENT;
-    const hipError_t e = bcnn::launch_pack(src, dtype, bias, outer, channels, inner, dst,
+    const hipError_t e = bcnn::launch_pack(src, dtype, bias, outer, channels, src_channels, inner, dst,
                                            static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
@@ -157,14 +158,24 @@ static int pack_entry(const void* src, int dtype, int64_t outer, int64_t channel
 int bcnn_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
               uint32_t* dst, void* hip_stream)
 {
-    return pack_entry(src, dtype, outer, channels, inner, nullptr, dst, hip_stream);
+    return pack_entry(src, dtype, outer, channels, channels, inner, nullptr, dst, hip_stream);
 }
 
 int bcnn_pack_bias(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
                    const float* bias, uint32_t* dst, void* hip_stream)
 {
     if (!bias) return BCNN_ERR_INVALID_ARG;
-    return pack_entry(src, dtype, outer, channels, inner, bias, dst, hip_stream);
+    return pack_entry(src, dtype, outer, channels, channels, inner, bias, dst, hip_stream);
+}
+
+int bcnn_pack_bias_replicated(const void* src, int dtype, int64_t outer, int64_t src_channels,
+                              int64_t inner, int32_t replication, const float* bias, uint32_t* dst,
+                              void* hip_stream)
+{
+    if (!bias || replication < 1 || src_channels < 1) return BCNN_ERR_INVALID_ARG;
+    if (src_channels > INT_MAX / replication) return BCNN_ERR_UNSUPPORTED;
+    return pack_entry(src, dtype, outer, src_channels * replication, src_channels, inner, bias, dst,
+                      hip_stream);
 }
 
 static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const uint32_t* x,
@@ -263,6 +274,9 @@ int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_pack
     if (!x_packed || !w_packed || !ep || !ep->bn_scale || !ep->bn_bias) return BCNN_ERR_INVALID_ARG;
     if (!r && !x_next_packed) return BCNN_ERR_INVALID_ARG;
     if (ep->real_dtype != BCNN_F32 && ep->real_dtype != BCNN_F16) return BCNN_ERR_UNSUPPORTED;
+    const int id_channels = ep->identity_channels ? ep->identity_channels : s.c_out;
+    if (id_channels < 1 || id_channels > s.c_out) return BCNN_ERR_INVALID_ARG;
+    if (id_channels != s.c_out && ep->identity && ep->identity == r) return BCNN_ERR_INVALID_ARG;
     const uintptr_t esz = ep->real_dtype == BCNN_F32 ? 4 : 2;
     if (static_cast<const void*>(x_packed) == static_cast<const void*>(x_next_packed) ||
         static_cast<const void*>(x_packed) == r)
@@ -274,6 +288,7 @@ int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_pack
         return BCNN_ERR_ALIGNMENT;
     bcnn::ModuleEp m;
     m.scale = ep->bn_scale; m.bias = ep->bn_bias; m.identity = ep->identity; m.slope = ep->prelu_slope;
+    m.id_channels = id_channels;
     m.next_bias = ep->next_bias; m.r = r; m.x_next = x_next_packed; m.half = ep->real_dtype == BCNN_F16;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e;

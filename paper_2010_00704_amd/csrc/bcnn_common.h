@@ -25,7 +25,8 @@ struct ConvShape {
 struct ModuleEp {
     const float* scale;      // [c_out]
     const float* bias;       // [c_out]
-    const void* identity;    // [m][c_out] float or half, or nullptr
+    const void* identity;    // [m][id_channels] float or half, or nullptr; channel o reads o mod id_channels
+    int32_t id_channels;     // c_out unless the identity stream is replicated by bookkeeping
     const float* slope;      // [c_out] or nullptr (no activation)
     const float* next_bias;  // [c_out] or nullptr (0)
     void* r;                 // [m][c_out] float or half, or nullptr
@@ -48,9 +49,10 @@ __device__ __forceinline__ float module_value(float y, float g, float b, bool ha
 }
 
 // Launchers, one per kernel family.  Each returns the hipError_t of its launch.
-// bias: per-channel float added before the sign, or nullptr
+// bias: per-channel float added before the sign, or nullptr.  src_channels < channels: the source
+// has src_channels channels and output channel c reads source channel c mod src_channels.
 hipError_t launch_pack(const void* src, int dtype, const float* bias, int64_t outer, int64_t channels,
-                       int64_t inner, uint32_t* dst, hipStream_t stream);
+                       int64_t src_channels, int64_t inner, uint32_t* dst, hipStream_t stream);
 hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows,
                                       int64_t c_out, uint32_t* y_packed, hipStream_t stream);
 // ep != nullptr: module epilogue (thr and out are ignored)

@@ -680,7 +680,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH_F32) ? 2 : 1)) v
         const int c0 = o0 + 64 * wc + 4 * cgrp;                // this lane's first channel after the transpose
         const bool vec_ok = (s.c_out % 4 == 0) &&
                             ((reinterpret_cast<uintptr_t>(MODULE ? ep.r : out) & (HALF ? 7 : 15)) == 0) &&
-                            (!MODULE || (reinterpret_cast<uintptr_t>(ep.identity) & (HALF ? 7 : 15)) == 0);
+                            (!MODULE || ((reinterpret_cast<uintptr_t>(ep.identity) & (HALF ? 7 : 15)) == 0 &&
+                                         ep.id_channels % 4 == 0));
         // per-channel parameters of the lane's four channels (clamped loads for a ragged c_out)
         float pg[4], pb_[4], pa[4], pc[4];
         if constexpr (MODULE) {
@@ -707,13 +708,16 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH_F32) ? 2 : 1)) v
                 const int m = m0 + 32 * (PB * wp + pb) + 4 * g + prow;
                 real4 t4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
                 if (ep.identity && m < s.m) {
-                    const real_t* idp = static_cast<const real_t*>(ep.identity) + (size_t)m * s.c_out + c0;
-                    if (vec_ok && c0 + 4 <= s.c_out) {
-                        t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(idp));
+                    // the identity stream may have fewer channels than the output
+                    // (replication by bookkeeping): channel o reads o mod id_channels
+                    const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels;
+                    const int id0 = c0 % ep.id_channels;
+                    if (vec_ok && c0 + 4 <= s.c_out) {      // id_channels % 4 == 0: the four stay together
+                        t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(idrow + id0));
                     } else {
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            if (c0 + k < s.c_out) t4[k] = idp[k];
+                            if (c0 + k < s.c_out) t4[k] = idrow[(id0 + k) % ep.id_channels];
                     }
                 }
                 dst[g] = t4;

@@ -73,9 +73,14 @@ __device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp&
     constexpr int PER = HALF ? 8 : 4;                  // elements per 16-byte vector
     typedef real_t realv __attribute__((ext_vector_type(PER)));
     const size_t row = (size_t)m * s.c_out + t.o0;
-    const real_t* idp = static_cast<const real_t*>(ep.identity) + row;
+    // the identity stream may have fewer channels than the output (replication by
+    // bookkeeping): channel o reads o mod id_channels
+    const int idc = ep.id_channels;
+    const int id0 = t.o0 % idc;
+    const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * idc;
+    const real_t* idp = idrow + id0;
     real_t* rp = static_cast<real_t*>(ep.r) + row;
-    const bool vec = FULL && (s.c_out % PER == 0) &&
+    const bool vec = FULL && (s.c_out % PER == 0) && (idc % PER == 0) && (id0 + TN <= idc) &&
                      ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & 15) == 0;
     float idv[TN];
 #pragma unroll
@@ -91,7 +96,7 @@ __device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp&
         } else {
 #pragma unroll
             for (int o = 0; o < TN; ++o)
-                if (FULL || t.stores(o)) idv[o] = (float)idp[o];
+                if (FULL || t.stores(o)) idv[o] = (float)idrow[(id0 + o) % idc];
         }
     }
     const int ob = FULL ? t.o0 : 0;                    // FULL: plain offsets from the tile's first channel

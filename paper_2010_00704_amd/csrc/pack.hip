@@ -25,6 +25,17 @@ __device__ __forceinline__ bool bit_of(T v, const float* __restrict__ bias, int6
     else return nonneg(v);
 }
 
+// Channel replication by bookkeeping (Section 4.2.2 of the paper: a building
+// block that widens the network sees every real channel R times; no copy of the
+// real map is made): output channel c reads source channel c mod src_channels,
+// while the bias stays indexed by c.  REP == false: src_channels == channels.
+template <bool REP>
+__device__ __forceinline__ int64_t src_channel(int64_t c, int64_t src_channels)
+{
+    if constexpr (REP) return (int64_t)((uint32_t)c % (uint32_t)src_channels);   // both below 2^31
+    else return c;
+}
+
 // ---- [outer][C][inner] with inner >= 64: lanes run along `inner` ------------
 // One thread owns one inner position and builds `cwg` consecutive words of that
 // pixel.  For a fixed channel the 256 threads of a block read 256 consecutive
@@ -35,10 +46,10 @@ __device__ __forceinline__ bool bit_of(T v, const float* __restrict__ bias, int6
 constexpr int PACK_THREADS = 256;
 constexpr int PACK_CW_CHUNK = 8;  // most words per block: 256*8*4 B = 8 KB LDS
 
-template <typename T, bool BIAS>
+template <typename T, bool BIAS, bool REP>
 __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
-    const T* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t inner,
-    int64_t cw_total, int cwg, int groups, uint32_t* __restrict__ dst)
+    const T* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t src_channels,
+    int64_t inner, int64_t cw_total, int cwg, int groups, uint32_t* __restrict__ dst)
 {
     __shared__ uint32_t stage[PACK_THREADS * PACK_CW_CHUNK];
     const int64_t a = blockIdx.y / groups;
@@ -48,7 +59,7 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
     const int64_t i = i0 + tid;
     const bool live = i < inner;
     const int64_t icl = live ? i : inner - 1;
-    const T* col = src + a * channels * inner + icl;
+    const T* col = src + a * src_channels * inner + icl;
     const int rows_here = (int)((inner - i0 < PACK_THREADS) ? (inner - i0) : PACK_THREADS);
     const int jn = (int)((cw_total - j0 < cwg) ? (cw_total - j0) : cwg);
 
@@ -58,12 +69,13 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
         if (c0 + 32 <= channels) {
             T v[32];
 #pragma unroll
-            for (int b = 0; b < 32; ++b) v[b] = __builtin_nontemporal_load(col + (c0 + b) * inner);
+            for (int b = 0; b < 32; ++b)
+                v[b] = __builtin_nontemporal_load(col + src_channel<REP>(c0 + b, src_channels) * inner);
 #pragma unroll
             for (int b = 0; b < 32; ++b) word |= (uint32_t)bit_of<BIAS>(v[b], bias, c0 + b) << b;
         } else {
             for (int b = 0; c0 + b < channels; ++b)
-                word |= (uint32_t)bit_of<BIAS>(col[(c0 + b) * inner], bias, c0 + b) << b;
+                word |= (uint32_t)bit_of<BIAS>(col[src_channel<REP>(c0 + b, src_channels) * inner], bias, c0 + b) << b;
         }
         stage[tid * jn + j] = word;
     }
@@ -80,10 +92,10 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
 // 16-byte non-temporal loads (four consecutive pixels of one channel); the 32
 // channel loads of a word are issued in two batches of 16.  This is the form
 // that gets closest to the chip's read bandwidth.
-template <bool BIAS>
+template <bool BIAS, bool REP>
 __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
-    const float* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t inner,
-    int64_t cw_total, int cwg, int groups, uint32_t* __restrict__ dst)
+    const float* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t src_channels,
+    int64_t inner, int64_t cw_total, int cwg, int groups, uint32_t* __restrict__ dst)
 {
     typedef float f4 __attribute__((ext_vector_type(4)));
     __shared__ uint32_t stage[PACK_THREADS * 4 * PACK_CW_CHUNK];
@@ -94,7 +106,7 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
     const int64_t i = i0 + 4 * tid;
     const bool live = i < inner;                       // inner % 4 == 0: all four pixels or none
     const int64_t icl = live ? i : inner - 4;
-    const float* col = src + a * channels * inner + icl;
+    const float* col = src + a * src_channels * inner + icl;
     const int64_t rest = inner - i0;
     const int rows_here = (int)(rest < PACK_THREADS * 4 ? rest : PACK_THREADS * 4);
     const int jn = (int)((cw_total - j0 < cwg) ? (cw_total - j0) : cwg);
@@ -108,7 +120,8 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
                 f4 v[16];
 #pragma unroll
                 for (int b = 0; b < 16; ++b)
-                    v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(col + (c0 + 16 * half + b) * inner));
+                    v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(
+                        col + src_channel<REP>(c0 + 16 * half + b, src_channels) * inner));
 #pragma unroll
                 for (int b = 0; b < 16; ++b) {
                     w0 |= (uint32_t)bit_of<BIAS>(v[b][0], bias, c0 + 16 * half + b) << (16 * half + b);
@@ -119,7 +132,7 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
             }
         } else {
             for (int b = 0; c0 + b < channels; ++b) {
-                const f4 v = *reinterpret_cast<const f4*>(col + (c0 + b) * inner);
+                const f4 v = *reinterpret_cast<const f4*>(col + src_channel<REP>(c0 + b, src_channels) * inner);
                 w0 |= (uint32_t)bit_of<BIAS>(v[0], bias, c0 + b) << b;
                 w1 |= (uint32_t)bit_of<BIAS>(v[1], bias, c0 + b) << b;
                 w2 |= (uint32_t)bit_of<BIAS>(v[2], bias, c0 + b) << b;
@@ -146,10 +159,10 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
 // consecutive elements).  A thread ORs its rows' sign bits into partial words,
 // the R partials of a pixel meet in LDS.  A block packs up to 8 words (256
 // channels) of one `outer` index.
-template <typename T, int IP, bool BIAS>
+template <typename T, int IP, bool BIAS, bool REP>
 __global__ __launch_bounds__(256) void pack_small_inner_kernel(
-    const T* __restrict__ src, const float* __restrict__ bias, int64_t channels, int inner,
-    int64_t cw_total, int groups, uint32_t* __restrict__ dst)
+    const T* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t src_channels,
+    int inner, int64_t cw_total, int groups, uint32_t* __restrict__ dst)
 {
     constexpr int R = 256 / IP;          // channel rows per pass
     constexpr int PASSES = 32 / R;       // passes per output word (R divides 32 as IP >= 8)
@@ -159,7 +172,7 @@ __global__ __launch_bounds__(256) void pack_small_inner_kernel(
     const int64_t j0 = (int64_t)(blockIdx.x % groups) * G;
     const int i = threadIdx.x % IP, q = threadIdx.x / IP;
     const bool live = i < inner;
-    const T* base = src + a * channels * inner + (live ? i : 0);
+    const T* base = src + a * src_channels * inner + (live ? i : 0);
     const int jn = (int)((cw_total - j0 < G) ? (cw_total - j0) : G);
     for (int j = 0; j < jn; ++j) {
         const int64_t c0 = (j0 + j) * 32;
@@ -168,14 +181,15 @@ __global__ __launch_bounds__(256) void pack_small_inner_kernel(
             T v[PASSES];
 #pragma unroll
             for (int k = 0; k < PASSES; ++k)
-                v[k] = __builtin_nontemporal_load(base + (c0 + q + R * k) * inner);
+                v[k] = __builtin_nontemporal_load(base + src_channel<REP>(c0 + q + R * k, src_channels) * inner);
 #pragma unroll
             for (int k = 0; k < PASSES; ++k)
                 word |= (uint32_t)bit_of<BIAS>(v[k], bias, c0 + q + R * k) << (q + R * k);
         } else {
             for (int k = 0; k < PASSES; ++k) {
                 const int64_t c = c0 + q + R * k;
-                if (c < channels) word |= (uint32_t)bit_of<BIAS>(base[c * inner], bias, c) << (q + R * k);
+                if (c < channels)
+                    word |= (uint32_t)bit_of<BIAS>(base[src_channel<REP>(c, src_channels) * inner], bias, c) << (q + R * k);
             }
         }
         part[j][q][i] = live ? word : 0u;
@@ -195,10 +209,10 @@ __global__ __launch_bounds__(256) void pack_small_inner_kernel(
 // One wave per (row, 64-channel group); the wave-wide ballot IS the two packed
 // words.  Reads are perfectly coalesced.  ROWS rows are handled per wave so
 // that several loads are in flight.
-template <typename T, int ROWS, bool BIAS>
+template <typename T, int ROWS, bool BIAS, bool REP>
 __global__ __launch_bounds__(256) void pack_rows_kernel(
     const T* __restrict__ src, const float* __restrict__ bias, int64_t rows, int64_t channels,
-    int64_t cw_total, uint32_t* __restrict__ dst)
+    int64_t src_channels, int64_t cw_total, uint32_t* __restrict__ dst)
 {
     const int lane = threadIdx.x & 63;
     const int64_t groups = (channels + 63) / 64;
@@ -211,7 +225,8 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
         const int64_t r = r0 + k;
-        bit[k] = (r < rows && c < channels) ? bit_of<BIAS>(src[r * channels + c], bias, c) : false;
+        bit[k] = (r < rows && c < channels)
+                     ? bit_of<BIAS>(src[r * src_channels + src_channel<REP>(c, src_channels)], bias, c) : false;
     }
 #pragma unroll
     for (int k = 0; k < ROWS; ++k) {
@@ -223,10 +238,10 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(
 }
 
 // ---- anything else (small inner, e.g. 3x3 filter taps): one thread per word --
-template <typename T, bool BIAS>
+template <typename T, bool BIAS, bool REP>
 __global__ __launch_bounds__(256) void pack_generic_kernel(
     const T* __restrict__ src, const float* __restrict__ bias, int64_t outer, int64_t channels,
-    int64_t inner, int64_t cw_total, uint32_t* __restrict__ dst)
+    int64_t src_channels, int64_t inner, int64_t cw_total, uint32_t* __restrict__ dst)
 {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= outer * inner * cw_total) return;
@@ -236,14 +251,16 @@ __global__ __launch_bounds__(256) void pack_generic_kernel(
     uint32_t word = 0;
     for (int b = 0; b < 32; ++b) {
         const int64_t c = j * 32 + b;
-        if (c < channels) word |= (uint32_t)bit_of<BIAS>(src[(a * channels + c) * inner + i], bias, c) << b;
+        if (c < channels)
+            word |= (uint32_t)bit_of<BIAS>(src[(a * src_channels + src_channel<REP>(c, src_channels)) * inner + i],
+                                           bias, c) << b;
     }
     dst[t] = word;
 }
 
-template <typename T, bool BIAS>
-hipError_t pack_dispatch(const T* src, const float* bias, int64_t outer, int64_t channels, int64_t inner,
-                         uint32_t* dst, hipStream_t stream)
+template <typename T, bool BIAS, bool REP>
+hipError_t pack_dispatch(const T* src, const float* bias, int64_t outer, int64_t channels,
+                         int64_t src_channels, int64_t inner, uint32_t* dst, hipStream_t stream)
 {
     const int64_t cw = (channels + 31) / 32;
     if (inner == 1) {
@@ -251,8 +268,8 @@ hipError_t pack_dispatch(const T* src, const float* bias, int64_t outer, int64_t
         const int64_t groups = (channels + 63) / 64;
         const int64_t waves = ((outer + ROWS - 1) / ROWS) * groups;
         const int64_t blocks = (waves + 3) / 4;
-        hipLaunchKernelGGL((pack_rows_kernel<T, ROWS, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           src, bias, outer, channels, cw, dst);
+        hipLaunchKernelGGL((pack_rows_kernel<T, ROWS, BIAS, REP>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           src, bias, outer, channels, src_channels, cw, dst);
     } else if (std::is_same<T, float>::value && inner >= 256 && inner % 4 == 0 &&
                (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
         const int64_t bx = (inner + PACK_THREADS * 4 - 1) / (PACK_THREADS * 4);
@@ -260,9 +277,9 @@ hipError_t pack_dispatch(const T* src, const float* bias, int64_t outer, int64_t
         while (cwg > 1 && bx * outer * ((cw + cwg - 1) / cwg) < 512) cwg >>= 1;
         const int64_t groups = (cw + cwg - 1) / cwg;
         if (outer * groups > 65535) goto generic;
-        hipLaunchKernelGGL((pack_columns4_kernel<BIAS>), dim3((unsigned)bx, (unsigned)(outer * groups)),
+        hipLaunchKernelGGL((pack_columns4_kernel<BIAS, REP>), dim3((unsigned)bx, (unsigned)(outer * groups)),
                            dim3(PACK_THREADS), 0, stream, reinterpret_cast<const float*>(src), bias, channels,
-                           inner, cw, cwg, (int)groups, dst);
+                           src_channels, inner, cw, cwg, (int)groups, dst);
     } else if (inner >= 64) {
         const int64_t bx = (inner + PACK_THREADS - 1) / PACK_THREADS;
         // words per block: as many as possible (up to 8) while two blocks per CU remain
@@ -270,30 +287,31 @@ hipError_t pack_dispatch(const T* src, const float* bias, int64_t outer, int64_t
         while (cwg > 1 && bx * outer * ((cw + cwg - 1) / cwg) < 512) cwg >>= 1;
         const int64_t groups = (cw + cwg - 1) / cwg;
         if (outer * groups > 65535) goto generic;
-        hipLaunchKernelGGL((pack_columns_kernel<T, BIAS>), dim3((unsigned)bx, (unsigned)(outer * groups)),
-                           dim3(PACK_THREADS), 0, stream, src, bias, channels, inner, cw, cwg, (int)groups, dst);
+        hipLaunchKernelGGL((pack_columns_kernel<T, BIAS, REP>), dim3((unsigned)bx, (unsigned)(outer * groups)),
+                           dim3(PACK_THREADS), 0, stream, src, bias, channels, src_channels, inner, cw, cwg,
+                           (int)groups, dst);
     } else if (inner >= 5) {
         const int64_t groups = (cw + 7) / 8;
         const int64_t blocks = outer * groups;
         if (blocks > 0x7FFFFFFF) goto generic;
         if (inner > 32)
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 64, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, bias, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 64, BIAS, REP>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, src_channels, (int)inner, cw, (int)groups, dst);
         else if (inner > 16)
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 32, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, bias, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 32, BIAS, REP>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, src_channels, (int)inner, cw, (int)groups, dst);
         else if (inner > 8)
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 16, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, bias, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 16, BIAS, REP>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, src_channels, (int)inner, cw, (int)groups, dst);
         else
-            hipLaunchKernelGGL((pack_small_inner_kernel<T, 8, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                               src, bias, channels, (int)inner, cw, (int)groups, dst);
+            hipLaunchKernelGGL((pack_small_inner_kernel<T, 8, BIAS, REP>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                               src, bias, channels, src_channels, (int)inner, cw, (int)groups, dst);
     } else {
     generic:
         const int64_t total = outer * inner * cw;
         const int64_t blocks = (total + 255) / 256;
-        hipLaunchKernelGGL((pack_generic_kernel<T, BIAS>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           src, bias, outer, channels, inner, cw, dst);
+        hipLaunchKernelGGL((pack_generic_kernel<T, BIAS, REP>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           src, bias, outer, channels, src_channels, inner, cw, dst);
     }
     return hipGetLastError();
 }
@@ -383,20 +401,23 @@ __global__ __launch_bounds__(256) void diag_copy_kernel(const uint32_t* __restri
 }  // namespace
 
 template <typename T>
-hipError_t pack_typed(const void* src, const float* bias, int64_t outer, int64_t channels, int64_t inner,
-                      uint32_t* dst, hipStream_t stream)
+hipError_t pack_typed(const void* src, const float* bias, int64_t outer, int64_t channels,
+                      int64_t src_channels, int64_t inner, uint32_t* dst, hipStream_t stream)
 {
-    if (bias) return pack_dispatch<T, true>(static_cast<const T*>(src), bias, outer, channels, inner, dst, stream);
-    return pack_dispatch<T, false>(static_cast<const T*>(src), nullptr, outer, channels, inner, dst, stream);
+    const T* p = static_cast<const T*>(src);
+    if (src_channels != channels)   // replication always comes with a bias
+        return pack_dispatch<T, true, true>(p, bias, outer, channels, src_channels, inner, dst, stream);
+    if (bias) return pack_dispatch<T, true, false>(p, bias, outer, channels, channels, inner, dst, stream);
+    return pack_dispatch<T, false, false>(p, nullptr, outer, channels, channels, inner, dst, stream);
 }
 
 hipError_t launch_pack(const void* src, int dtype, const float* bias, int64_t outer, int64_t channels,
-                       int64_t inner, uint32_t* dst, hipStream_t stream)
+                       int64_t src_channels, int64_t inner, uint32_t* dst, hipStream_t stream)
 {
     switch (dtype) {
-        case 0: return pack_typed<float>(src, bias, outer, channels, inner, dst, stream);
-        case 1: return pack_typed<_Float16>(src, bias, outer, channels, inner, dst, stream);
-        case 2: return pack_typed<int8_t>(src, bias, outer, channels, inner, dst, stream);
+        case 0: return pack_typed<float>(src, bias, outer, channels, src_channels, inner, dst, stream);
+        case 1: return pack_typed<_Float16>(src, bias, outer, channels, src_channels, inner, dst, stream);
+        case 2: return pack_typed<int8_t>(src, bias, outer, channels, src_channels, inner, dst, stream);
         default: return hipErrorInvalidValue;
     }
 }

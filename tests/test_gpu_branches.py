@@ -104,6 +104,35 @@ def test_pack_bias(dev, outer, channels, inner, dtype):
     assert np.array_equal(got, want)
 
 
+REPLICATED_SHAPES = [
+    # outer, source channels, inner, replication   (every kernel family; ragged and word-aligned channel counts)
+    (5, 35, 1, 2), (3, 32, 49, 4), (2, 50, 9, 3), (2, 33, 300, 2), (2, 32, 784, 8), (1, 16, 4, 2), (3, 64, 1, 3),
+    (2, 64, 1024, 2),
+]
+
+
+@pytest.mark.parametrize("outer,src_channels,inner,rep", REPLICATED_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_pack_bias_replicated(dev, outer, src_channels, inner, rep, dtype):
+    """Section 4.2.2: channels replicated by bookkeeping, one bias per replicated
+    channel; the oracle makes the copy for real."""
+    seed = 7500 + outer * 131 + src_channels * 7 + inner + rep
+    x = W.real_with_sign(seed, W.pm1(seed, (outer, src_channels, inner)))
+    if dtype == "f16":
+        x = x.astype(np.float16)
+    channels = src_channels * rep
+    bias = W.uniform_f32(seed + 2, (channels,), -1.5, 1.5)
+    x32 = x.astype(np.float32)
+    for k in range(min(channels, 6)):
+        bias[channels - 1 - k] = -x32[k % outer, (channels - 1 - k) % src_channels, (5 * k) % inner]
+    want = oracle.pack_channels(oracle.sign_bias_f32(oracle.replicate_channels(x32, rep), bias))
+    cw = (channels + 31) // 32
+    out = Guarded(outer * inner * cw, dev)
+    B.check(B.bcnn_pack_bias_replicated(torch.from_numpy(x).to(dev), B.BCNN_F16 if dtype == "f16" else B.BCNN_F32,
+                                        outer, src_channels, inner, rep, up(bias, dev), out.ptr), "pack_rep")
+    assert np.array_equal(out.get().reshape(outer, inner, cw), want)
+
+
 def test_pack_bias_rejects_missing_bias(dev):
     x = torch.zeros((1, 32, 4), dtype=torch.float32, device=dev)
     out = torch.zeros((4,), dtype=torch.int32, device=dev)

@@ -198,6 +198,45 @@ def test_module_table1_shapes(dev, level, half):
     assert np.array_equal(bits, want_bits)
 
 
+@pytest.mark.parametrize("shape", [(2, 128, 24, 24, 128, 1, 1, 0, 64), (1, 256, 30, 30, 192, 1, 1, 0, 48),
+                                   (2, 64, 14, 14, 96, 1, 1, 0, 32), (3, 96, 9, 9, 70, 3, 1, 1, 35),
+                                   (2, 128, 20, 20, 100, 1, 1, 0, 25)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_module_replicated_identity(dev, shape, variant, half):
+    """Section 4.2.2: the identity stream keeps its channels and is replicated by
+    bookkeeping; the oracle adds a real copy."""
+    n, cin, h, w, o, k, stride, pad, idc = shape
+    seed = 9800 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23, 29))) + half
+    x = W.pm1(seed, (n, cin, h, w), 0.5)
+    wt = W.pm1(seed + 1, (o, cin, k, k))
+    ho = (h + 2 * pad - k) // stride + 1
+    wo = (w + 2 * pad - k) // stride + 1
+    m = n * ho * wo
+    g, b, _, alpha, c = make_params(seed + 2, 1, o, half, False)
+    ident = W.uniform_f32(seed + 9, (m, idc), -40.0, 40.0)
+    if half:
+        ident = ident.astype(np.float16)
+    rep = -(-o // idc)
+    ident_full = oracle.replicate_channels(ident, rep, axis=1)[:, :o]
+    want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident_full, alpha, c, half)
+    desc = B.conv_desc(n, cin, h, w, o, k, stride, pad)
+    xp = up(i32(oracle.pack_channels(x.reshape(n, cin, -1))), dev)
+    wp = up(i32(oracle.pack_channels(wt.reshape(o, cin, -1))), dev)
+    rbuf = Guarded(m * o * (2 if half else 4), dev)
+    cwo = (o + 31) // 32
+    bits = Guarded(m * cwo * 4, dev)
+    rc = B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), up(ident, dev), up(alpha, dev), up(c, dev),
+                                     B.BCNN_F16 if half else B.BCNN_F32, rbuf.ptr, bits.ptr, variant,
+                                     identity_channels=idc)
+    if rc == B.BCNN_ERR_UNSUPPORTED:
+        pytest.skip("variant does not cover this shape")
+    B.check(rc, "module")
+    assert np.array_equal(rbuf.get(np.float16 if half else np.float32, m * o).reshape(m, o), want_r)
+    assert np.array_equal(bits.get(np.uint32, m * cwo).reshape(n, ho * wo, cwo), want_bits)
+
+
 def test_module_argument_checks(dev):
     desc = B.conv_desc(1, 64, 8, 8, 32, 1, 1, 0)
     x = torch.zeros((64 * 2,), dtype=torch.int32, device=dev)

@@ -123,3 +123,22 @@ def test_special_cases():
     # the sums enter linearly: unit scale, zero bias, no identity, no activation returns them
     _, r32_y = oracle.module_epilogue(y, np.ones_like(g), np.zeros_like(b), None, None)
     assert np.array_equal(r32_y, y.astype(np.float32))
+
+
+def test_channel_replication_is_a_plain_copy():
+    """Channel k = j*C + c of the replicated tensor is channel c (checked with
+    explicit loops), on either layout used by the tests."""
+    rng = np.random.default_rng(7)
+    x = rng.normal(size=(2, 5, 3)).astype(np.float32)          # [outer, C, inner]
+    y = oracle.replicate_channels(x, 3)
+    assert y.shape == (2, 15, 3)
+    for a in range(2):
+        for k in range(15):
+            for i in range(3):
+                assert y[a, k, i] == x[a, k % 5, i]
+    rows = rng.normal(size=(4, 6)).astype(np.float32)          # [rows, C]
+    z = oracle.replicate_channels(rows, 2, axis=1)
+    assert z.shape == (4, 12) and all(z[m, k] == rows[m, k % 6] for m in range(4) for k in range(12))
+    assert np.array_equal(oracle.replicate_channels(x, 1), x)
+    with pytest.raises(ValueError):
+        oracle.replicate_channels(x, 0)
