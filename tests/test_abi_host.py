@@ -135,3 +135,50 @@ def test_config_table_matches_the_stated_shapes():
     assert ops[3] == 2 * 50176 * 512 * 2304
     assert ops[4] == 4 * 2 * 12544 * 1024 * 9216
     assert W.out_hw(W.CONFIGS[3]) == (28, 28)
+
+
+def test_widened_entry_points_reject_bad_arguments():
+    """bcnn_pack_bias[_replicated], the branch calls and the module call check
+    their arguments on the host before any launch."""
+    L = B.lib()
+    d3 = B.bcnn_conv_desc(n=1, c_in=64, h=8, w=8, c_out=32, kh=3, kw=3, stride=1, pad=1)
+    d1 = B.bcnn_conv_desc(n=1, c_in=64, h=8, w=8, c_out=32, kh=1, kw=1, stride=1, pad=0)
+    x, w, g, z, p = FAKE, FAKE + 0x1000, FAKE + 0x2000, FAKE + 0x3000, FAKE + 0x4000
+    # pack with bias / replication
+    assert L.bcnn_pack_bias(x, B.BCNN_F32, 1, 32, 4, None, z, None) == B.BCNN_ERR_INVALID_ARG
+    assert L.bcnn_pack_bias(x, B.BCNN_F32, 1, 32, 4, g + 2, z, None) == B.BCNN_ERR_ALIGNMENT
+    assert L.bcnn_pack_bias(x, 9, 1, 32, 4, g, z, None) == B.BCNN_ERR_UNSUPPORTED
+    assert L.bcnn_pack_bias_replicated(x, B.BCNN_F32, 1, 32, 4, 0, g, z, None) == B.BCNN_ERR_INVALID_ARG
+    assert L.bcnn_pack_bias_replicated(x, B.BCNN_F32, 1, 0, 4, 2, g, z, None) == B.BCNN_ERR_INVALID_ARG
+    assert L.bcnn_pack_bias_replicated(x, B.BCNN_F32, 1, 1 << 30, 4, 4, g, z, None) == B.BCNN_ERR_UNSUPPORTED
+    # branches
+    f = L.bcnn_conv2d_binary_branches
+    assert f(ctypes.byref(d3), 9, x, 0, w, None, 0, g, None, None, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert f(ctypes.byref(d3), 8, x, 0, w, None, 0, g, None, z, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert f(ctypes.byref(d1), 0, x, 0, w, None, 0, g, None, z, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert f(ctypes.byref(d1), 2000, x, 0, w, None, 0, g, None, z, 0, None) == B.BCNN_ERR_UNSUPPORTED
+    assert f(ctypes.byref(d3), 9, x, 1, w, None, 0, g, None, z, 0, None) == B.BCNN_ERR_INVALID_ARG  # stride < tensor
+    assert f(ctypes.byref(d3), 9, x, 0, w, None, 5, g, None, z, 0, None) == B.BCNN_ERR_INVALID_ARG  # pad mode
+    assert f(ctypes.byref(d3), 9, x, 0, w, p + 1, 0, g, None, z, 0, None) == B.BCNN_ERR_ALIGNMENT
+    assert f(ctypes.byref(d3), 9, x, 0, w, None, 0, g, None, z, 77, None) == B.BCNN_ERR_UNSUPPORTED  # variant
+    assert f(ctypes.byref(d3), 9, x, 0, w, None, 0, g, None, z, B.BCNN_VARIANT_MFMA_FP4, None) \
+        == B.BCNN_ERR_UNSUPPORTED                                                  # c_in not a multiple of 256
+    assert L.bcnn_conv2d_binary_branches_sign_pack(ctypes.byref(d3), 9, x, 0, w, None, 0, g, None, x, 0, None) \
+        == B.BCNN_ERR_INVALID_ARG                                                  # output aliases input
+    # module
+    def ep(**kw):
+        base = dict(bn_scale=g, bn_bias=g + 0x100, identity=None, prelu_slope=None, next_bias=None,
+                    real_dtype=B.BCNN_F32, identity_channels=0)
+        base.update(kw)
+        return B.bcnn_module_epilogue(**base)
+    m = L.bcnn_conv2d_binary_module
+    assert m(ctypes.byref(d1), x, w, None, z, p, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep()), None, None, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep(bn_scale=None)), z, p, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep(real_dtype=B.BCNN_I8)), z, p, 0, None) == B.BCNN_ERR_UNSUPPORTED
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep(identity_channels=33)), z, p, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep(identity=z, identity_channels=16)), z, p, 0, None) \
+        == B.BCNN_ERR_INVALID_ARG                                                  # replicated identity in place
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep(real_dtype=B.BCNN_F16)), z + 1, p, 0, None) == B.BCNN_ERR_ALIGNMENT
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep()), z, p, B.BCNN_VARIANT_MFMA_I8, None) == B.BCNN_ERR_UNSUPPORTED
+    assert m(ctypes.byref(d1), x, w, ctypes.byref(ep()), z, p, B.BCNN_VARIANT_MFMA_FP4, None) == B.BCNN_ERR_UNSUPPORTED
