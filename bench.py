@@ -290,6 +290,18 @@ def aux_measurements(torch, B, dev, work):
     out["valu_probe_tbops"] = round(tbops, 1)
     out["valu_probe_implied_ghz"] = round(tbops / (256 * 64 * 32) * 1e3, 3)
 
+    # matrix-core issue-rate probe: blocks*4 waves * iters * 8 MFMAs * 2*32*32*64 FLOP, random +-1 fp4
+    # operands in registers: what the matrix cores sustain on this kind of data (clock under load included)
+    for tag, mblocks in (("mfma_fp4_probe_tflops", 256), ("mfma_fp4_probe_224cu_tflops", 224)):
+        fsink = torch.empty(mblocks * 256, dtype=torch.float32, device=dev)
+        B.check(B.bcnn_diag_mfma_fp4_peak(fsink, mblocks, 50), "mfma peak")
+        a, b = ev(), ev()
+        a.record()
+        B.check(B.bcnn_diag_mfma_fp4_peak(fsink, mblocks, 4000), "mfma peak")
+        b.record()
+        b.synchronize()
+        out[tag] = round(mblocks * 4 * 4000 * 8 * 2.0 * 32 * 32 * 64 / (a.elapsed_time(b) * 1e-3) / 1e12, 1)
+
     # pack kernel on the largest input (shape 4, 205 MB fp32), 4 rotating copies
     wk = work[3]
     cfg = wk["cfg"]

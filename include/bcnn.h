@@ -266,9 +266,14 @@ const char *bcnn_status_string(int status);
  *   xor + popcount-accumulate pairs on registers and writes one word to
  *   sink[global thread id]; sink holds blocks*256 words.  Times the vector
  *   ALUs' xor/popcount issue rate with no memory traffic.
+ * bcnn_diag_mfma_fp4_peak: every wave issues `iters` rounds of 8 independent
+ *   32x32x64 fp4 matrix instructions on random +-1 operands held in registers
+ *   and writes one float to sink[global thread id] (blocks*256 floats).  Times
+ *   the rate the matrix cores sustain on this kind of data.
  */
 int bcnn_diag_copy_u32(const uint32_t *src, uint32_t *dst, int64_t words, void *hip_stream);
 int bcnn_diag_valu_peak(uint32_t *sink, int32_t blocks, int32_t iters, void *hip_stream);
+int bcnn_diag_mfma_fp4_peak(float *sink, int32_t blocks, int32_t iters, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,7 @@ EXPORTS = (
     "bcnn_conv2d_binary_variant", "bcnn_threshold_sign_pack", "bcnn_out_dim",
     "bcnn_status_string", "bcnn_diag_copy_u32", "bcnn_diag_valu_peak",
     "bcnn_pack_bias", "bcnn_conv2d_binary_branches", "bcnn_conv2d_binary_branches_sign_pack",
-    "bcnn_conv2d_binary_module", "bcnn_pack_bias_replicated",
+    "bcnn_conv2d_binary_module", "bcnn_pack_bias_replicated", "bcnn_diag_mfma_fp4_peak",
 )
 
 
@@ -73,6 +73,7 @@ def lib():
         L.bcnn_status_string.restype = ctypes.c_char_p
         L.bcnn_diag_copy_u32.argtypes = [vp, vp, i64, vp]
         L.bcnn_diag_valu_peak.argtypes = [vp, i32, i32, vp]
+        L.bcnn_diag_mfma_fp4_peak.argtypes = [vp, i32, i32, vp]
         L.bcnn_pack_bias.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp]
         L.bcnn_pack_bias_replicated.argtypes = [vp, ctypes.c_int, i64, i64, i64, i32, vp, vp, vp]
         L.bcnn_conv2d_binary_branches.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp]
@@ -186,6 +187,10 @@ def bcnn_diag_copy_u32(src, dst, words, stream=None):
 
 def bcnn_diag_valu_peak(sink, blocks, iters, stream=None):
     return lib().bcnn_diag_valu_peak(_ptr(sink), blocks, iters, _stream(stream))
+
+
+def bcnn_diag_mfma_fp4_peak(sink, blocks, iters, stream=None):
+    return lib().bcnn_diag_mfma_fp4_peak(_ptr(sink), blocks, iters, _stream(stream))
 
 
 def check(status, where="bcnn"):

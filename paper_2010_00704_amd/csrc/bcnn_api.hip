@@ -39,6 +39,35 @@ __global__ __launch_bounds__(256) void diag_valu_peak_kernel(uint32_t* __restric
     sink[gid] = r;
 }
 
+// Matrix-core issue-rate probe: every wave keeps 8 independent accumulators of
+// v_mfma_f32_32x32x64_f8f6f4 busy with fp4 operands that are random +-1 (the
+// codes 0x2 / 0xA, as in the convolution), held in registers; no memory traffic.
+typedef int diag_v8i __attribute__((ext_vector_type(8)));
+typedef float diag_v16f __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void diag_mfma_fp4_peak_kernel(float* __restrict__ sink, int iters)
+{
+    uint32_t seed = (blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
+    diag_v8i a[2], b[4];
+    for (int q = 0; q < 6; ++q)
+        for (int j = 0; j < 8; ++j) {
+            seed = seed * 1664525u + 1013904223u;
+            const int v = j < 4 ? (int)((seed & 0x88888888u) | 0x22222222u) : 0;
+            if (q < 2) a[q][j] = v; else b[q - 2][j] = v;
+        }
+    diag_v16f c[8];
+    for (int n = 0; n < 8; ++n)
+        for (int r = 0; r < 16; ++r) c[n][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n)
+            c[n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[n & 1], b[n >> 1], c[n], 4, 4, 0, 0, 0, 0);
+    }
+    float s = 0.0f;
+    for (int n = 0; n < 8; ++n)
+        for (int r = 0; r < 16; ++r) s += c[n][r];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 int out_dim(int in, int k, int stride, int pad)
@@ -341,6 +370,15 @@ int bcnn_diag_valu_peak(uint32_t* sink, int32_t blocks, int32_t iters, void* hip
     if (!sink || blocks < 1 || iters < 1) return BCNN_ERR_INVALID_ARG;
     if (!bcnn::aligned(sink, 4)) return BCNN_ERR_ALIGNMENT;
     hipLaunchKernelGGL(bcnn::diag_valu_peak_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), sink, iters);
+    return hipGetLastError() == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
+int bcnn_diag_mfma_fp4_peak(float* sink, int32_t blocks, int32_t iters, void* hip_stream)
+{
+    if (!sink || blocks < 1 || iters < 1) return BCNN_ERR_INVALID_ARG;
+    if (!bcnn::aligned(sink, 4)) return BCNN_ERR_ALIGNMENT;
+    hipLaunchKernelGGL(bcnn::diag_mfma_fp4_peak_kernel, dim3((unsigned)blocks), dim3(256), 0,
                        static_cast<hipStream_t>(hip_stream), sink, iters);
     return hipGetLastError() == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
