@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     conv2d_pm1,
     conv2d_pm1_at,
     module_epilogue,
+    module_tail,
     num_threads,
     out_dim,
     pack_channels,

@@ -203,3 +203,38 @@ void oracle_module_epilogue(const int32_t *y, const float *gamma, const float *b
             }
         }
 }
+
+/*
+ * The same tail for a module whose binary part is a sum of parallel branches
+ * (Figure 2, bottom): the branches' scaled sum z (with the batch-norm biases
+ * already in it) takes the place of the batch-norm output; identity addition
+ * and PReLU follow as above.  z64 / z32: [rows][O], either may be NULL
+ * together with its output; identity [rows][O] float or NULL; alpha [O] or
+ * NULL.  Float path, one rounding per step:  t = z + identity;
+ * r = (t >= 0) ? t : alpha[o] * t.
+ */
+void oracle_module_tail(const double *z64, const float *z32, const float *identity,
+                        const float *alpha, int64_t rows, int O, double *r64, float *r32)
+{
+    for (int64_t m = 0; m < rows; ++m)
+        for (int o = 0; o < O; ++o) {
+            const size_t at = (size_t)m * O + o;
+            if (z64 && r64) {
+                double t = z64[at];
+                if (identity)
+                    t += (double)identity[at];
+                r64[at] = (t >= 0.0 || !alpha) ? t : (double)alpha[o] * t;
+            }
+            if (z32 && r32) {
+                volatile float t = z32[at];
+                if (identity)
+                    t = t + identity[at];
+                if (!(t >= 0.0f) && alpha) {
+                    volatile float a = alpha[o] * t;
+                    r32[at] = a;
+                } else {
+                    r32[at] = t;
+                }
+            }
+        }
+}

@@ -60,6 +60,8 @@ def _load():
     lib.oracle_branches_pm1.restype = i32
     lib.oracle_module_epilogue.argtypes = [vp, vp, vp, vp, vp, i64, i32, vp, vp]
     lib.oracle_module_epilogue.restype = None
+    lib.oracle_module_tail.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp]
+    lib.oracle_module_tail.restype = None
     _lib = lib
     return lib
 
@@ -257,6 +259,32 @@ def module_epilogue(y, gamma, beta, identity=None, alpha=None):
                                    _ptr(identity) if identity is not None else None,
                                    _ptr(alpha) if alpha is not None else None,
                                    y.size // o, o, _ptr(r64), _ptr(r32))
+    return r64, r32
+
+
+def module_tail(z64, z32, identity=None, alpha=None):
+    """Identity addition and PReLU on a branch sum z (the tail of a module
+    with parallel branches).  z64 float64 and z32 float32 of the same shape
+    [..., O]; identity float32 of that shape or None; alpha [O] or None ->
+    (r64, r32)."""
+    z64 = np.ascontiguousarray(z64, dtype=np.float64)
+    z32 = np.ascontiguousarray(z32, dtype=np.float32)
+    if z64.shape != z32.shape:
+        raise ValueError("z64 and z32 must have the same shape")
+    o = z32.shape[-1]
+    if identity is not None:
+        identity = np.ascontiguousarray(identity, dtype=np.float32)
+        if identity.shape != z32.shape:
+            raise ValueError("identity must have the shape of z")
+    if alpha is not None:
+        alpha = np.ascontiguousarray(alpha, dtype=np.float32)
+        if alpha.shape != (o,):
+            raise ValueError("alpha must have one entry per output channel")
+    r64 = np.empty(z64.shape, dtype=np.float64)
+    r32 = np.empty(z32.shape, dtype=np.float32)
+    _load().oracle_module_tail(_ptr(z64), _ptr(z32), _ptr(identity) if identity is not None else None,
+                               _ptr(alpha) if alpha is not None else None, z32.size // o, o,
+                               _ptr(r64), _ptr(r32))
     return r64, r32
 
 

@@ -142,3 +142,24 @@ def test_channel_replication_is_a_plain_copy():
     assert np.array_equal(oracle.replicate_channels(x, 1), x)
     with pytest.raises(ValueError):
         oracle.replicate_channels(x, 0)
+
+
+def test_module_tail_continues_the_batch_norm_output():
+    """Identity addition and PReLU applied to a given sum z: fed with the
+    batch-norm output itself it must reproduce the whole epilogue; library
+    prelu in double; hand-worked values of M1 with z = g*y + b."""
+    y, g, b, ident, a = _random_case(5)
+    t64, t32 = oracle.module_epilogue(y, g, b, None, None)          # batch norm alone
+    want64, want32 = oracle.module_epilogue(y, g, b, ident, a)
+    r64, r32 = oracle.module_tail(t64, t32, ident, a)
+    assert np.array_equal(r32, want32) and np.array_equal(r64, want64)
+    tt = torch.from_numpy(t64) + torch.from_numpy(ident.astype(np.float64))
+    lib = F.prelu(tt.T.unsqueeze(0), torch.from_numpy(a.astype(np.float64))).squeeze(0).T.numpy()
+    assert np.allclose(r64, lib, rtol=0, atol=1e-12)
+    case = _golden()[0]
+    z = np.array(case["g"]) * np.array(case["y"], dtype=np.float64) + np.array(case["b"])   # exact binary fractions
+    r64, r32 = oracle.module_tail(z, z.astype(np.float32), np.array(case["identity"], dtype=np.float32), case["a"])
+    assert np.array_equal(r64, np.array(case["r"])) and np.array_equal(r32, np.array(case["r"], dtype=np.float32))
+    # no identity, no slope: z passes through
+    r64, r32 = oracle.module_tail(t64, t32, None, None)
+    assert np.array_equal(r32, t32) and np.array_equal(r64, t64)
