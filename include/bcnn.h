@@ -252,6 +252,24 @@ int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc *desc, int32_t br
                                           const float *bias, uint32_t *z_packed, int variant,
                                           void *hip_stream);
 
+/*
+ * The module with parallel branches (Figure 2, bottom; with kh = kw = 3 the
+ * F x F construction of Section 4.2.1's last paragraph inside a module): the
+ * branch sum z of bcnn_conv2d_binary_branches takes the place of the
+ * batch-norm output and continues, in float32 and one rounding per step, as
+ *   t = z + identity[m][o];  r = t >= 0 ? t : prelu_slope[o] * t
+ *   r is rounded to real_dtype and stored;  bit = (r_stored + next_bias[o] >= 0)
+ * Arguments as in bcnn_conv2d_binary_branches and bcnn_conv2d_binary_module;
+ * ep->bn_scale and ep->bn_bias must be NULL here (scale[branches][c_out] and
+ * bias[c_out] are the branches' batch norms).  c_out below 32 is UNSUPPORTED.
+ */
+int bcnn_conv2d_binary_branches_module(const bcnn_conv_desc *desc, int32_t branches,
+                                       const uint32_t *x_packed, int64_t x_branch_stride,
+                                       const uint32_t *w_packed, const uint32_t *pad_words, int pad_mode,
+                                       const float *scale, const float *bias,
+                                       const bcnn_module_epilogue *ep, void *r, uint32_t *x_next_packed,
+                                       int variant, void *hip_stream);
+
 /* floor((in + 2*pad - k)/stride) + 1, or 0 if the window does not fit. Host only. */
 int bcnn_out_dim(int32_t in, int32_t k, int32_t stride, int32_t pad);
 

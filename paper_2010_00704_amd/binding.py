@@ -29,6 +29,7 @@ EXPORTS = (
     "bcnn_status_string", "bcnn_diag_copy_u32", "bcnn_diag_valu_peak",
     "bcnn_pack_bias", "bcnn_conv2d_binary_branches", "bcnn_conv2d_binary_branches_sign_pack",
     "bcnn_conv2d_binary_module", "bcnn_pack_bias_replicated", "bcnn_diag_mfma_fp4_peak",
+    "bcnn_conv2d_binary_branches_module",
 )
 
 
@@ -80,6 +81,9 @@ def lib():
         L.bcnn_conv2d_binary_branches_sign_pack.argtypes = [dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp]
         L.bcnn_conv2d_binary_module.argtypes = [dp, vp, vp, ctypes.POINTER(bcnn_module_epilogue), vp, vp,
                                                 ctypes.c_int, vp]
+        L.bcnn_conv2d_binary_branches_module.argtypes = [
+            dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, ctypes.POINTER(bcnn_module_epilogue), vp, vp,
+            ctypes.c_int, vp]
         for name in EXPORTS:
             if name != "bcnn_status_string":
                 getattr(L, name).restype = ctypes.c_int
@@ -157,6 +161,17 @@ def bcnn_conv2d_binary_module(desc, x_packed, w_packed, bn_scale, bn_bias, ident
     return lib().bcnn_conv2d_binary_module(ctypes.byref(_desc(desc)), _ptr(x_packed), _ptr(w_packed),
                                            ctypes.byref(ep), _ptr(r), _ptr(x_next_packed), int(variant),
                                            _stream(stream))
+
+
+def bcnn_conv2d_binary_branches_module(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode,
+                                       scale, bias, identity, prelu_slope, next_bias, real_dtype, r,
+                                       x_next_packed, variant=0, stream=None, identity_channels=0):
+    ep = bcnn_module_epilogue(None, None, _ptr(identity), _ptr(prelu_slope), _ptr(next_bias), int(real_dtype),
+                              int(identity_channels))
+    return lib().bcnn_conv2d_binary_branches_module(
+        ctypes.byref(_desc(desc)), int(branches), _ptr(x_packed), int(x_branch_stride), _ptr(w_packed),
+        _ptr(pad_words), int(pad_mode), _ptr(scale), _ptr(bias), ctypes.byref(ep), _ptr(r),
+        _ptr(x_next_packed), int(variant), _stream(stream))
 
 
 def bcnn_conv2d_binary(desc, x_packed, w_packed, y, stream=None):

@@ -208,7 +208,7 @@ int bcnn_pack_bias_replicated(const void* src, int dtype, int64_t outer, int64_t
 }
 
 static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const uint32_t* x,
-                          int64_t x_branch_stride,
+                          int64_t x_branch_stride, const bcnn::ModuleEp* tail,
                           const uint32_t* w, const uint32_t* pad_words, int pad_mode,
                           const float* scale, const float* bias, void* out, bool fused, int variant,
                           void* hip_stream)
@@ -216,14 +216,15 @@ static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const ui
     bcnn::ConvShape s;
     const int rc = bcnn::make_shape(desc, &s);
     if (rc != BCNN_OK) return rc;
-    if (!x || !w || !scale || !out) return BCNN_ERR_INVALID_ARG;
+    if (!x || !w || !scale || (!out && !tail)) return BCNN_ERR_INVALID_ARG;
+    if (tail && s.c_out < 32) return BCNN_ERR_UNSUPPORTED;
     if (pad_mode != BCNN_PAD_WORDS && pad_mode != BCNN_PAD_ZERO) return BCNN_ERR_INVALID_ARG;
     if (branches < 1 || (s.ks > 1 && branches != s.ks * s.ks)) return BCNN_ERR_INVALID_ARG;
     if (branches > 1024 || (int64_t)s.c_out * branches * s.cw > INT_MAX) return BCNN_ERR_UNSUPPORTED;
     const int64_t tensor_words = (int64_t)s.n * s.h * s.w * s.cw;
     if (x_branch_stride != 0 && x_branch_stride < tensor_words) return BCNN_ERR_INVALID_ARG;
     if (x_branch_stride * branches > INT_MAX) return BCNN_ERR_UNSUPPORTED;
-    if (static_cast<const void*>(x) == out) return BCNN_ERR_INVALID_ARG;
+    if (out && static_cast<const void*>(x) == out) return BCNN_ERR_INVALID_ARG;
     if (!bcnn::aligned(x, 4) || !bcnn::aligned(w, 4) || !bcnn::aligned(scale, 4) || !bcnn::aligned(out, 4) ||
         (pad_words && !bcnn::aligned(pad_words, 4)) || (bias && !bcnn::aligned(bias, 4)))
         return BCNN_ERR_ALIGNMENT;
@@ -232,7 +233,7 @@ static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const ui
     a.x = x; a.x_branch_stride = x_branch_stride; a.w = w;
     a.pad_words = pad_mode == BCNN_PAD_WORDS ? pad_words : nullptr;
     a.zero_pad = pad_mode == BCNN_PAD_ZERO;
-    a.scale = scale; a.bias = bias; a.out = out; a.fused = fused;
+    a.scale = scale; a.bias = bias; a.out = out; a.fused = fused; a.tail = tail;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const bool mfma_ok = bcnn::conv_branches_mfma_supported(s, a);
     hipError_t e;
@@ -259,8 +260,8 @@ int bcnn_conv2d_binary_branches(const bcnn_conv_desc* desc, int32_t branches, co
                                 const uint32_t* pad_words, int pad_mode, const float* scale,
                                 const float* bias, float* z, int variant, void* hip_stream)
 {
-    return branches_entry(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale,
-                          bias, z, false, variant, hip_stream);
+    return branches_entry(desc, branches, x_packed, x_branch_stride, nullptr, w_packed, pad_words, pad_mode,
+                          scale, bias, z, false, variant, hip_stream);
 }
 
 int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc* desc, int32_t branches,
@@ -269,8 +270,50 @@ int bcnn_conv2d_binary_branches_sign_pack(const bcnn_conv_desc* desc, int32_t br
                                           const float* bias, uint32_t* z_packed, int variant,
                                           void* hip_stream)
 {
-    return branches_entry(desc, branches, x_packed, x_branch_stride, w_packed, pad_words, pad_mode, scale,
-                          bias, z_packed, true, variant, hip_stream);
+    return branches_entry(desc, branches, x_packed, x_branch_stride, nullptr, w_packed, pad_words, pad_mode,
+                          scale, bias, z_packed, true, variant, hip_stream);
+}
+
+// Fills the kernels' view of a module epilogue from the public struct; `with_bn` says whether the
+// batch-norm scale and bias are part of this call.  Returns BCNN_OK or the error.
+static int make_module_ep(const bcnn_module_epilogue* ep, bool with_bn, const bcnn::ConvShape& s,
+                          const void* x_packed, void* r, uint32_t* x_next_packed, bcnn::ModuleEp* m)
+{
+    if (!ep || (with_bn && (!ep->bn_scale || !ep->bn_bias))) return BCNN_ERR_INVALID_ARG;
+    if (!with_bn && (ep->bn_scale || ep->bn_bias)) return BCNN_ERR_INVALID_ARG;
+    if (!r && !x_next_packed) return BCNN_ERR_INVALID_ARG;
+    if (ep->real_dtype != BCNN_F32 && ep->real_dtype != BCNN_F16) return BCNN_ERR_UNSUPPORTED;
+    const int id_channels = ep->identity_channels ? ep->identity_channels : s.c_out;
+    if (id_channels < 1 || id_channels > s.c_out) return BCNN_ERR_INVALID_ARG;
+    if (id_channels != s.c_out && ep->identity && ep->identity == r) return BCNN_ERR_INVALID_ARG;
+    const uintptr_t esz = ep->real_dtype == BCNN_F32 ? 4 : 2;
+    if (x_packed == static_cast<const void*>(x_next_packed) || x_packed == r) return BCNN_ERR_INVALID_ARG;
+    if ((ep->bn_scale && !bcnn::aligned(ep->bn_scale, 4)) || (ep->bn_bias && !bcnn::aligned(ep->bn_bias, 4)) ||
+        (ep->prelu_slope && !bcnn::aligned(ep->prelu_slope, 4)) ||
+        (ep->next_bias && !bcnn::aligned(ep->next_bias, 4)) || (ep->identity && !bcnn::aligned(ep->identity, esz)) ||
+        (r && !bcnn::aligned(r, esz)) || (x_next_packed && !bcnn::aligned(x_next_packed, 4)))
+        return BCNN_ERR_ALIGNMENT;
+    m->scale = ep->bn_scale; m->bias = ep->bn_bias; m->identity = ep->identity; m->slope = ep->prelu_slope;
+    m->id_channels = id_channels;
+    m->next_bias = ep->next_bias; m->r = r; m->x_next = x_next_packed; m->half = ep->real_dtype == BCNN_F16;
+    return BCNN_OK;
+}
+
+int bcnn_conv2d_binary_branches_module(const bcnn_conv_desc* desc, int32_t branches,
+                                       const uint32_t* x_packed, int64_t x_branch_stride,
+                                       const uint32_t* w_packed, const uint32_t* pad_words, int pad_mode,
+                                       const float* scale, const float* bias,
+                                       const bcnn_module_epilogue* ep, void* r, uint32_t* x_next_packed,
+                                       int variant, void* hip_stream)
+{
+    bcnn::ConvShape s;
+    const int rc = bcnn::make_shape(desc, &s);
+    if (rc != BCNN_OK) return rc;
+    bcnn::ModuleEp m;
+    const int rc2 = make_module_ep(ep, false, s, x_packed, r, x_next_packed, &m);
+    if (rc2 != BCNN_OK) return rc2;
+    return branches_entry(desc, branches, x_packed, x_branch_stride, &m, w_packed, pad_words, pad_mode, scale,
+                          bias, nullptr, false, variant, hip_stream);
 }
 
 int bcnn_conv2d_binary(const bcnn_conv_desc* desc, const uint32_t* x_packed,
@@ -300,25 +343,11 @@ int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_pack
     bcnn::ConvShape s;
     const int rc = bcnn::make_shape(desc, &s);
     if (rc != BCNN_OK) return rc;
-    if (!x_packed || !w_packed || !ep || !ep->bn_scale || !ep->bn_bias) return BCNN_ERR_INVALID_ARG;
-    if (!r && !x_next_packed) return BCNN_ERR_INVALID_ARG;
-    if (ep->real_dtype != BCNN_F32 && ep->real_dtype != BCNN_F16) return BCNN_ERR_UNSUPPORTED;
-    const int id_channels = ep->identity_channels ? ep->identity_channels : s.c_out;
-    if (id_channels < 1 || id_channels > s.c_out) return BCNN_ERR_INVALID_ARG;
-    if (id_channels != s.c_out && ep->identity && ep->identity == r) return BCNN_ERR_INVALID_ARG;
-    const uintptr_t esz = ep->real_dtype == BCNN_F32 ? 4 : 2;
-    if (static_cast<const void*>(x_packed) == static_cast<const void*>(x_next_packed) ||
-        static_cast<const void*>(x_packed) == r)
-        return BCNN_ERR_INVALID_ARG;
-    if (!bcnn::aligned(x_packed, 4) || !bcnn::aligned(w_packed, 4) || !bcnn::aligned(ep->bn_scale, 4) ||
-        !bcnn::aligned(ep->bn_bias, 4) || (ep->prelu_slope && !bcnn::aligned(ep->prelu_slope, 4)) ||
-        (ep->next_bias && !bcnn::aligned(ep->next_bias, 4)) || (ep->identity && !bcnn::aligned(ep->identity, esz)) ||
-        (r && !bcnn::aligned(r, esz)) || (x_next_packed && !bcnn::aligned(x_next_packed, 4)))
-        return BCNN_ERR_ALIGNMENT;
+    if (!x_packed || !w_packed) return BCNN_ERR_INVALID_ARG;
+    if (!bcnn::aligned(x_packed, 4) || !bcnn::aligned(w_packed, 4)) return BCNN_ERR_ALIGNMENT;
     bcnn::ModuleEp m;
-    m.scale = ep->bn_scale; m.bias = ep->bn_bias; m.identity = ep->identity; m.slope = ep->prelu_slope;
-    m.id_channels = id_channels;
-    m.next_bias = ep->next_bias; m.r = r; m.x_next = x_next_packed; m.half = ep->real_dtype == BCNN_F16;
+    const int rc2 = make_module_ep(ep, true, s, x_packed, r, x_next_packed, &m);
+    if (rc2 != BCNN_OK) return rc2;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     const bool mfma_ok = bcnn::conv_mfma_fp4_supported(s, x_packed, w_packed);

@@ -38,14 +38,18 @@ struct ModuleEp {
 // interface (one rounding per step: fma, add, multiply; then storage
 // rounding when the stream is half).  Returns the value as stored.
 template <bool HALF>
-__device__ __forceinline__ float module_value(float y, float g, float b, bool has_id, float idv,
-                                              bool has_slope, float a)
+__device__ __forceinline__ float module_tail(float t, bool has_id, float idv, bool has_slope, float a)
 {
-    float t = __builtin_fmaf(g, y, b);
     if (has_id) t = t + idv;
     if (has_slope) t = (t >= 0.0f) ? t : a * t;
     if constexpr (HALF) t = (float)(_Float16)t;
     return t;
+}
+template <bool HALF>
+__device__ __forceinline__ float module_value(float y, float g, float b, bool has_id, float idv,
+                                              bool has_slope, float a)
+{
+    return module_tail<HALF>(__builtin_fmaf(g, y, b), has_id, idv, has_slope, a);
 }
 
 // Launchers, one per kernel family.  Each returns the hipError_t of its launch.
@@ -81,6 +85,9 @@ struct BranchArgs {
     const float* bias;        // [c_out] or nullptr
     void* out;                // float [m][c_out], or packed bits [m][cwo] when fused
     bool fused;
+    // non-null: the branch sum continues into a module's tail (identity addition, PReLU, real stream
+    // out, next bias + sign + pack); scale and bias of *tail are unused, `out` and `fused` too
+    const ModuleEp* tail;
 };
 hipError_t launch_conv_branches(const ConvShape& s, const BranchArgs& a, hipStream_t stream);
 // the same on the matrix cores; `supported` says whether it covers the call

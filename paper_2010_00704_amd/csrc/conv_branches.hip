@@ -18,19 +18,84 @@
 // skipped altogether (a contribution of exactly 0).
 #include "bcnn_common.h"
 
+#include <type_traits>
+
 namespace bcnn {
 namespace {
 
 constexpr int TN = 32;
 enum { PAD_MINUS = 0, PAD_WORDS = 1, PAD_SKIP = 2 };
+enum { OUT_F32 = 0, OUT_BITS = 1, OUT_TAIL_F32 = 2, OUT_TAIL_F16 = 3 };   // what happens to the branch sum
 
-template <int TM, int VEC, int PADMODE, bool FUSED, bool FULL>
+// Tail of a module with parallel branches for one pixel of a lane (32 channels
+// from o0): identity addition, PReLU, real stream out, next bias + sign.  Used
+// with full tiles only (c_out >= 32); all loads come before any store because
+// the stream may be updated in place.
+template <bool HALF>
+__device__ __forceinline__ void tail_store(const ConvShape& s, const ModuleEp& ep, int m, int o0, int shift,
+                                           int ctile, const float (&z)[TN])
+{
+    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+    constexpr int PER = HALF ? 8 : 4;
+    typedef real_t realv __attribute__((ext_vector_type(PER)));
+    const int idc = ep.id_channels;
+    const int id0 = o0 % idc;
+    const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * idc;
+    real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + o0;
+    const bool vec = (s.c_out % PER == 0) && (idc % PER == 0) && (id0 + TN <= idc) &&
+                     ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & 15) == 0;
+    float idv[TN];
+#pragma unroll
+    for (int o = 0; o < TN; ++o) idv[o] = 0.0f;
+    if (ep.identity) {
+        if (vec) {
+#pragma unroll
+            for (int q = 0; q < TN / PER; ++q) {
+                const realv v = __builtin_nontemporal_load(reinterpret_cast<const realv*>(idrow + id0) + q);
+#pragma unroll
+                for (int k = 0; k < PER; ++k) idv[q * PER + k] = (float)v[k];
+            }
+        } else {
+#pragma unroll
+            for (int o = 0; o < TN; ++o) idv[o] = (float)idrow[(id0 + o) % idc];
+        }
+    }
+    float v[TN];
+    uint32_t word = 0;
+#pragma unroll
+    for (int o = 0; o < TN; ++o) {
+        v[o] = module_tail<HALF>(z[o], ep.identity != nullptr, idv[o], ep.slope != nullptr,
+                                 ep.slope ? (ep.slope + o0)[o] : 1.0f);
+        const float c = ep.next_bias ? (ep.next_bias + o0)[o] : 0.0f;
+        word |= (uint32_t)(v[o] + c >= 0.0f) << o;
+    }
+    if (ep.r) {
+        if (vec) {
+#pragma unroll
+            for (int q = 0; q < TN / PER; ++q) {
+                realv u;
+#pragma unroll
+                for (int k = 0; k < PER; ++k) u[k] = (real_t)v[q * PER + k];
+                if (q * PER >= shift) reinterpret_cast<realv*>(rp)[q] = u;
+            }
+        } else {
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                if (o >= shift) rp[o] = (real_t)v[o];
+        }
+    }
+    if (ep.x_next) ep.x_next[(size_t)m * s.cwo + ctile] = word >> shift;
+}
+
+template <int TM, int VEC, int PADMODE, int OUT, bool FULL>
 __global__ __launch_bounds__(256) void conv_branches_kernel(
     ConvShape s, int32_t taps, int32_t n_mtiles, int32_t n_ctiles,
     const uint32_t* __restrict__ x, int64_t x_branch_stride, const uint32_t* __restrict__ w,
     const uint32_t* __restrict__ pad_words, const float* __restrict__ scale,
-    const float* __restrict__ bias, void* __restrict__ out)
+    const float* __restrict__ bias, void* __restrict__ out, ModuleEp ep)
 {
+    constexpr bool FUSED = OUT == OUT_BITS;
+    static_assert(OUT < OUT_TAIL_F32 || FULL, "the module tail is built for full channel tiles");
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * 4 + wave;
@@ -167,7 +232,12 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
         }
     }
 
-    if constexpr (FUSED) {
+    if constexpr (OUT == OUT_TAIL_F32 || OUT == OUT_TAIL_F16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            if (live[i])
+                tail_store<OUT == OUT_TAIL_F16>(s, ep, mtile * (64 * TM) + i * 64 + lane, o0, shift, ctile, z[i]);
+    } else if constexpr (FUSED) {
         uint32_t* zp = static_cast<uint32_t*>(out);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -212,17 +282,22 @@ hipError_t launch_mode(const ConvShape& s, const BranchArgs& a, hipStream_t stre
     const int n_mtiles = (s.m + 64 * TM - 1) / (64 * TM);
     const int64_t waves = (int64_t)n_ctiles * n_mtiles;
     const unsigned blocks = (unsigned)((waves + 3) / 4);
+    const ModuleEp ep = a.tail ? *a.tail : ModuleEp{};
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), 0, stream, s, a.branches, n_mtiles, n_ctiles, a.x,
-                           a.x_branch_stride, a.w, a.pad_words, a.scale, a.bias, a.out);
+                           a.x_branch_stride, a.w, a.pad_words, a.scale, a.bias, a.out, ep);
     };
     const bool full = s.c_out >= TN;
-    if (a.fused) {
-        if (full) go(conv_branches_kernel<TM, VEC, PADMODE, true, true>);
-        else go(conv_branches_kernel<TM, VEC, PADMODE, true, false>);
+    if (a.tail) {
+        if (!full) return hipErrorInvalidValue;     // the caller routes c_out < 32 elsewhere
+        if (ep.half) go(conv_branches_kernel<TM, VEC, PADMODE, OUT_TAIL_F16, true>);
+        else go(conv_branches_kernel<TM, VEC, PADMODE, OUT_TAIL_F32, true>);
+    } else if (a.fused) {
+        if (full) go(conv_branches_kernel<TM, VEC, PADMODE, OUT_BITS, true>);
+        else go(conv_branches_kernel<TM, VEC, PADMODE, OUT_BITS, false>);
     } else {
-        if (full) go(conv_branches_kernel<TM, VEC, PADMODE, false, true>);
-        else go(conv_branches_kernel<TM, VEC, PADMODE, false, false>);
+        if (full) go(conv_branches_kernel<TM, VEC, PADMODE, OUT_F32, true>);
+        else go(conv_branches_kernel<TM, VEC, PADMODE, OUT_F32, false>);
     }
     return hipGetLastError();
 }

@@ -125,21 +125,23 @@ constexpr int PAD_LDS_WORDS = 9 * 64;   // pad words kept in LDS: taps * cw <= t
 constexpr int MAX_BRANCHES = 16;        // scales kept in LDS: taps <= this
 
 // PB = pixel blocks (of 32) per wave; the workgroup covers 2*32*PB pixels.
-// Branch outputs come in three flavours of what a tap outside the image stands
-// for: -1 everywhere (nothing to do), the branch's pad words, or nothing at all.
-enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3,
-       OUT_BRANCH_F32 = 4, OUT_BRANCH_BITS = 5,                 // + 2 * pad mode
-       OUT_BRANCH_F32_WORDS = 6, OUT_BRANCH_BITS_WORDS = 7, OUT_BRANCH_F32_SKIP = 8, OUT_BRANCH_BITS_SKIP = 9 };
+// Branch mode: OUT = OUT_BRANCH + 4 * pad mode + kind.  Pad mode: what a tap
+// outside the image stands for (0: -1 everywhere, nothing to do; 1: the
+// branch's pad words; 2: nothing at all).  Kind: what happens to the branch sum
+// (float out, sign bits, or the module tail with a float / half real stream).
+enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3, OUT_BRANCH = 4 };
+enum { KIND_F32 = 0, KIND_BITS = 1, KIND_TAIL_F32 = 2, KIND_TAIL_F16 = 3 };
 
 template <int PB, int OUT, bool EVEN>
-__global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH_F32) ? 2 : 1)) void conv_mfma_fp4_kernel(
+__global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void conv_mfma_fp4_kernel(
     MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
     const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep, BranchEp bp)
 {
     constexpr bool FUSED = OUT == OUT_BITS;
-    constexpr bool BRANCH = OUT >= OUT_BRANCH_F32;
-    constexpr bool BRANCH_BITS = BRANCH && (OUT & 1);
-    constexpr int PADMODE = BRANCH ? (OUT - OUT_BRANCH_F32) / 2 : 0;   // 0: -1, 1: pad words, 2: skip
+    constexpr bool BRANCH = OUT >= OUT_BRANCH;
+    constexpr int KIND = BRANCH ? (OUT - OUT_BRANCH) % 4 : -1;
+    constexpr bool BRANCH_BITS = KIND == KIND_BITS;
+    constexpr int PADMODE = BRANCH ? (OUT - OUT_BRANCH) / 4 : 0;       // 0: -1, 1: pad words, 2: skip
     static_assert(!BRANCH || EVEN, "branch mode needs whole chunks per tap");
     constexpr int WG_PX = 64 * PB;
     // One stage = the chunk's 8 K-words of every row of the tile, as 16-byte
@@ -668,8 +670,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH_F32) ? 2 : 1)) v
         // (the stages are free now); afterwards a lane holds 4 consecutive
         // channels of a pixel, 16 lanes one pixel's 64 channels, and a store
         // instruction writes 256 contiguous bytes per pixel, four pixels at a time.
-        constexpr bool MODULE = OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16;
-        constexpr bool HALF = OUT == OUT_MODULE_F16;
+        constexpr bool MODULE = OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16 || KIND >= KIND_TAIL_F32;
+        constexpr bool HALF = OUT == OUT_MODULE_F16 || KIND == KIND_TAIL_F16;
         int32_t* y = static_cast<int32_t*>(out);
         constexpr int ROW_WORDS = 64 + 4;                      // padded row: 64 channels
         static_assert(4 * 32 * ROW_WORDS * 4 <= 3 * STAGE_BYTES, "transpose tiles must fit the stages");
@@ -688,8 +690,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH_F32) ? 2 : 1)) v
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int ch = c0 + k < s.c_out ? c0 + k : s.c_out - 1;
-                pg[k] = ep.scale[ch];
-                pb_[k] = ep.bias[ch];
+                pg[k] = BRANCH ? 1.0f : ep.scale[ch];     // branch mode: the sum is already scaled
+                pb_[k] = BRANCH ? 0.0f : ep.bias[ch];
                 pa[k] = ep.slope ? ep.slope[ch] : 1.0f;
                 pc[k] = ep.next_bias ? ep.next_bias[ch] : 0.0f;
             }
@@ -777,8 +779,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH_F32) ? 2 : 1)) v
                     uint32_t nib = 0;
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
-                        v[k] = module_value<HALF>((float)qv[k], pg[k], pb_[k], ep.identity != nullptr,
-                                                  (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
+                        if constexpr (BRANCH)
+                            v[k] = module_tail<HALF>(__int_as_float(qv[k]), ep.identity != nullptr,
+                                                     (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
+                        else
+                            v[k] = module_value<HALF>((float)qv[k], pg[k], pb_[k], ep.identity != nullptr,
+                                                      (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
                         nib |= (uint32_t)(c0 + k < s.c_out && v[k] + pc[k] >= 0.0f) << k;
                     }
                     if (ep.r && row_ok) {
@@ -816,7 +822,7 @@ hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int
     constexpr int WG_PX = 64 * PB;
     a.n_ptiles = (a.s.m + WG_PX - 1) / WG_PX;
     const unsigned blocks = (unsigned)(a.n_ptiles * a.n_ctiles);
-    if constexpr (OUT >= OUT_BRANCH_F32) {
+    if constexpr (OUT >= OUT_BRANCH) {
         hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
     } else {
         if (a.units_per_tap % 2 == 0)
@@ -929,14 +935,16 @@ hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& b, hi
     bp.bias = b.bias;
     bp.pad_words = b.pad_words;
     bp.pad_mode = b.zero_pad ? 2 : (b.pad_words ? 1 : 0);
-    if (b.fused) {
-        if (bp.pad_mode == 2) return launch_pb<4, OUT_BRANCH_BITS_SKIP>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
-        if (bp.pad_mode == 1) return launch_pb<4, OUT_BRANCH_BITS_WORDS>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
-        return launch_pb<4, OUT_BRANCH_BITS>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
-    }
-    if (bp.pad_mode == 2) return launch_pb<4, OUT_BRANCH_F32_SKIP>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
-    if (bp.pad_mode == 1) return launch_pb<4, OUT_BRANCH_F32_WORDS>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
-    return launch_pb<4, OUT_BRANCH_F32>(a, b.x, b.w, nullptr, b.out, nullptr, stream, &bp);
+    const int kind = b.tail ? (b.tail->half ? KIND_TAIL_F16 : KIND_TAIL_F32) : (b.fused ? KIND_BITS : KIND_F32);
+#define BCNN_BRANCH_CASE(P, K)                                                                              \
+    if (bp.pad_mode == P && kind == K)                                                                      \
+        return launch_pb<4, OUT_BRANCH + 4 * P + K>(a, b.x, b.w, nullptr, b.out, b.tail, stream, &bp);
+    BCNN_BRANCH_CASE(0, KIND_F32) BCNN_BRANCH_CASE(0, KIND_BITS) BCNN_BRANCH_CASE(0, KIND_TAIL_F32)
+    BCNN_BRANCH_CASE(0, KIND_TAIL_F16) BCNN_BRANCH_CASE(1, KIND_F32) BCNN_BRANCH_CASE(1, KIND_BITS)
+    BCNN_BRANCH_CASE(1, KIND_TAIL_F32) BCNN_BRANCH_CASE(1, KIND_TAIL_F16) BCNN_BRANCH_CASE(2, KIND_F32)
+    BCNN_BRANCH_CASE(2, KIND_BITS) BCNN_BRANCH_CASE(2, KIND_TAIL_F32) BCNN_BRANCH_CASE(2, KIND_TAIL_F16)
+#undef BCNN_BRANCH_CASE
+    return hipErrorInvalidValue;
 }
 
 }  // namespace bcnn

@@ -337,3 +337,80 @@ def test_branches_full_size(dev, index, variant):
     assert np.array_equal(got, z32)
     bits = zp[picks].cpu().numpy().view(np.uint32)
     assert np.array_equal(bits, oracle_bits(z32))
+
+
+# ------------------------------------------------------------ branches inside a module
+TAIL_SHAPES = [
+    # n, c_in, h, w, c_out, k or P (negative: -P parallel 1x1 branches), stride, pad
+    (2, 256, 14, 14, 128, -2, 1, 0),     # the paper's P = 2 module, matrix-core kernel
+    (3, 512, 9, 9, 100, -2, 1, 0),
+    (2, 256, 12, 12, 96, 3, 1, 1),       # F x F construction inside a module
+    (2, 64, 14, 14, 64, -2, 1, 0),       # vector-ALU kernel
+    (3, 96, 7, 9, 70, 3, 2, 1),
+    (40, 64, 14, 14, 64, -3, 1, 0),
+]
+
+
+@pytest.mark.parametrize("shape", TAIL_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("mode", ["minus", "words", "zero"])
+def test_branches_module_matches_oracle(dev, shape, variant, half, mode):
+    """Parallel branches (or the nine shifted ones) followed by identity
+    addition, PReLU, real stream out and the next module's bias + sign."""
+    n, c, h, w, o, kp, stride, pad = shape
+    k, p = (1, -kp) if kp < 0 else (kp, kp * kp)
+    if k == 1 and mode != "minus":
+        pytest.skip("no padding with 1x1 branches")
+    seed = 9900 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23))) + half + 2 * MODES.index(mode)
+    xb = W.pm1(seed, (p, n, c, h, w), 0.45)
+    wt = W.pm1(seed + 1, (o, c, p) if k == 1 else (o, c, k, k))
+    padv = W.pm1(seed + 2, (p, c))
+    ho = (h + 2 * pad - k) // stride + 1
+    wo = (w + 2 * pad - k) // stride + 1
+    m = n * ho * wo
+    for grid in (False, True):
+        if grid:
+            g = W.uniform_f32(seed + 3, (p, o), -2.0, 2.0, steps=16)
+            hb = W.uniform_f32(seed + 4, (o,), -8.0, 8.0, steps=64)
+            ident = W.uniform_f32(seed + 5, (m, o), -16.0, 16.0, steps=128)
+            alpha = W.uniform_f32(seed + 6, (o,), 0.0, 1.0, steps=4)
+            cn = W.uniform_f32(seed + 7, (o,), -4.0, 4.0, steps=32)
+        else:
+            g = W.uniform_f32(seed + 3, (p, o), -1.5, 1.5)
+            hb = W.uniform_f32(seed + 4, (o,), -30.0, 30.0)
+            ident = W.uniform_f32(seed + 5, (m, o), -40.0, 40.0)
+            alpha = W.uniform_f32(seed + 6, (o,), 0.05, 0.5)
+            cn = W.uniform_f32(seed + 7, (o,), -10.0, 10.0)
+        if half:
+            ident = ident.astype(np.float16)
+        if mode == "minus":
+            padv_o, words, code = -np.ones((p, c), dtype=np.int8), None, B.BCNN_PAD_WORDS
+        elif mode == "words":
+            padv_o, words, code = padv, pack_padv(padv), B.BCNN_PAD_WORDS
+        else:
+            padv_o, words, code = np.zeros((p, c), dtype=np.int8), None, B.BCNN_PAD_ZERO
+        z64, z32 = oracle.branches_pm1(xb, padv_o, wt, g, hb, stride, pad)
+        _, r32 = oracle.module_tail(z64, z32, ident.astype(np.float32).reshape(z32.shape), alpha)
+        stored = r32.astype(np.float16) if half else r32
+        sgn = oracle.sign_bias_f32(stored.astype(np.float32).reshape(m, o, 1), cn)
+        want_bits = oracle.pack_channels(sgn.reshape(n, ho * wo, o).transpose(0, 2, 1))
+
+        desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
+        cw = (c + 31) // 32
+        xp = up(i32(np.stack([pack_nchw(xb[t]) for t in range(p)])), dev)
+        wp = up(i32(oracle.pack_channels(wt.reshape(o, c, -1))), dev)
+        esz = 2 if half else 4
+        rbuf = Guarded((m * o * esz + 3) // 4, dev)
+        rbuf.buf.view(torch.uint8)[4 * GUARD:4 * GUARD + m * o * esz] = \
+            torch.from_numpy(np.ascontiguousarray(ident).view(np.uint8).reshape(-1)).to(dev)
+        cwo = (o + 31) // 32
+        bits = Guarded(m * cwo, dev)
+        rc = B.bcnn_conv2d_binary_branches_module(
+            desc, p, xp, n * h * w * cw, wp, up(i32(words), dev) if words is not None else None, code, up(g, dev),
+            up(hb, dev), rbuf.ptr, up(alpha, dev), up(cn, dev), B.BCNN_F16 if half else B.BCNN_F32, rbuf.ptr,
+            bits.ptr, variant)
+        run_variant(rc, "branches_module")
+        got_r = rbuf.get(np.uint8)[:m * o * esz].view(np.float16 if half else np.float32).reshape(m, o)
+        assert np.array_equal(got_r, stored.reshape(m, o))
+        assert np.array_equal(bits.get(np.uint32).reshape(n, ho * wo, cwo), want_bits)
