@@ -22,21 +22,46 @@ def sources():
     return sorted(glob.glob(os.path.join(_HERE, "csrc", "*.hip")))
 
 
-def build_library(verbose=False):
-    """Compile every .hip file under csrc/ into libbcnn.so.  Always compiles."""
-    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + ["-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_HERE, "csrc"),
-                             "-o", tmp] + sources()
+def _run(cmd):
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # hipcc's host pass does not know the packed-fp32 feature name and says so; harmless
     log = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if proc.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + log)
-    if verbose and log.strip():
-        print(log)
-    os.replace(tmp, LIB_PATH)
+    return proc.returncode, log
+
+
+def build_library(verbose=False):
+    """Compile every .hip file under csrc/ (one hipcc process per file, in
+    parallel) and link them into libbcnn.so.  Always compiles."""
+    import shutil
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
+    srcs = sources()
+    tmpdir = tempfile.mkdtemp(prefix="bcnn_build_")
+    try:
+        common = [f for f in FLAGS if f != "-shared"] + ["-I", os.path.join(_ROOT, "include"),
+                                                         "-I", os.path.join(_HERE, "csrc")]
+        objs = [os.path.join(tmpdir, os.path.basename(src) + ".o") for src in srcs]
+        jobs = min(len(srcs), max(1, min(8, os.cpu_count() or 1)))
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            results = list(pool.map(lambda so: _run([HIPCC] + common + ["-c", so[0], "-o", so[1]]), zip(srcs, objs)))
+        logs = []
+        for src, (rc, log) in zip(srcs, results):
+            if rc != 0:
+                raise RuntimeError("hipcc failed on %s:\n%s" % (os.path.basename(src), log))
+            if log.strip():
+                logs.append(log)
+        tmp = LIB_PATH + ".tmp.%d" % os.getpid()
+        rc, log = _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
+        if rc != 0:
+            if os.path.exists(tmp):
+                os.remove(tmp)
+            raise RuntimeError("link failed:\n" + log)
+        if verbose and (logs or log.strip()):
+            print("\n".join(logs + [log]))
+        os.replace(tmp, LIB_PATH)
+    finally:
+        shutil.rmtree(tmpdir, ignore_errors=True)
     return LIB_PATH
 
 

@@ -1,839 +1,7 @@
-// Binary convolution on the matrix cores.
-//
-// +-1 is exactly representable in the 4-bit float format E2M1 (+1.0 = 0b0010,
-// -1.0 = 0b1010; the other codes used below are 0.5, 2, 4 and 0), products
-// are small integers and fp32 sums of fewer than 2^22 of them are exact, so v_mfma_f32_32x32x64_f8f6f4 with both operands in fp4
-// computes the same integer as K - 2*popcount(x xor w) (BCNN paper, Section 1:
-// the operator is a matrix product; Section 4.2.1: operands are +-1) at 8x the
-// rate of the xor/popcount path on the vector ALUs.
-//
-// Operands stay 1 bit per element in HBM, L2 and LDS.  A lane expands one
-// packed 32-bit word (32 consecutive K positions of its row) into the four
-// VGPRs of an fp4 fragment right before the MFMA.  VGPR j of a fragment takes
-// the bits 4i+j of the word on both sides (the sum over K is order
-// independent, only the pairing matters).  Vector-ALU work per MFMA is the
-// limit here (about four vector ops hide under one 32-cycle MFMA, measured),
-// so the side with many fragments, the inputs, gets the cheapest expansion:
-//     j = 3 : (word & 0x88888888) | 0x22222222   sign bit over magnitude 1
-//     j < 3 :  word & (0x11111111 << j)          the bit alone: 0 or 0.5/1/2
-// 4 ops per fragment, no shifts.  The weights (few fragments) compensate:
-//     j = 3 : as above
-//     j < 3 : ((~word << (3-j)) & 0x88888888) | magnitude 4/2/1
-// 8 ops.  With s = +-1 the value of a bit: j = 3 gives (-s_w)(-s_x) = s_w*s_x;
-// j < 3 gives (alpha*s_w)(beta*bit_x) = s_w*(1 + s_x) = s_w + s_w*s_x.  So the
-// MFMA sum is the wanted dot product plus, per output channel, the sum of
-// that channel's weights over the positions 4i+0..2 = 2*pop - 24*words.  The
-// threads that stream the weights into LDS count pop on the way, and the
-// epilogue subtracts it.  All partial sums are integers (or multiples of 0.5
-// in the fused case) below 2^23: exact in fp32.  Positions that are 0 in both
-// operands (channel tail bits, zero-filled K padding) contribute +1 at j = 3
-// and 0 at j < 3; the host folds their count into the accumulator's initial
-// value.  Out-of-image taps are all-zero words on the input side only (= -1 in
-// every channel), exactly the padding convention.
-//
-// Tiling.  MFMA rows (M of the instruction) are output channels, columns are
-// output pixels.  A workgroup of 4 waves (2 x 2) owns 128 channels x 64*PB
-// pixels; a wave owns 2 x PB blocks of 32 x 32 (PB = 4 or 7; 7 divides the
-// pixel counts of 7/14/28/56-wide feature maps, see the launcher).
-// K is walked in chunks of 8 packed words (256 bits = 4 MFMA K-steps) over the
-// flattened (tap, channel-word) axis; each chunk of both operands is staged
-// once per workgroup in LDS (double buffered) with full-width global loads,
-// and every wave reads each fragment's words with one ds_read_b128.  Per
-// chunk a wave issues 8*PB MFMAs (32 cycles each) and 4*(2+PB)*7 expansion
-// ops; only about 3 vector ops per MFMA hide in its shadow (measured), which
-// is why the wide tile matters.
-//
-// Epilogue.  Weight rows are permuted inside each 32-channel block so that a
-// lane ends up holding 16 CONSECUTIVE channels of one pixel (lane half h,
-// register r <-> channel 16h + r).  int32 sums: subtract the per-channel
-// constant, convert and store 64 B runs.  Fused sign-pack: subtract constant
-// + thr[channel] - 0.5, so the value is sum - thr + 0.5, never zero, and its
-// sign bit is the complement of the output bit; 16 v_alignbit ops collect the
-// sign bits of a block, one cross-half exchange completes the 32-bit word.
-#include "bcnn_common.h"
-
-#include <type_traits>
-
-#include <utility>
+// Launchers of the matrix-core convolution (kernel: conv_mfma_fp4_kernel.h).
+#include "conv_mfma_fp4_kernel.h"
 
 namespace bcnn {
-namespace {
-
-// Compile-time loop: f(std::integral_constant<int, 0>) ... f(<N-1>), so that
-// every index inside is a constant expression.
-template <class F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr int WG_CH = 128;  // channels per workgroup (2 waves x 2 blocks of 32)
-constexpr int CB = 2;       // channel blocks per wave
-
-// MFMA row i of a 32-row block carries this channel of the block (see header).
-__device__ __forceinline__ int row_to_channel(int i)
-{
-    return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3);
-}
-
-// Constants that enter v_and_or_b32 live in VGPRs (the asm hides their values
-// from the optimiser): as literals they would force the two-instruction VOP2
-// form, because VOP3 encodings take no literal here.
-struct Fp4Masks { uint32_t m8, c2, c4, c6; };
-__device__ __forceinline__ Fp4Masks fp4_masks()
-{
-    Fp4Masks k;
-    asm volatile("v_mov_b32 %0, 0x88888888" : "=v"(k.m8));
-    asm volatile("v_mov_b32 %0, 0x22222222" : "=v"(k.c2));
-    asm volatile("v_mov_b32 %0, 0x44444444" : "=v"(k.c4));
-    asm volatile("v_mov_b32 %0, 0x66666666" : "=v"(k.c6));
-    return k;
-}
-
-struct MfmaArgs {
-    ConvShape s;
-    int32_t n_ptiles, n_ctiles;
-    int32_t units_per_tap;  // cw / 4
-    int32_t n_units;        // taps * cw / 4: 16-byte units along K that hold real data
-    int32_t n_chunks;       // ceil(n_units / 2)
-    int32_t z;              // 256 * n_chunks - K: positions that count +1 on their own
-    int32_t x_bytes, w_bytes;  // sizes of the packed tensors, for the buffer descriptors
-    int32_t row_jump;       // words added to the input offset when a filter row is complete
-    int32_t tap_step;       // words added when a tap (branch) is complete: 0 for the plain convolution
-    int32_t taps;           // filter taps = branches
-    int32_t chunks_per_tap; // branch mode: cw / 8
-};
-
-// Branch mode (see the section in front of the fold below): per-branch scales,
-// bias, what a tap outside the image stands for.
-struct BranchEp {
-    const float* scale;         // [taps][c_out]
-    const float* bias;          // [c_out] or nullptr
-    const uint32_t* pad_words;  // [taps][cw] (pad_mode 1)
-    int32_t pad_mode;           // 0: -1 everywhere, 1: pad_words, 2: the tap contributes nothing
-};
-constexpr int PAD_LDS_WORDS = 9 * 64;   // pad words kept in LDS: taps * cw <= this
-constexpr int MAX_BRANCHES = 16;        // scales kept in LDS: taps <= this
-
-// PB = pixel blocks (of 32) per wave; the workgroup covers 2*32*PB pixels.
-// Branch mode: OUT = OUT_BRANCH + 4 * pad mode + kind.  Pad mode: what a tap
-// outside the image stands for (0: -1 everywhere, nothing to do; 1: the
-// branch's pad words; 2: nothing at all).  Kind: what happens to the branch sum
-// (float out, sign bits, or the module tail with a float / half real stream).
-enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3, OUT_BRANCH = 4 };
-enum { KIND_F32 = 0, KIND_BITS = 1, KIND_TAIL_F32 = 2, KIND_TAIL_F16 = 3 };
-
-template <int PB, int OUT, bool EVEN>
-__global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void conv_mfma_fp4_kernel(
-    MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
-    const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep, BranchEp bp)
-{
-    constexpr bool FUSED = OUT == OUT_BITS;
-    constexpr bool BRANCH = OUT >= OUT_BRANCH;
-    constexpr int KIND = BRANCH ? (OUT - OUT_BRANCH) % 4 : -1;
-    constexpr bool BRANCH_BITS = KIND == KIND_BITS;
-    constexpr int PADMODE = BRANCH ? (OUT - OUT_BRANCH) / 4 : 0;       // 0: -1, 1: pad words, 2: skip
-    static_assert(!BRANCH || EVEN, "branch mode needs whole chunks per tap");
-    constexpr int WG_PX = 64 * PB;
-    // One stage = the chunk's 8 K-words of every row of the tile, as 16-byte
-    // units (4 words = one K-half of a row).  Unit order: [block of 32 rows]
-    // [K-half][row], blocks 0..3 weights, 4.. inputs; one wave-wide load fills
-    // one block (1 KB), and lane l of a reader wave finds the words of its MFMA
-    // row at unit 64*block + l.  Three stages rotate.
-    constexpr int NBLK = 4 + 2 * PB;             // blocks per stage
-    constexpr int STAGE_BYTES = NBLK * 1024;
-    constexpr int NL = (NBLK + 3) / 4;           // loads per wave and chunk
-    __shared__ uint4 stage[3 * NBLK * 64];
-    __shared__ int wpop_lds[WG_CH];
-    __shared__ int tapcnt_lds[BRANCH ? 2 : 1][2][WG_CH];        // per tap: [parity][pop | pad count][channel]
-    __shared__ uint32_t pad_lds[BRANCH ? PAD_LDS_WORDS + 8 : 1];
-    __shared__ float scale_lds[BRANCH ? MAX_BRANCHES : 1][WG_CH];   // scale[tap][channel of the tile]
-    const ConvShape& s = a.s;
-    const int t = threadIdx.x;
-    const int lane = t & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int wc = wave & 1, wp = wave >> 1;
-    const int hsel = lane >> 5;
-    const int j = lane & 31;
-
-    // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs; give
-    // each XCD a contiguous range of tiles (channel tile fastest) so that the
-    // workgroups sharing an input tile share an L2.
-    int tile = blockIdx.x;
-    const int n_tiles = a.n_ptiles * a.n_ctiles;
-    const int per_xcd = n_tiles >> 3;
-    if (tile < per_xcd * 8) tile = (tile & 7) * per_xcd + (tile >> 3);
-    const int ctile = tile % a.n_ctiles;
-    const int ptile = tile / a.n_ctiles;
-    const int o0 = ctile * WG_CH;
-    const int m0 = ptile * WG_PX;
-
-    // ---- loader state.  Global -> LDS directly (buffer_load ... lds: lane l
-    // of a wave writes 16 bytes at the LDS base of the instruction + 16*l, no
-    // registers in between).  Per chunk wave w loads block w (weights) and the
-    // input blocks w, w+4, ... ; lane l covers row l%32 of the block and the
-    // K-half l/32 (even or odd 16-byte unit of the chunk).  A block index past
-    // the end is clamped: the same data lands twice, which is harmless, and
-    // every wave issues the same number of loads.
-    int wrow_bytes;
-    {
-        int ch = o0 + 32 * wave + row_to_channel(j);
-        ch = ch < s.c_out ? ch : s.c_out - 1;
-        wrow_bytes = ch * a.n_units * 16;
-    }
-    // For input block i of this wave: word offset of the row's window top-left
-    // tap (may point outside the image; only used where the tap's validity
-    // bit is set) and one validity bit per tap.
-    int rbase[NL - 1];
-    uint32_t vmask[NL - 1];
-    int bblk[NL - 1];
-#pragma unroll
-    for (int i = 0; i < NL - 1; ++i) {
-        int b = wave + 4 * i;
-        b = b < 2 * PB ? b : 2 * PB - 1;
-        bblk[i] = b;
-        const int row = 32 * b + j;
-        int m = m0 + row;
-        m = m < s.m ? m : s.m - 1;
-        const int hw = s.ho * s.wo;
-        const int n = m / hw;
-        const int r = m - n * hw;
-        const int oh = r / s.wo;
-        const int ph = oh * s.stride - s.pad;
-        const int pw = (r - oh * s.wo) * s.stride - s.pad;
-        rbase[i] = ((n * s.h + ph) * s.w + pw) * s.cw;
-        uint32_t vm = s.ks == 1 ? 0xFFFFFFFFu : 0u;   // 1x1: no padding, every branch is inside
-        for (int u = 0; u < s.ks; ++u)
-            for (int v = 0; v < s.ks; ++v) {
-                const int ih = ph + u, iw = pw + v;
-                if (ih >= 0 && ih < s.h && iw >= 0 && iw < s.w) vm |= 1u << (u * s.ks + v);
-            }
-        vmask[i] = vm;
-    }
-
-    // ---- position of the chunk to fetch next along K.
-    // Lanes 0-31 fetch the chunk's even 16-byte unit, lanes 32-63 the odd one.
-    // All of it is wave-uniform scalar arithmetic without selects or division
-    // (compare results used as 0/1 factors), so it never branches and costs
-    // the vector ALU nothing.
-    //   EVEN (units per tap even: C_in a multiple of 256): both units of a
-    //     chunk lie in one tap, 16 bytes apart, so one (tap, offset) pair
-    //     serves the wave and the lanes' halves are folded into rbase/wrow.
-    //     Past the last chunk the position stops advancing: the extra fetches
-    //     of the pipeline's tail reload the last chunk's inputs (and zeros for
-    //     the weights) into stages whose contents are never multiplied.
-    //   otherwise: the two units are tracked separately and each lane selects
-    //     its own; units past the end (K padding) read as zero.
-    const int row_jump = a.row_jump;
-    struct KPos { int unit, tap, v, ut, off; };
-    KPos k0 = {0, 0, 0, 0, 0}, k1 = {0, 0, 0, 0, 0};
-    auto advance1 = [&](KPos& p, int per_tap, int step_words, int go) {
-        const int ut1 = p.ut + go;
-        const int tap_done = ut1 == per_tap ? 1 : 0;
-        p.ut = ut1 * (1 - tap_done);
-        p.tap += tap_done;
-        const int v1 = p.v + tap_done;
-        const int row_done = v1 == s.ks ? 1 : 0;
-        p.v = v1 * (1 - row_done);
-        p.off += go * step_words + row_done * row_jump + tap_done * a.tap_step;
-        p.unit += go;
-    };
-    if constexpr (!EVEN) advance1(k1, a.units_per_tap, 4, 1);
-    int fetched = 0;   // chunks fetched so far (EVEN only)
-    auto advance = [&]() {
-        if constexpr (EVEN) {
-            fetched += 1;
-            // k0.unit counts chunks here; stop on the last one
-            advance1(k0, a.units_per_tap >> 1, 8, k0.unit + 1 < a.n_chunks ? 1 : 0);
-        } else {
-            advance1(k0, a.units_per_tap, 4, 1); advance1(k0, a.units_per_tap, 4, 1);
-            advance1(k1, a.units_per_tap, 4, 1); advance1(k1, a.units_per_tap, 4, 1);
-        }
-    };
-    if constexpr (EVEN) {   // fold the lane's K-half into its base offsets
-        wrow_bytes += 16 * hsel;
-#pragma unroll
-        for (int i = 0; i < NL - 1; ++i) rbase[i] += 4 * hsel;
-    }
-
-    // ---- global -> LDS loads.
-    // A lane whose unit must read as zero (out-of-image tap, K padding past
-    // the last real unit) gets the offset -16, beyond any buffer: the hardware
-    // range check makes the load deliver 0, so the loader has no branches.
-    // The loads are written as inline assembly on purpose: the compiler's
-    // wait-count pass treats every later LDS read as possibly aliasing a
-    // pending global->LDS load and would force vmcnt(0) in front of it, which
-    // serialises the pipeline.  Written this way the compiler does not see
-    // them, and the explicit s_waitcnt vmcnt(N) before each barrier below is
-    // what orders them (N = loads that may still be in flight).  M0 carries
-    // the LDS destination; nothing else in this kernel uses M0.  The v_bfi
-    // between the M0 write and the load (offset = mask ? offset : -16) also
-    // fills the wait state that pair needs.
-    auto make_rsrc = [](const void* base, int bytes) -> v4i {
-        const uint64_t p = reinterpret_cast<uint64_t>(base);
-        // dword 1: address bits 47:32, stride 0; dword 3: 32-bit untyped data format
-        return v4i{(int)(uint32_t)p, (int)((uint32_t)(p >> 32) & 0xFFFFu), bytes, 0x00020000};
-    };
-    const v4i xres = make_rsrc(x, a.x_bytes);
-    const v4i wres = make_rsrc(w, a.w_bytes);
-    const uint32_t stage_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)stage;
-    auto dma16 = [&](const v4i& rsrc, uint32_t lds_byte, uint32_t offset, uint32_t mask) {
-        uint32_t tmp;
-        asm volatile("s_mov_b32 m0, %1\n\tv_bfi_b32 %0, %3, %2, -16\n\tbuffer_load_dwordx4 %0, %4, 0 offen lds"
-                     : "=&v"(tmp) : "s"(lds_byte), "v"(offset), "v"(mask), "s"(rsrc) : "memory");
-    };
-    // per chunk, before its fetch_piece calls
-    int f_real = -1, f_tap = 0, f_off = 0, f_woff = 0;
-    auto fetch_begin = [&]() {
-        if constexpr (EVEN) {
-            // weights of a chunk past the end must read as zero: the readers
-            // count the set bits of every weight word that passes through
-            f_real = -(fetched < a.n_chunks ? 1 : 0);
-            f_tap = k0.tap;
-            f_off = k0.off;
-            f_woff = wrow_bytes + k0.unit * 32;
-        } else {
-            const int unit = hsel ? k1.unit : k0.unit;
-            f_real = unit < a.n_units ? -1 : 0;
-            f_tap = hsel ? k1.tap : k0.tap;
-            f_off = hsel ? k1.off : k0.off;
-            f_woff = wrow_bytes + unit * 16;
-        }
-    };
-    auto fetch_piece = [&](int buf, int i) {  // i = 0: weight block; i = 1..NL-1: input blocks
-        if (i == 0) {
-            dma16(wres, stage_lds + (uint32_t)(buf * NBLK + wave) * 1024u, (uint32_t)f_woff, (uint32_t)f_real);
-        } else {
-            // validity bit of the tap, sign-extended to a mask
-            int m = __builtin_amdgcn_sbfe((int)vmask[i - 1], (uint32_t)f_tap & 31u, 1u);
-            if constexpr (!EVEN) m &= f_real;
-            dma16(xres, stage_lds + (uint32_t)(buf * NBLK + 4 + bblk[i - 1]) * 1024u,
-                  (uint32_t)(rbase[i - 1] + f_off) << 2, (uint32_t)m);
-        }
-    };
-
-    // ---- branch mode: F x F as F*F shifted binary 1x1 branches (or P parallel
-    // 1x1 branches), each with its own real scale per output channel (BCNN
-    // paper, Section 4.2.1, last paragraph; Figure 2, bottom).  A tap's chunks
-    // accumulate in `acc` as usual; when the tap is complete its exact integer
-    // sum y_t = acc - (2*pop_t(channel) - 192*chunks_per_tap) is folded into the
-    // float totals, tot = fma(scale[t][channel], y_t, tot), and acc restarts at
-    // zero.  pop_t are the weight-bit counts of that tap alone, exchanged
-    // through LDS at every fold.  A pixel whose tap lies outside the image has
-    // read all-zero words (-1 everywhere); where the tap should stand for the
-    // branch's pad words instead, its y_t is replaced by c_in - 2*popcount(pad
-    // words xor weights), which the weight readers count on the way like pop_t;
-    // where it should contribute nothing the fold is skipped for that pixel.
-    v16f tot[BRANCH ? CB : 1][BRANCH ? PB : 1];
-    uint32_t vmask_d[PB];
-    auto branch_channel = [&](int cb, int r) {
-        const int ch = o0 + 64 * wc + 32 * cb + 16 * hsel + r;
-        return ch < s.c_out ? ch : s.c_out - 1;
-    };
-    if constexpr (BRANCH) {
-        for (int i = t; i < a.taps * WG_CH; i += 256) {
-            const int tp = i / WG_CH, cl = i - tp * WG_CH;
-            const int ch = o0 + cl < s.c_out ? o0 + cl : s.c_out - 1;
-            scale_lds[tp][cl] = bp.scale[(size_t)tp * s.c_out + ch];
-        }
-        for (int i = t; i < PAD_LDS_WORDS + 8; i += 256)
-            pad_lds[i] = (PADMODE == 1 && i < a.taps * s.cw) ? bp.pad_words[i] : 0u;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float b = bp.bias ? bp.bias[branch_channel(cb, r)] : 0.0f;
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb) tot[cb][pb][r] = b;
-            }
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-            int m = m0 + 32 * (PB * wp + pb) + j;
-            m = m < s.m ? m : s.m - 1;
-            const int hw = s.ho * s.wo;
-            const int n = m / hw;
-            const int r = m - n * hw;
-            const int oh = r / s.wo;
-            const int ph = oh * s.stride - s.pad;
-            const int pw_ = (r - oh * s.wo) * s.stride - s.pad;
-            (void)n;
-            uint32_t vm = s.ks == 1 ? 0xFFFFFFFFu : 0u;
-            for (int u = 0; u < s.ks; ++u)
-                for (int v = 0; v < s.ks; ++v) {
-                    const int ih = ph + u, iw = pw_ + v;
-                    if (ih >= 0 && ih < s.h && iw >= 0 && iw < s.w) vm |= 1u << (u * s.ks + v);
-                }
-            vmask_d[pb] = vm;
-        }
-    }
-
-    // ---- accumulators: lane (pixel j = lane%32, half h = lane/32), register r
-    //      <-> channel 32*block + 16h + r.  They start at zero; every constant
-    //      and per-channel term is applied in the epilogue.
-    v16f acc[CB][PB];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
-
-    // ---- main loop, software pipelined by hand.
-    // A wave issues in order, so whatever follows a run of MFMAs in program
-    // order waits for all of them to issue; only work placed BETWEEN MFMAs
-    // overlaps with the matrix core.  Each chunk is therefore a fixed program
-    // of 4 K-steps x PB pixel blocks x 2 channel blocks MFMA slots, and after
-    // every MFMA comes a small piece of the other work (order pinned by
-    // scheduling barriers):
-    //   every slot : half of an input fragment two blocks ahead (fragments
-    //                live in a ring of four, so few registers hold them) and
-    //                a share of the next K-step's two weight fragments
-    //   K-step 0   : global -> LDS loads of chunk c+2; loader bookkeeping
-    //   K-step 1   : at its end, wait for this wave's loads of chunk c+1
-    //                (issued five K-steps earlier) and workgroup barrier
-    //   K-step 2   : LDS reads of chunk c+1's weight words
-    //   K-step 3   : LDS reads of chunk c+1's input words, each block's right
-    //                after that block's last use
-    // Stage c%3 holds chunk c.  All of it is read during chunk c-1, whose
-    // end every wave has reached behind chunk c's barrier; chunk c+3's loads
-    // are issued a whole chunk after that.
-    constexpr int NF = CB + PB;       // words per lane and K-step: weights first, then inputs
-    constexpr int NS = CB * PB;       // MFMA slots per K-step
-    static_assert(CB == 2, "slot program assumes two channel blocks");
-    static_assert(NL + 2 <= NS && NF <= NS && 2 * NL <= 15, "side work must fit the MFMA slots of a K-step");
-    const Fp4Masks masks = fp4_masks();
-    int fa[2][CB][4];                 // weight fragments, double buffered over K-steps
-    int fb[4][4];                     // input fragments, ring over (K-step, pixel block)
-    uint4 pw[NF];                     // this lane's four words (K-steps 0..3) of the chunk, per block
-    uint4 pwn[CB];                    // the next chunk's weight words (read before the current ones retire)
-    int wpop[CB] = {0, 0};            // set weight bits at positions 4i+0..2 of this lane's rows
-    const char* lds0 = reinterpret_cast<const char*>(stage) + lane * 16;
-    // One ds_read_b128 per block and chunk: lanes read consecutive 16-byte
-    // units, which is conflict free.  The next chunk's words replace a block's
-    // words during K-step 3, right after their last use.
-    auto read_unit = [&](uint4& dst, int buf, int f) {
-        const int blk = f < CB ? 2 * wc + f : 4 + PB * wp + (f - CB);
-        dst = *reinterpret_cast<const uint4*>(lds0 + buf * STAGE_BYTES + blk * 1024);
-    };
-    // Branch mode keeps the counts of the chunk read ahead apart (wnext, wpadn)
-    // until the chunk loop knows which tap they belong to; wpadn counts the
-    // positions where the weights differ from the tap's pad words (padq: this
-    // lane's four pad words of that chunk).
-    int wnext[CB] = {0, 0}, wpad[CB] = {0, 0}, wpadn[CB] = {0, 0};
-    uint4 padq = make_uint4(0u, 0u, 0u, 0u);
-    auto count_unit = [&](const uint4& q, int f) {   // well after the read, so nothing waits
-        const int c = __builtin_popcount(q.x & 0x77777777u) + __builtin_popcount(q.y & 0x77777777u) +
-                      __builtin_popcount(q.z & 0x77777777u) + __builtin_popcount(q.w & 0x77777777u);
-        if constexpr (BRANCH) {
-            wnext[f] = c;
-            if constexpr (PADMODE == 1)
-                wpadn[f] = __builtin_popcount(q.x ^ padq.x) + __builtin_popcount(q.y ^ padq.y) +
-                           __builtin_popcount(q.z ^ padq.z) + __builtin_popcount(q.w ^ padq.w);
-        } else {
-            wpop[f] += c;
-        }
-    };
-    auto word_of = [&](int f, int ks) -> uint32_t {   // ks = 0..3 within the chunk
-        return ks == 0 ? pw[f].x : ks == 1 ? pw[f].y : ks == 2 ? pw[f].z : pw[f].w;
-    };
-    // One VGPR (8 nibbles) of a fragment; VGPR jj takes the bits 4i+jj of the
-    // packed word on both sides (see the header for the values).
-    auto expand_w = [&](uint32_t word, int jj) -> int {
-        if (jj == 3) return (int)((word & masks.m8) | masks.c2);
-        return (int)(((~word << (3 - jj)) & masks.m8) | (jj == 0 ? masks.c6 : jj == 1 ? masks.c4 : masks.c2));
-    };
-    auto expand_x = [&](uint32_t word, int jj) -> int {
-        if (jj == 3) return (int)((word & masks.m8) | masks.c2);
-        return (int)(word & (0x11111111u << jj));
-    };
-    auto mfma_one = [&](int ks, int cb, int pb) {
-        const int (&A)[4] = fa[ks & 1][cb];
-        const int (&Bf)[4] = fb[(ks * PB + pb) & 3];
-        const v8i va = {A[0], A[1], A[2], A[3], 0, 0, 0, 0};
-        const v8i vb = {Bf[0], Bf[1], Bf[2], Bf[3], 0, 0, 0, 0};
-        acc[cb][pb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-            va, vb, acc[cb][pb], 4 /*A: fp4*/, 4 /*B: fp4*/, 0, 0, 0, 0);
-    };
-    // One chunk.  On entry p0 holds its first word pair, fa[0] its K-step 0
-    // weight fragments and fb[0], fb[1] its first two input fragments; on exit
-    // the same holds for the next chunk.  b1/b2 = stages of chunk c+1, c+2.
-    auto chunk_body = [&](int b1, int b2) {
-        static_for<4 * NS>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            constexpr int ks = i / NS, sl = i % NS;   // K-step, slot within it
-            constexpr int pb = sl / CB, cb = sl % CB;
-            mfma_one(ks, cb, pb);
-            // input fragment two blocks ahead: registers 2*cb, 2*cb+1.  Past the
-            // end of the chunk this reads p0 of the next chunk (loaded in K-step 2).
-            {
-                constexpr int q = ks * PB + pb + 2;           // linear (K-step, block) index
-                constexpr int qks = (q / PB) & 3, qpb = q % PB;
-                const uint32_t word = word_of(CB + qpb, qks);
-                fb[q & 3][2 * cb] = expand_x(word, 2 * cb);
-                fb[q & 3][2 * cb + 1] = expand_x(word, 2 * cb + 1);
-            }
-            // next K-step's weight fragments: 8 registers over the NS slots
-            static_for<(sl + 1) * 8 / NS - sl * 8 / NS>([&](auto jc) {
-                constexpr int idx = sl * 8 / NS + decltype(jc)::value;
-                constexpr int f = idx >> 2, jj = idx & 3;
-                if constexpr (ks < 3) fa[(ks + 1) & 1][f][jj] = expand_w(word_of(f, ks + 1), jj);
-                else fa[0][f][jj] = expand_w(pwn[f].x, jj);
-            });
-            // side work, spread over the slots of its K-step
-            if constexpr (ks == 1 && sl == NS - 1) {
-                // outstanding: this wave's loads of chunks c+1 and c+2, NL each, in order
-                asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NL) : "memory");   // chunk c+1 has landed
-                __syncthreads();
-            }
-            // chunk c+1's words: weights early in K-step 2 (into the spare
-            // set), input block pb in K-step 3 right after the block's last use
-            if constexpr (ks == 2 && sl < CB) read_unit(pwn[sl], b1, sl);
-            if constexpr (ks == 3 && cb == 1) read_unit(pw[CB + pb], b1, CB + pb);
-            if constexpr (ks == 0 && sl == 0) fetch_begin();
-            if constexpr (ks == 0 && sl < NL) fetch_piece(b2, sl);       // chunk c+2
-            if constexpr (ks == 0 && sl == NL) advance();                // on to the units of the next fetch
-            if constexpr (ks == 3 && sl >= NS - CB) count_unit(pwn[sl - (NS - CB)], sl - (NS - CB));
-            __builtin_amdgcn_sched_barrier(0);
-        });
-#pragma unroll
-        for (int f = 0; f < CB; ++f) pw[f] = pwn[f];
-    };
-
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {                        // chunks 0, 1 -> stages 0, 1
-        fetch_begin();
-#pragma unroll
-        for (int i = 0; i < NL; ++i) fetch_piece(c, i);
-        advance();
-    }
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NL) : "memory");   // chunk 0 has landed
-    __syncthreads();
-#pragma unroll
-    for (int f = 0; f < NF; ++f) read_unit(pw[f], 0, f);
-    if constexpr (PADMODE == 1) padq = *reinterpret_cast<const uint4*>(pad_lds + 4 * hsel);   // chunk 0
-#pragma unroll
-    for (int f = 0; f < CB; ++f) {
-        count_unit(pw[f], f);
-        if constexpr (BRANCH) { wpop[f] = wnext[f]; wpad[f] = wpadn[f]; }
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) fa[0][f][jj] = expand_w(pw[f].x, jj);
-    }
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) fb[q][jj] = expand_x(pw[CB + q].x, jj);
-
-    {
-        int b0 = 0, b1 = 1, b2 = 2;
-        int tap = 0, chunk_in_tap = 0, par = 0;
-        const int c_in = 256 * a.chunks_per_tap;
-        for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
-            if constexpr (PADMODE == 1)   // pad words of the chunk whose weights this body reads ahead
-                padq = *reinterpret_cast<const uint4*>(pad_lds + 8 * (chunk + 1) + 4 * hsel);
-            chunk_body(b1, b2);
-            const int tmp = b0; b0 = b1; b1 = b2; b2 = tmp;
-            if constexpr (BRANCH) {
-                chunk_in_tap += 1;
-                if (chunk_in_tap < a.chunks_per_tap) {
-#pragma unroll
-                    for (int f = 0; f < CB; ++f) { wpop[f] += wnext[f]; wpad[f] += wpadn[f]; }
-                    continue;
-                }
-                // ---- the tap is complete: fold it
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb) {
-                    // lanes l and l^32 read the two K-halves of the same weight row
-                    const int both = wpop[cb] + __shfl_xor(wpop[cb], 32, 64);
-                    const int bothp = wpad[cb] + __shfl_xor(wpad[cb], 32, 64);
-                    if (hsel == 0) {
-                        tapcnt_lds[par][0][64 * wc + 32 * cb + row_to_channel(j)] = both;
-                        if constexpr (PADMODE == 1) tapcnt_lds[par][1][64 * wc + 32 * cb + row_to_channel(j)] = bothp;
-                    }
-                    wpop[cb] = wnext[cb];
-                    wpad[cb] = wpadn[cb];
-                }
-                __syncthreads();
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int cl = 64 * wc + 32 * cb + 16 * hsel + r;
-                        const float corr = (float)(2 * tapcnt_lds[par][0][cl] - 192 * a.chunks_per_tap);
-                        float ypad = 0.0f;
-                        if constexpr (PADMODE == 1) ypad = (float)(c_in - 2 * tapcnt_lds[par][1][cl]);
-                        const float g = scale_lds[tap][cl];
-#pragma unroll
-                        for (int pb = 0; pb < PB; ++pb) {
-                            const bool inb = PADMODE == 0 || ((vmask_d[pb] >> tap) & 1u);
-                            float y = acc[cb][pb][r] - corr;
-                            if constexpr (PADMODE == 1) y = inb ? y : ypad;
-                            const float zn = __builtin_fmaf(g, y, tot[cb][pb][r]);
-                            if constexpr (PADMODE == 2) tot[cb][pb][r] = inb ? zn : tot[cb][pb][r];
-                            else tot[cb][pb][r] = zn;
-                            acc[cb][pb][r] = 0.0f;
-                        }
-                        if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // keep the live set small
-                    }
-                tap += 1;
-                chunk_in_tap = 0;
-                par ^= 1;
-            }
-        }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // drain the loads of the chunks past the end
-
-    // ---- epilogue
-    // The accumulator holds  sum + Z - 192*n_chunks + 2*pop(channel)  (Z:
-    // positions that are zero on both sides and count +1, see the launcher;
-    // pop: the channel's set weight bits at positions 4i+0..2, see the
-    // header).  The two lanes that read a weight row's K-halves add their
-    // counts and the workgroup exchanges them through LDS indexed by channel.  What
-    // has to be subtracted per channel (plus the threshold, minus 0.5 so that
-    // the result is never zero, in the fused case) is kept in sub[][].
-    float sub[CB][16];
-    if constexpr (!BRANCH) {
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            // lanes l and l^32 read the two K-halves of the same weight row
-            const int both = wpop[cb] + __shfl_xor(wpop[cb], 32, 64);
-            if (hsel == 0) wpop_lds[64 * wc + 32 * cb + row_to_channel(j)] = both;
-        }
-        __syncthreads();
-        const int base = a.z - 192 * a.n_chunks;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int cl = 64 * wc + 32 * cb + 16 * hsel + r;
-                int v = base + 2 * wpop_lds[cl];
-                if constexpr (FUSED) {
-                    int ch = o0 + cl;
-                    ch = ch < s.c_out ? ch : s.c_out - 1;
-                    int th = thr[ch];
-                    // |y| <= K, so thresholds beyond +-(K+1) decide nothing new
-                    th = th > s.k + 1 ? s.k + 1 : (th < -s.k - 1 ? -s.k - 1 : th);
-                    sub[cb][r] = (float)(v + th) - 0.5f;  // exact: multiples of 0.5 below 2^23
-                } else {
-                    sub[cb][r] = (float)v;
-                }
-            }
-    }
-    if constexpr (FUSED || BRANCH_BITS) {
-        // bit = (y >= thr)  <=>  acc - sub = y - thr + 0.5 > 0  <=>  sign bit clear
-        // (branch mode: bit = (z >= 0), a real comparison because z may be -0)
-        uint32_t* yp = static_cast<uint32_t*>(out);
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-            uint32_t part[CB];
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                if constexpr (BRANCH) {
-                    uint32_t bits = 0;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) bits |= (uint32_t)(tot[cb][pb][r] >= 0.0f) << r;
-                    part[cb] = bits;
-                } else {
-                    uint32_t sg = 0;
-#pragma unroll
-                    for (int r = 15; r >= 0; --r)  // r = 0 ends in bit 0
-                        sg = __builtin_amdgcn_alignbit(sg, __float_as_uint(acc[cb][pb][r] - sub[cb][r]), 31);
-                    part[cb] = ~sg & 0xFFFFu;     // bit r = (sum >= thr) for channel 16h + r
-                }
-            }
-            // lanes of half 0 finish block 0, lanes of half 1 finish block 1
-            const uint32_t give = hsel ? part[0] : part[1];
-            const uint32_t got = (uint32_t)__shfl_xor((int)give, 32, 64);
-            const uint32_t mine = hsel ? part[1] : part[0];
-            uint32_t word = hsel ? (got | (mine << 16)) : (mine | (got << 16));
-            const int m = m0 + 32 * (PB * wp + pb) + j;
-            const int wi = (o0 >> 5) + 2 * wc + hsel;  // packed word index along channels
-            if (m < s.m && wi < s.cwo) {
-                const int valid = s.c_out - 32 * wi;   // real channels in this word
-                if (valid < 32) word &= (1u << valid) - 1u;
-                yp[(size_t)m * s.cwo + wi] = word;
-            }
-        }
-    } else {
-        // int32 sums, or the module's real-valued epilogue.  In registers a lane
-        // holds 16 consecutive channels of one pixel, i.e. 64-byte pieces 1 KB
-        // apart: poor store granularity.  Each wave therefore transposes its 32
-        // pixels x 64 channels of a pixel block through its own 8.5 KB of LDS
-        // (the stages are free now); afterwards a lane holds 4 consecutive
-        // channels of a pixel, 16 lanes one pixel's 64 channels, and a store
-        // instruction writes 256 contiguous bytes per pixel, four pixels at a time.
-        constexpr bool MODULE = OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16 || KIND >= KIND_TAIL_F32;
-        constexpr bool HALF = OUT == OUT_MODULE_F16 || KIND == KIND_TAIL_F16;
-        int32_t* y = static_cast<int32_t*>(out);
-        constexpr int ROW_WORDS = 64 + 4;                      // padded row: 64 channels
-        static_assert(4 * 32 * ROW_WORDS * 4 <= 3 * STAGE_BYTES, "transpose tiles must fit the stages");
-        __syncthreads();                                       // every wave is done with the stages
-        int32_t* tile = reinterpret_cast<int32_t*>(stage) + wave * (32 * ROW_WORDS);
-        const int cgrp = lane & 15;                            // 4-channel group within the wave's 64
-        const int prow = lane >> 4;                            // pixel row within a group of four
-        const int c0 = o0 + 64 * wc + 4 * cgrp;                // this lane's first channel after the transpose
-        const bool vec_ok = (s.c_out % 4 == 0) &&
-                            ((reinterpret_cast<uintptr_t>(MODULE ? ep.r : out) & (HALF ? 7 : 15)) == 0) &&
-                            (!MODULE || ((reinterpret_cast<uintptr_t>(ep.identity) & (HALF ? 7 : 15)) == 0 &&
-                                         ep.id_channels % 4 == 0));
-        // per-channel parameters of the lane's four channels (clamped loads for a ragged c_out)
-        float pg[4], pb_[4], pa[4], pc[4];
-        if constexpr (MODULE) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int ch = c0 + k < s.c_out ? c0 + k : s.c_out - 1;
-                pg[k] = BRANCH ? 1.0f : ep.scale[ch];     // branch mode: the sum is already scaled
-                pb_[k] = BRANCH ? 0.0f : ep.bias[ch];
-                pa[k] = ep.slope ? ep.slope[ch] : 1.0f;
-                pc[k] = ep.next_bias ? ep.next_bias[ch] : 0.0f;
-            }
-        }
-        // The identity vectors of a pixel block are fetched one block ahead of
-        // their use and before any store of that block: the real stream may be
-        // updated in place, so the compiler must not be left to order these
-        // loads against the stores, and issued together they overlap.
-        using real_t = typename std::conditional<HALF, _Float16, float>::type;
-        typedef real_t real4 __attribute__((ext_vector_type(4)));
-        constexpr int AHEAD = HALF ? 2 : 1;                    // blocks in flight ahead of the one in work
-        real4 ids[AHEAD + 1][8];
-        auto load_ids = [&](int pb, real4 (&dst)[8]) {
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                const int m = m0 + 32 * (PB * wp + pb) + 4 * g + prow;
-                real4 t4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
-                if (ep.identity && m < s.m) {
-                    // the identity stream may have fewer channels than the output
-                    // (replication by bookkeeping): channel o reads o mod id_channels
-                    const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels;
-                    const int id0 = c0 % ep.id_channels;
-                    if (vec_ok && c0 + 4 <= s.c_out) {      // id_channels % 4 == 0: the four stay together
-                        t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(idrow + id0));
-                    } else {
-#pragma unroll
-                        for (int k = 0; k < 4; ++k)
-                            if (c0 + k < s.c_out) t4[k] = idrow[(id0 + k) % ep.id_channels];
-                    }
-                }
-                dst[g] = t4;
-            }
-        };
-        if constexpr (MODULE) {
-#pragma unroll
-            for (int k = 0; k < AHEAD && k < PB; ++k) load_ids(k, ids[k]);
-        }
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int r = 0; r < 16; r += 4) {
-                    int4 q;
-                    if constexpr (BRANCH) {           // float totals travel as their bit patterns
-                        q.x = __float_as_int(tot[cb][pb][r + 0]);
-                        q.y = __float_as_int(tot[cb][pb][r + 1]);
-                        q.z = __float_as_int(tot[cb][pb][r + 2]);
-                        q.w = __float_as_int(tot[cb][pb][r + 3]);
-                    } else {
-                        q.x = (int)(acc[cb][pb][r + 0] - sub[cb][r + 0]);
-                        q.y = (int)(acc[cb][pb][r + 1] - sub[cb][r + 1]);
-                        q.z = (int)(acc[cb][pb][r + 2] - sub[cb][r + 2]);
-                        q.w = (int)(acc[cb][pb][r + 3] - sub[cb][r + 3]);
-                    }
-                    *reinterpret_cast<int4*>(tile + j * ROW_WORDS + 32 * cb + 16 * hsel + r) = q;
-                }
-            if constexpr (MODULE) {
-                if (pb + AHEAD < PB) load_ids(pb + AHEAD, ids[(pb + AHEAD) % (AHEAD + 1)]);
-            }
-            // same wave wrote and reads: LDS operations of a wave complete in order
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                const int px = 4 * g + prow;
-                const int4 q = *reinterpret_cast<const int4*>(tile + px * ROW_WORDS + 4 * cgrp);
-                const int m = m0 + 32 * (PB * wp + pb) + px;
-                const bool row_ok = m < s.m;
-                if constexpr (!MODULE) {
-                    if (row_ok) {
-                        int32_t* dstp = y + (size_t)m * s.c_out + c0;
-                        if (vec_ok && c0 + 4 <= s.c_out) {
-                            *reinterpret_cast<int4*>(dstp) = q;
-                        } else {
-                            if (c0 + 0 < s.c_out) dstp[0] = q.x;
-                            if (c0 + 1 < s.c_out) dstp[1] = q.y;
-                            if (c0 + 2 < s.c_out) dstp[2] = q.z;
-                            if (c0 + 3 < s.c_out) dstp[3] = q.w;
-                        }
-                    }
-                } else {
-                    real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + c0;
-                    const bool whole = vec_ok && c0 + 4 <= s.c_out;
-                    const int qv[4] = {q.x, q.y, q.z, q.w};
-                    float v[4];
-                    uint32_t nib = 0;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        if constexpr (BRANCH)
-                            v[k] = module_tail<HALF>(__int_as_float(qv[k]), ep.identity != nullptr,
-                                                     (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
-                        else
-                            v[k] = module_value<HALF>((float)qv[k], pg[k], pb_[k], ep.identity != nullptr,
-                                                      (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
-                        nib |= (uint32_t)(c0 + k < s.c_out && v[k] + pc[k] >= 0.0f) << k;
-                    }
-                    if (ep.r && row_ok) {
-                        if (whole) {
-                            real4 t4;
-#pragma unroll
-                            for (int k = 0; k < 4; ++k) t4[k] = (real_t)v[k];
-                            *reinterpret_cast<real4*>(rp) = t4;
-                        } else {
-#pragma unroll
-                            for (int k = 0; k < 4; ++k)
-                                if (c0 + k < s.c_out) rp[k] = (real_t)v[k];
-                        }
-                    }
-                    // eight neighbouring lanes hold the 32 channels of one packed word
-                    uint32_t wd = nib << (4 * (cgrp & 7));
-                    wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
-                    wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
-                    wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x141, 0xF, 0xF, true);  // row_half_mirror
-                    const int wi = ((o0 + 64 * wc) >> 5) + (cgrp >> 3);
-                    if (ep.x_next && row_ok && (cgrp & 7) == 0 && wi < s.cwo)
-                        ep.x_next[(size_t)m * s.cwo + wi] = wd;
-                }
-            }
-        }
-    }
-}
-
-template <int PB, int OUT>
-hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int32_t* thr,
-                     void* out, const ModuleEp* ep, hipStream_t stream, const BranchEp* bp = nullptr)
-{
-    const ModuleEp e = ep ? *ep : ModuleEp{};
-    const BranchEp b = bp ? *bp : BranchEp{};
-    constexpr int WG_PX = 64 * PB;
-    a.n_ptiles = (a.s.m + WG_PX - 1) / WG_PX;
-    const unsigned blocks = (unsigned)(a.n_ptiles * a.n_ctiles);
-    if constexpr (OUT >= OUT_BRANCH) {
-        hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
-    } else {
-        if (a.units_per_tap % 2 == 0)
-            hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
-        else
-            hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, false>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
-    }
-    return hipGetLastError();
-}
-
-}  // namespace
 
 bool conv_mfma_fp4_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w)
 {
@@ -936,15 +104,9 @@ hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& b, hi
     bp.pad_words = b.pad_words;
     bp.pad_mode = b.zero_pad ? 2 : (b.pad_words ? 1 : 0);
     const int kind = b.tail ? (b.tail->half ? KIND_TAIL_F16 : KIND_TAIL_F32) : (b.fused ? KIND_BITS : KIND_F32);
-#define BCNN_BRANCH_CASE(P, K)                                                                              \
-    if (bp.pad_mode == P && kind == K)                                                                      \
-        return launch_pb<4, OUT_BRANCH + 4 * P + K>(a, b.x, b.w, nullptr, b.out, b.tail, stream, &bp);
-    BCNN_BRANCH_CASE(0, KIND_F32) BCNN_BRANCH_CASE(0, KIND_BITS) BCNN_BRANCH_CASE(0, KIND_TAIL_F32)
-    BCNN_BRANCH_CASE(0, KIND_TAIL_F16) BCNN_BRANCH_CASE(1, KIND_F32) BCNN_BRANCH_CASE(1, KIND_BITS)
-    BCNN_BRANCH_CASE(1, KIND_TAIL_F32) BCNN_BRANCH_CASE(1, KIND_TAIL_F16) BCNN_BRANCH_CASE(2, KIND_F32)
-    BCNN_BRANCH_CASE(2, KIND_BITS) BCNN_BRANCH_CASE(2, KIND_TAIL_F32) BCNN_BRANCH_CASE(2, KIND_TAIL_F16)
-#undef BCNN_BRANCH_CASE
-    return hipErrorInvalidValue;
+    if (bp.pad_mode == 2) return launch_branch_mfma_pad_skip(a, b, bp, kind, stream);
+    if (bp.pad_mode == 1) return launch_branch_mfma_pad_words(a, b, bp, kind, stream);
+    return launch_branch_mfma_pad_minus(a, b, bp, kind, stream);
 }
 
 }  // namespace bcnn

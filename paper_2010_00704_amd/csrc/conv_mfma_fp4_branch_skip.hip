@@ -1,0 +1,13 @@
+// Branch mode of the matrix-core convolution, pad mode 2 (no contribution): its own
+// translation unit so that the big kernel's instances compile in parallel.
+#include "conv_mfma_fp4_kernel.h"
+
+namespace bcnn {
+
+hipError_t launch_branch_mfma_pad_skip(const MfmaArgs& a, const BranchArgs& b, const BranchEp& bp, int kind,
+                                     hipStream_t stream)
+{
+    return launch_branch_mfma_kind<2>(a, b, bp, kind, stream);
+}
+
+}  // namespace bcnn
