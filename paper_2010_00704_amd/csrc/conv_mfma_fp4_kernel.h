@@ -706,6 +706,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         typedef real_t real4 __attribute__((ext_vector_type(4)));
         constexpr int AHEAD = HALF ? 2 : 1;                    // blocks in flight ahead of the one in work
         real4 ids[AHEAD + 1][8];
+        const int id0 = MODULE ? c0 % (ep.id_channels > 0 ? ep.id_channels : 1) : 0;   // channel of the identity stream
         auto load_ids = [&](int pb, real4 (&dst)[8]) {
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
@@ -715,13 +716,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     // the identity stream may have fewer channels than the output
                     // (replication by bookkeeping): channel o reads o mod id_channels
                     const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels;
-                    const int id0 = c0 % ep.id_channels;
                     if (vec_ok && c0 + 4 <= s.c_out) {      // id_channels % 4 == 0: the four stay together
                         t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(idrow + id0));
                     } else {
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            if (c0 + k < s.c_out) t4[k] = idrow[(id0 + k) % ep.id_channels];
+                            if (c0 + k < s.c_out) t4[k] = idrow[id0 + k < ep.id_channels ? id0 + k : id0 + k - ep.id_channels];
                     }
                 }
                 dst[g] = t4;
@@ -765,7 +765,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     if (row_ok) {
                         int32_t* dstp = y + (size_t)m * s.c_out + c0;
                         if (vec_ok && c0 + 4 <= s.c_out) {
-                            *reinterpret_cast<int4*>(dstp) = q;
+                            __builtin_nontemporal_store(v4i{q.x, q.y, q.z, q.w}, reinterpret_cast<v4i*>(dstp));
                         } else {
                             if (c0 + 0 < s.c_out) dstp[0] = q.x;
                             if (c0 + 1 < s.c_out) dstp[1] = q.y;
