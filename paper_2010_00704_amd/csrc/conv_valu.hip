@@ -262,6 +262,126 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
     }
 }
 
+// ---- tiny problems ---------------------------------------------------------
+// With a handful of waves in the whole launch nothing hides the latency of the
+// main kernel's chain of scalar weight loads (32 channels x taps, one after the
+// other).  Here a wave (one per block, 64 pixels x 32 channels as above) fetches
+// everything it needs up front with vector loads, so it pays one memory latency:
+// its pixels' input words (one register per word) and its 32 weight rows
+// (register r: word 2r of channel `lane` in lanes 0-31, word 2r+1 in lanes 32-63).
+// v_readlane then turns a weight word into the scalar operand of v_xor_b32.
+// Covers taps * cw <= 2 * SMALL_REGS words per weight row.
+constexpr int SMALL_REGS = 18;
+
+template <int OUT, bool FULL>
+__global__ __launch_bounds__(64) void conv_valu_small_kernel(
+    ConvShape s, int32_t n_ctiles, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
+    const int32_t* __restrict__ thr, void* __restrict__ out)
+{
+    const int lane = threadIdx.x;
+    const int ctile = blockIdx.x % n_ctiles;
+    const int mtile = blockIdx.x / n_ctiles;
+    Tile<FULL> t;
+    t.o_last = s.c_out - 1;
+    t.o0 = (FULL && ctile * TN + TN > s.c_out) ? s.c_out - TN : ctile * TN;
+    t.shift = ctile * TN - t.o0;
+
+    const int m = mtile * 64 + lane;
+    const bool live = m < s.m;
+    const int mc = live ? m : s.m - 1;
+    const int hw = s.ho * s.wo;
+    const int pn = mc / hw;
+    const int rr = mc - pn * hw;
+    const int oh = rr / s.wo;
+    const int ph = oh * s.stride - s.pad;
+    const int pw = (rr - oh * s.wo) * s.stride - s.pad;
+
+    const int row_words = s.ks * s.ks * s.cw;     // words per weight row = per pixel window
+    // weights: lane's channel (lanes 32-63 take the same channels again, odd words)
+    const uint32_t* wrow = w + (size_t)t.chan(lane & 31) * row_words + (lane >> 5);
+    uint32_t wr[SMALL_REGS];
+#pragma unroll
+    for (int r = 0; r < SMALL_REGS; ++r) {
+        const int word = 2 * r + (lane >> 5);
+        wr[r] = word < row_words ? wrow[2 * r] : 0u;
+    }
+    // inputs: word k of the lane's window = tap k / cw, channel word k % cw
+    uint32_t xr[2 * SMALL_REGS];
+    {
+        int j = 0, u = 0, v = 0;                 // channel word, filter row, filter column of word k
+#pragma unroll
+        for (int k = 0; k < 2 * SMALL_REGS; ++k) {
+            const int ih = ph + u, iw = pw + v;
+            const bool ok = k < row_words && ih >= 0 && ih < s.h && iw >= 0 && iw < s.w;
+            xr[k] = ok ? x[((size_t)(pn * s.h + ih) * s.w + iw) * s.cw + j] : 0u;
+            if (++j == s.cw) {
+                j = 0;
+                if (++v == s.ks) { v = 0; ++u; }
+            }
+        }
+    }
+
+    int32_t acc[TN];
+#pragma unroll
+    for (int o = 0; o < TN; ++o) acc[o] = 0;
+#pragma unroll
+    for (int r = 0; r < SMALL_REGS; ++r) {
+        if (2 * r < row_words) {
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                acc[o] += __builtin_popcount(xr[2 * r] ^ (uint32_t)__builtin_amdgcn_readlane((int)wr[r], o));
+        }
+        if (2 * r + 1 < row_words) {
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                acc[o] += __builtin_popcount(xr[2 * r + 1] ^ (uint32_t)__builtin_amdgcn_readlane((int)wr[r], 32 + o));
+        }
+    }
+
+    if constexpr (OUT == OUT_BITS) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int o = 0; o < TN; ++o) {
+            const bool on = (FULL || t.stores(o)) && (s.k - 2 * acc[o] >= thr[t.chan(o)]);
+            word |= (uint32_t)on << o;
+        }
+        if (live) static_cast<uint32_t*>(out)[(size_t)m * s.cwo + ctile] = word >> t.shift;
+    } else {
+        if (live) {
+            int32_t* row = static_cast<int32_t*>(out) + (size_t)m * s.c_out + t.o0;
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                if (t.stores(o)) row[o] = s.k - 2 * acc[o];
+        }
+    }
+}
+
+// Whether the tiny-problem kernel applies, and its launch.
+bool small_applies(const ConvShape& s)
+{
+    const int64_t waves = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 63) / 64);
+    return s.ks * s.ks * s.cw <= 2 * SMALL_REGS && waves <= 256;
+}
+
+hipError_t launch_small(const ConvShape& s, const uint32_t* x, const uint32_t* w, const int32_t* thr,
+                        void* out, hipStream_t stream)
+{
+    const int n_ctiles = (s.c_out + TN - 1) / TN;
+    const unsigned blocks = (unsigned)(n_ctiles * ((s.m + 63) / 64));
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(64), 0, stream, s, n_ctiles, x, w, thr, out);
+    };
+    const bool full = s.c_out >= TN;
+    if (thr) {
+        if (full) go(conv_valu_small_kernel<OUT_BITS, true>);
+        else go(conv_valu_small_kernel<OUT_BITS, false>);
+    } else {
+        if (full) go(conv_valu_small_kernel<OUT_I32, true>);
+        else go(conv_valu_small_kernel<OUT_I32, false>);
+    }
+    return hipGetLastError();
+}
+
 template <int TM, int VEC, int OUT>
 hipError_t launch_out(const ConvShape& s, const uint32_t* x, const uint32_t* w, const int32_t* thr,
                       void* out, const ModuleEp& ep, hipStream_t stream)
@@ -308,6 +428,7 @@ hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_
     // Two pixels per lane halve the scalar weight traffic per popcount; one
     // pixel per lane gives twice as many waves, which small problems need to
     // cover 1024 SIMDs.
+    if (!ep && small_applies(s)) return launch_small(s, x, w, thr, out, stream);
     const int64_t waves2 = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 127) / 128);
     if (waves2 >= 2048) return launch_tm<2>(s, x, w, thr, out, ep, stream);
     return launch_tm<1>(s, x, w, thr, out, ep, stream);
