@@ -1,0 +1,83 @@
+"""Helpers shared by the GPU parity tests: guarded device buffers, uploads and
+the oracle-side packing of logical +-1 tensors."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2010_00704_amd import binding as B
+
+GUARD = 64              # words on each side of every output
+SENTINEL = 0x5A5A5A5A
+
+
+class Guarded:
+    """A device buffer of `words` 32-bit words with sentinel bands around it
+    that must stay untouched."""
+
+    def __init__(self, words, dev):
+        self.words = int(words)
+        self.buf = torch.full((self.words + 2 * GUARD,), SENTINEL, dtype=torch.int32, device=dev)
+
+    @classmethod
+    def of_bytes(cls, nbytes, dev):
+        return cls((int(nbytes) + 3) // 4, dev)
+
+    @property
+    def ptr(self):
+        return self.buf.data_ptr() + 4 * GUARD
+
+    def put(self, a):
+        """Copies the bytes of a numpy array to the start of the buffer."""
+        flat = torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1))
+        self.buf.view(torch.uint8)[4 * GUARD:4 * GUARD + flat.numel()] = flat.to(self.buf.device)
+
+    def get(self, dtype=np.uint32, count=None):
+        """The buffer's contents as `dtype` (the first `count` elements if given)
+        after checking both guard bands."""
+        torch.cuda.synchronize()
+        host = self.buf.cpu().numpy()
+        assert np.all(host[:GUARD] == SENTINEL), "write before the output buffer"
+        assert np.all(host[GUARD + self.words:] == SENTINEL), "write past the output buffer"
+        data = host[GUARD:GUARD + self.words].view(dtype)
+        return data if count is None else data[:count]
+
+
+def gpu_device():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    B.lib()
+    return torch.device("cuda:0")
+
+
+def up(a, dev):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def i32(a):
+    """uint32 numpy -> int32 view (torch has no uint32 tensors)."""
+    return np.ascontiguousarray(a).view(np.int32)
+
+
+def run_variant(rc, what):
+    """An explicitly requested variant may not cover a shape: that is a skip,
+    anything else that is not OK is a failure."""
+    if rc == B.BCNN_ERR_UNSUPPORTED:
+        pytest.skip("variant does not cover this shape")
+    B.check(rc, what)
+
+
+def oracle_pack_nchw(x):
+    """[n, c, *spatial] +-1 -> packed [n, prod(spatial), cw] (the oracle's packer)."""
+    n, c = x.shape[:2]
+    return oracle.pack_channels(x.reshape(n, c, -1))
+
+
+def oracle_pack_vectors(v):
+    """[rows, c] +-1 -> packed [rows, cw] (pad words, one vector per row)."""
+    return oracle.pack_channels(v[:, :, None])[:, 0, :]
+
+
+def oracle_bits_of_sign(s):
+    """[n, ho, wo, o] +-1 -> packed [n, ho*wo, cwo]."""
+    n, ho, wo, o = s.shape
+    return oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))

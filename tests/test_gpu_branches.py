@@ -15,53 +15,23 @@ import torch
 import oracle
 from paper_2010_00704_amd import binding as B
 from paper_2010_00704_amd import workloads as W
+from gpu_helpers import (GUARD, Guarded, gpu_device, i32, oracle_bits_of_sign, oracle_pack_nchw,
+                         oracle_pack_vectors, run_variant, up)
 
 pytestmark = pytest.mark.gpu
-
-GUARD = 64
-SENTINEL = 0x5A5A5A5A
 
 
 @pytest.fixture(scope="module")
 def dev():
-    assert torch.cuda.is_available(), "these tests need the GPU"
-    B.lib()
-    return torch.device("cuda:0")
-
-
-class Guarded:
-    def __init__(self, words, dev):
-        self.words = int(words)
-        self.buf = torch.full((self.words + 2 * GUARD,), SENTINEL, dtype=torch.int32, device=dev)
-
-    @property
-    def ptr(self):
-        return self.buf.data_ptr() + 4 * GUARD
-
-    def get(self, dtype=np.uint32):
-        torch.cuda.synchronize()
-        host = self.buf.cpu().numpy()
-        assert np.all(host[:GUARD] == SENTINEL), "write before the output buffer"
-        assert np.all(host[GUARD + self.words:] == SENTINEL), "write past the output buffer"
-        return host[GUARD:GUARD + self.words].view(dtype)
-
-
-def up(a, dev):
-    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-
-
-def i32(a):
-    return np.ascontiguousarray(a).view(np.int32)
+    return gpu_device()
 
 
 def pack_nchw(x):
-    n, c = x.shape[:2]
-    return oracle.pack_channels(x.reshape(n, c, -1))
+    return oracle_pack_nchw(x)
 
 
 def pack_padv(padv):
-    """[P, C] of +-1 -> packed pad words [P, cw] (oracle's packer; inner = 1)."""
-    return oracle.pack_channels(padv[:, :, None])[:, 0, :]
+    return oracle_pack_vectors(padv)
 
 
 # ------------------------------------------------------------ bias, sign, pack
@@ -158,12 +128,6 @@ VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4]
 VARIANT_IDS = ["auto", "valu", "mfma_fp4"]
 
 
-def run_variant(rc, what):
-    if rc == B.BCNN_ERR_UNSUPPORTED:
-        pytest.skip("variant does not cover this shape")
-    B.check(rc, what)
-
-
 def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused, variant=B.BCNN_VARIANT_AUTO):
     bcount, n, c, h, w = xb.shape
     o, k = wt.shape[0], (wt.shape[2] if wt.ndim == 4 else 1)
@@ -189,9 +153,7 @@ def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused, varia
 
 
 def oracle_bits(z32):
-    n, ho, wo, o = z32.shape
-    s = oracle.sign_f32(z32)
-    return oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))
+    return oracle_bits_of_sign(oracle.sign_f32(z32))
 
 
 BRANCH_SHAPES = [

@@ -14,51 +14,17 @@ import torch
 import oracle
 from paper_2010_00704_amd import binding as B
 from paper_2010_00704_amd import workloads as W
+from gpu_helpers import Guarded, gpu_device, i32, up
 
 pytestmark = pytest.mark.gpu
 
-GUARD = 64
-SENTINEL = 0x5A5A5A5A
 VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4]
 VARIANT_IDS = ["auto", "valu", "mfma_fp4"]
 
 
 @pytest.fixture(scope="module")
 def dev():
-    assert torch.cuda.is_available(), "these tests need the GPU"
-    B.lib()
-    return torch.device("cuda:0")
-
-
-class Guarded:
-    """Device bytes between sentinel bands; `nbytes` is rounded up to words."""
-
-    def __init__(self, nbytes, dev):
-        self.words = (int(nbytes) + 3) // 4
-        self.buf = torch.full((self.words + 2 * GUARD,), SENTINEL, dtype=torch.int32, device=dev)
-
-    @property
-    def ptr(self):
-        return self.buf.data_ptr() + 4 * GUARD
-
-    def put(self, a):
-        flat = torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1))
-        self.buf.view(torch.uint8)[4 * GUARD:4 * GUARD + flat.numel()] = flat.to(self.buf.device)
-
-    def get(self, dtype, count):
-        torch.cuda.synchronize()
-        host = self.buf.cpu().numpy()
-        assert np.all(host[:GUARD] == SENTINEL), "write before the output buffer"
-        assert np.all(host[GUARD + self.words:] == SENTINEL), "write past the output buffer"
-        return host[GUARD:GUARD + self.words].view(dtype)[:count]
-
-
-def up(a, dev):
-    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-
-
-def i32(a):
-    return np.ascontiguousarray(a).view(np.int32)
+    return gpu_device()
 
 
 def oracle_module(x, wt, stride, pad, g, b, ident, alpha, c, half):
@@ -101,7 +67,7 @@ def gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant, wa
     xp = up(i32(oracle.pack_channels(x.reshape(n, cin, -1))), dev)
     wp = up(i32(oracle.pack_channels(wt.reshape(o, cin, -1))), dev)
     esz = 2 if half else 4
-    rbuf = Guarded(m * o * esz, dev)
+    rbuf = Guarded.of_bytes(m * o * esz, dev)
     idt = None
     if ident is not None:
         if in_place:
@@ -110,7 +76,7 @@ def gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant, wa
         else:
             idt = up(ident, dev)
     cwo = (o + 31) // 32
-    bits = Guarded(m * cwo * 4, dev)
+    bits = Guarded(m * cwo, dev)
     rc = B.bcnn_conv2d_binary_module(
         desc, xp, wp, up(g, dev), up(b, dev), idt, up(alpha, dev) if alpha is not None else None,
         up(c, dev) if c is not None else None, B.BCNN_F16 if half else B.BCNN_F32,
@@ -224,9 +190,9 @@ def test_module_replicated_identity(dev, shape, variant, half):
     desc = B.conv_desc(n, cin, h, w, o, k, stride, pad)
     xp = up(i32(oracle.pack_channels(x.reshape(n, cin, -1))), dev)
     wp = up(i32(oracle.pack_channels(wt.reshape(o, cin, -1))), dev)
-    rbuf = Guarded(m * o * (2 if half else 4), dev)
+    rbuf = Guarded.of_bytes(m * o * (2 if half else 4), dev)
     cwo = (o + 31) // 32
-    bits = Guarded(m * cwo * 4, dev)
+    bits = Guarded(m * cwo, dev)
     rc = B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), up(ident, dev), up(alpha, dev), up(c, dev),
                                      B.BCNN_F16 if half else B.BCNN_F32, rbuf.ptr, bits.ptr, variant,
                                      identity_channels=idc)

@@ -13,67 +13,26 @@ import torch
 import oracle
 from paper_2010_00704_amd import binding as B
 from paper_2010_00704_amd import workloads as W
+from gpu_helpers import Guarded, gpu_device, i32, oracle_pack_nchw, run_variant, up
 
 pytestmark = pytest.mark.gpu
 
-GUARD = 64              # words on each side of every output
-SENTINEL = 0x5A5A5A5A
 VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4_T4, B.BCNN_VARIANT_MFMA_FP4_T7,
             B.BCNN_VARIANT_MFMA_I8]
 VARIANT_IDS = ["auto", "valu", "mfma_fp4_t4", "mfma_fp4_t7", "mfma_i8"]
 
 
-def run_variant(rc, what):
-    """An explicitly requested variant may not cover a shape: that is a skip,
-    anything else that is not OK is a failure."""
-    if rc == B.BCNN_ERR_UNSUPPORTED:
-        pytest.skip("variant does not cover this shape")
-    B.check(rc, what)
-
-
 @pytest.fixture(scope="module")
 def dev():
-    assert torch.cuda.is_available(), "these tests need the GPU"
-    B.lib()
-    return torch.device("cuda:0")
-
-
-class Guarded:
-    """A device buffer of `words` 32-bit words with sentinel bands around it."""
-
-    def __init__(self, words, dev):
-        self.words = int(words)
-        self.buf = torch.full((self.words + 2 * GUARD,), SENTINEL, dtype=torch.int32, device=dev)
-
-    @property
-    def ptr(self):
-        return self.buf.data_ptr() + 4 * GUARD
-
-    def get(self, dtype=np.uint32):
-        torch.cuda.synchronize()
-        host = self.buf.cpu().numpy()
-        assert np.all(host[:GUARD] == SENTINEL), "write before the output buffer"
-        assert np.all(host[GUARD + self.words:] == SENTINEL), "write past the output buffer"
-        return host[GUARD:GUARD + self.words].view(dtype)
-
-
-def up(a, dev):
-    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    return gpu_device()
 
 
 def packed_view(a):
-    """uint32 numpy -> int32 torch-compatible view."""
-    return np.ascontiguousarray(a).view(np.int32)
-
-
-def oracle_pack_nchw(x):
-    n, c = x.shape[:2]
-    return oracle.pack_channels(x.reshape(n, c, -1))  # [n, h*w, cw]
+    return i32(a)
 
 
 def oracle_pack_weights(w):
-    o, c = w.shape[:2]
-    return oracle.pack_channels(w.reshape(o, c, -1))  # [o, kh*kw, cw]
+    return oracle_pack_nchw(w)   # [o, kh*kw, cw]
 
 
 def rand_pm1(rng, shape, p=0.5):
