@@ -16,76 +16,14 @@
 // mode, the all-zero word (-1 everywhere), the branch's pad words (the sign of
 // the branch's bias per channel: the paper zero-fills before the bias), or
 // skipped altogether (a contribution of exactly 0).
-#include "bcnn_common.h"
-
-#include <type_traits>
+#include "valu_epilogue.h"
 
 namespace bcnn {
 namespace {
 
-constexpr int TN = 32;
+using valu::TN;
 enum { PAD_MINUS = 0, PAD_WORDS = 1, PAD_SKIP = 2 };
 enum { OUT_F32 = 0, OUT_BITS = 1, OUT_TAIL_F32 = 2, OUT_TAIL_F16 = 3 };   // what happens to the branch sum
-
-// Tail of a module with parallel branches for one pixel of a lane (32 channels
-// from o0): identity addition, PReLU, real stream out, next bias + sign.  Used
-// with full tiles only (c_out >= 32); all loads come before any store because
-// the stream may be updated in place.
-template <bool HALF>
-__device__ __forceinline__ void tail_store(const ConvShape& s, const ModuleEp& ep, int m, int o0, int shift,
-                                           int ctile, const float (&z)[TN])
-{
-    using real_t = typename std::conditional<HALF, _Float16, float>::type;
-    constexpr int PER = HALF ? 8 : 4;
-    typedef real_t realv __attribute__((ext_vector_type(PER)));
-    const int idc = ep.id_channels;
-    const int id0 = o0 % idc;
-    const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * idc;
-    real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + o0;
-    const bool vec = (s.c_out % PER == 0) && (idc % PER == 0) && (id0 + TN <= idc) &&
-                     ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & 15) == 0;
-    float idv[TN];
-#pragma unroll
-    for (int o = 0; o < TN; ++o) idv[o] = 0.0f;
-    if (ep.identity) {
-        if (vec) {
-#pragma unroll
-            for (int q = 0; q < TN / PER; ++q) {
-                const realv v = __builtin_nontemporal_load(reinterpret_cast<const realv*>(idrow + id0) + q);
-#pragma unroll
-                for (int k = 0; k < PER; ++k) idv[q * PER + k] = (float)v[k];
-            }
-        } else {
-#pragma unroll
-            for (int o = 0; o < TN; ++o) idv[o] = (float)idrow[(id0 + o) % idc];
-        }
-    }
-    float v[TN];
-    uint32_t word = 0;
-#pragma unroll
-    for (int o = 0; o < TN; ++o) {
-        v[o] = module_tail<HALF>(z[o], ep.identity != nullptr, idv[o], ep.slope != nullptr,
-                                 ep.slope ? (ep.slope + o0)[o] : 1.0f);
-        const float c = ep.next_bias ? (ep.next_bias + o0)[o] : 0.0f;
-        word |= (uint32_t)(v[o] + c >= 0.0f) << o;
-    }
-    if (ep.r) {
-        if (vec) {
-#pragma unroll
-            for (int q = 0; q < TN / PER; ++q) {
-                realv u;
-#pragma unroll
-                for (int k = 0; k < PER; ++k) u[k] = (real_t)v[q * PER + k];
-                if (q * PER >= shift) reinterpret_cast<realv*>(rp)[q] = u;
-            }
-        } else {
-#pragma unroll
-            for (int o = 0; o < TN; ++o)
-                if (o >= shift) rp[o] = (real_t)v[o];
-        }
-    }
-    if (ep.x_next) ep.x_next[(size_t)m * s.cwo + ctile] = word >> shift;
-}
 
 template <int TM, int VEC, int PADMODE, int OUT, bool FULL>
 __global__ __launch_bounds__(256) void conv_branches_kernel(
@@ -236,7 +174,8 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             if (live[i])
-                tail_store<OUT == OUT_TAIL_F16>(s, ep, mtile * (64 * TM) + i * 64 + lane, o0, shift, ctile, z[i]);
+                valu::module_store<OUT == OUT_TAIL_F16, true, false>(s, ep, valu::Tile<true>::make(ctile, s.c_out),
+                                                                     mtile * (64 * TM) + i * 64 + lane, ctile, z[i]);
     } else if constexpr (FUSED) {
         uint32_t* zp = static_cast<uint32_t*>(out);
 #pragma unroll

@@ -20,14 +20,14 @@
 // index is ever clamped and per-channel parameters are plain contiguous scalar
 // loads.  With c_out < 32 rows beyond c_out are clamped to the last real one so
 // that every scalar load stays inside its tensor.
-#include "bcnn_common.h"
-
-#include <type_traits>
+#include "valu_epilogue.h"
 
 namespace bcnn {
 namespace {
 
-constexpr int TN = 32;
+using valu::TN;
+using valu::Tile;
+
 enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3 };
 
 template <int VEC>
@@ -44,91 +44,6 @@ __device__ __forceinline__ void load_words(const uint32_t* p, bool ok, uint32_t 
     }
 }
 
-// Where a tile's channels live: channel of accumulator o, and whether the tile
-// stores it.
-template <bool FULL>
-struct Tile {
-    int o0, shift, o_last;
-    __device__ __forceinline__ uint32_t chan(int o) const
-    {
-        if constexpr (FULL) return (uint32_t)(o0 + o);
-        else return (uint32_t)((o0 + o < o_last) ? (o0 + o) : o_last);
-    }
-    __device__ __forceinline__ bool stores(int o) const
-    {
-        if constexpr (FULL) return o >= shift;
-        else return o0 + o <= o_last;
-    }
-};
-
-// Module epilogue for one pixel of a lane.  The lane's 32 values are contiguous
-// in the real stream (128 or 64 bytes); when everything is 16-byte aligned
-// they move as 16-byte vectors, all loads before any store (the stream may be
-// updated in place).
-template <bool HALF, bool FULL>
-__device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp& ep, const Tile<FULL>& t,
-                                             int m, int ctile, const int32_t (&acc)[TN])
-{
-    using real_t = typename std::conditional<HALF, _Float16, float>::type;
-    constexpr int PER = HALF ? 8 : 4;                  // elements per 16-byte vector
-    typedef real_t realv __attribute__((ext_vector_type(PER)));
-    const size_t row = (size_t)m * s.c_out + t.o0;
-    // the identity stream may have fewer channels than the output (replication by
-    // bookkeeping): channel o reads o mod id_channels
-    const int idc = ep.id_channels;
-    const int id0 = t.o0 % idc;
-    const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * idc;
-    const real_t* idp = idrow + id0;
-    real_t* rp = static_cast<real_t*>(ep.r) + row;
-    const bool vec = FULL && (s.c_out % PER == 0) && (idc % PER == 0) && (id0 + TN <= idc) &&
-                     ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & 15) == 0;
-    float idv[TN];
-#pragma unroll
-    for (int o = 0; o < TN; ++o) idv[o] = 0.0f;
-    if (ep.identity) {
-        if (vec) {
-#pragma unroll
-            for (int q = 0; q < TN / PER; ++q) {
-                const realv v = __builtin_nontemporal_load(reinterpret_cast<const realv*>(idp) + q);
-#pragma unroll
-                for (int k = 0; k < PER; ++k) idv[q * PER + k] = (float)v[k];
-            }
-        } else {
-#pragma unroll
-            for (int o = 0; o < TN; ++o)
-                if (FULL || t.stores(o)) idv[o] = (float)idrow[(id0 + o) % idc];
-        }
-    }
-    const int ob = FULL ? t.o0 : 0;                    // FULL: plain offsets from the tile's first channel
-    float v[TN];
-    uint32_t word = 0;
-#pragma unroll
-    for (int o = 0; o < TN; ++o) {
-        const int oc = FULL ? o : (int)t.chan(o);
-        v[o] = module_value<HALF>((float)(s.k - 2 * acc[o]), (ep.scale + ob)[oc], (ep.bias + ob)[oc],
-                                  ep.identity != nullptr, idv[o], ep.slope != nullptr,
-                                  ep.slope ? (ep.slope + ob)[oc] : 1.0f);
-        const float c = ep.next_bias ? (ep.next_bias + ob)[oc] : 0.0f;
-        word |= (uint32_t)((FULL || t.stores(o)) && (v[o] + c >= 0.0f)) << o;
-    }
-    if (ep.r) {
-        if (vec) {
-#pragma unroll
-            for (int q = 0; q < TN / PER; ++q) {
-                realv u;
-#pragma unroll
-                for (int k = 0; k < PER; ++k) u[k] = (real_t)v[q * PER + k];
-                if (q * PER >= t.shift) reinterpret_cast<realv*>(rp)[q] = u;
-            }
-        } else {
-#pragma unroll
-            for (int o = 0; o < TN; ++o)
-                if (t.stores(o)) rp[o] = (real_t)v[o];
-        }
-    }
-    if (ep.x_next) ep.x_next[(size_t)m * s.cwo + ctile] = word >> t.shift;
-}
-
 template <int TM, int VEC, int OUT, bool FULL>
 __global__ __launch_bounds__(256) void conv_valu_kernel(
     ConvShape s, int32_t n_mtiles, int32_t n_ctiles,
@@ -142,10 +57,7 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
     const int ctile = tile % n_ctiles;
     const int mtile = tile / n_ctiles;
     if (mtile >= n_mtiles) return;
-    Tile<FULL> t;
-    t.o_last = s.c_out - 1;
-    t.o0 = (FULL && ctile * TN + TN > s.c_out) ? s.c_out - TN : ctile * TN;
-    t.shift = ctile * TN - t.o0;
+    const Tile<FULL> t = Tile<FULL>::make(ctile, s.c_out);
 
     int pn[TM], ph[TM], pw[TM];
     bool live[TM];
@@ -215,7 +127,8 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             if (live[i])
-                module_store<OUT == OUT_MODULE_F16, FULL>(s, ep, t, mtile * (64 * TM) + i * 64 + lane, ctile, acc[i]);
+                valu::module_store<OUT == OUT_MODULE_F16, FULL, true>(s, ep, t, mtile * (64 * TM) + i * 64 + lane,
+                                                                      ctile, acc[i]);
     } else if constexpr (OUT == OUT_BITS) {
         uint32_t* yp = static_cast<uint32_t*>(out);
         const int32_t* tp = thr + (FULL ? t.o0 : 0);
@@ -281,10 +194,7 @@ __global__ __launch_bounds__(64) void conv_valu_small_kernel(
     const int lane = threadIdx.x;
     const int ctile = blockIdx.x % n_ctiles;
     const int mtile = blockIdx.x / n_ctiles;
-    Tile<FULL> t;
-    t.o_last = s.c_out - 1;
-    t.o0 = (FULL && ctile * TN + TN > s.c_out) ? s.c_out - TN : ctile * TN;
-    t.shift = ctile * TN - t.o0;
+    const Tile<FULL> t = Tile<FULL>::make(ctile, s.c_out);
 
     const int m = mtile * 64 + lane;
     const bool live = m < s.m;
