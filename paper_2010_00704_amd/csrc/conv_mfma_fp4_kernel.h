@@ -156,6 +156,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     constexpr int NL = (NBLK + 3) / 4;           // loads per wave and chunk
     __shared__ uint4 stage[3 * NBLK * 64];
     __shared__ int wpop_lds[WG_CH];
+    __shared__ int thr_lds[FUSED ? WG_CH : 1];                  // thresholds of the tile, fetched at kernel start
     __shared__ int tapcnt_lds[BRANCH ? 2 : 1][2][WG_CH];        // per tap: [parity][pop | pad count][channel]
     __shared__ uint32_t pad_lds[BRANCH ? PAD_LDS_WORDS + 8 : 1];
     __shared__ float scale_lds[BRANCH ? MAX_BRANCHES : 1][WG_CH];   // scale[tap][channel of the tile]
@@ -178,6 +179,17 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     const int ptile = tile / a.n_ctiles;
     const int o0 = ctile * WG_CH;
     const int m0 = ptile * WG_PX;
+
+    // The tile's thresholds are fetched now and parked in LDS behind the first
+    // chunk's loads; the epilogue reads them there instead of waiting for global
+    // memory after the last MFMA.
+    int thr_early = 0;
+    if constexpr (FUSED) {
+        if (t < WG_CH) {
+            const int ch = o0 + t;
+            thr_early = thr[ch < s.c_out ? ch : s.c_out - 1];
+        }
+    }
 
     // ---- loader state.  Global -> LDS directly (buffer_load ... lds: lane l
     // of a wave writes 16 bytes at the LDS base of the instruction + 16*l, no
@@ -317,7 +329,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         } else {
             // validity bit of the tap, sign-extended to a mask
             int m = __builtin_amdgcn_sbfe((int)vmask[i - 1], (uint32_t)f_tap & 31u, 1u);
-            if constexpr (!EVEN) m &= f_real;
+            m &= f_real;     // chunks past the end fetch nothing (an out-of-range offset returns 0 at once)
             dma16(xres, stage_lds + (uint32_t)(buf * NBLK + 4 + bblk[i - 1]) * 1024u,
                   (uint32_t)(rbase[i - 1] + f_off) << 2, (uint32_t)m);
         }
@@ -517,6 +529,11 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         for (int i = 0; i < NL; ++i) fetch_piece(c, i);
         advance();
     }
+    if constexpr (FUSED) {
+        // |y| <= K, so thresholds beyond +-(K+1) decide nothing new and are clamped
+        if (t < WG_CH)
+            thr_lds[t] = thr_early > s.k + 1 ? s.k + 1 : (thr_early < -s.k - 1 ? -s.k - 1 : thr_early);
+    }
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(NL) : "memory");   // chunk 0 has landed
     __syncthreads();
 #pragma unroll
@@ -618,11 +635,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 const int cl = 64 * wc + 32 * cb + 16 * hsel + r;
                 int v = base + 2 * wpop_lds[cl];
                 if constexpr (FUSED) {
-                    int ch = o0 + cl;
-                    ch = ch < s.c_out ? ch : s.c_out - 1;
-                    int th = thr[ch];
-                    // |y| <= K, so thresholds beyond +-(K+1) decide nothing new
-                    th = th > s.k + 1 ? s.k + 1 : (th < -s.k - 1 ? -s.k - 1 : th);
+                    const int th = thr_lds[cl];
                     sub[cb][r] = (float)(v + th) - 0.5f;  // exact: multiples of 0.5 below 2^23
                 } else {
                     sub[cb][r] = (float)v;
