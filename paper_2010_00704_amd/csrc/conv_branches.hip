@@ -34,6 +34,9 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
 {
     constexpr bool FUSED = OUT == OUT_BITS;
     static_assert(OUT < OUT_TAIL_F32 || FULL, "the module tail is built for full channel tiles");
+    // full tiles with float or real outputs leave through a per-wave LDS tile (valu_epilogue.h)
+    constexpr bool WAVE_EPILOGUE = FULL && OUT != OUT_BITS;
+    __shared__ uint32_t ep_tile[WAVE_EPILOGUE ? 4 * 64 * valu::TROW : 1];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * 4 + wave;
@@ -170,12 +173,17 @@ __global__ __launch_bounds__(256) void conv_branches_kernel(
         }
     }
 
-    if constexpr (OUT == OUT_TAIL_F32 || OUT == OUT_TAIL_F16) {
+    if constexpr (WAVE_EPILOGUE) {
+        uint32_t* my_tile = ep_tile + wave * (64 * valu::TROW);
+        const valu::Tile<true> t = valu::Tile<true>::make(ctile, s.c_out);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            if (live[i])
-                valu::module_store<OUT == OUT_TAIL_F16, true, false>(s, ep, valu::Tile<true>::make(ctile, s.c_out),
-                                                                     mtile * (64 * TM) + i * 64 + lane, ctile, z[i]);
+        for (int i = 0; i < TM; ++i) {
+            const int m_first = mtile * (64 * TM) + i * 64;
+            if constexpr (OUT == OUT_F32)
+                valu::store_words_wave(s, t, m_first, lane, false, z[i], static_cast<uint32_t*>(out), my_tile);
+            else
+                valu::module_store_wave<OUT == OUT_TAIL_F16, false>(s, ep, t, m_first, ctile, lane, z[i], my_tile);
+        }
     } else if constexpr (FUSED) {
         uint32_t* zp = static_cast<uint32_t*>(out);
 #pragma unroll

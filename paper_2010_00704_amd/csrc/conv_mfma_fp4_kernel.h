@@ -734,7 +734,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     } else {
 #pragma unroll
                         for (int k = 0; k < 4; ++k)
-                            if (c0 + k < s.c_out) t4[k] = idrow[id0 + k < ep.id_channels ? id0 + k : id0 + k - ep.id_channels];
+                            if (c0 + k < s.c_out) t4[k] = idrow[(id0 + k) % ep.id_channels];
                     }
                 }
                 dst[g] = t4;

@@ -50,6 +50,9 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
     const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
     const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep)
 {
+    // full tiles with 32-bit or real outputs leave through a per-wave LDS tile (valu_epilogue.h)
+    constexpr bool WAVE_EPILOGUE = FULL && OUT != OUT_BITS;
+    __shared__ uint32_t ep_tile[WAVE_EPILOGUE ? 4 * 64 * valu::TROW : 1];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     const int tile = blockIdx.x * 4 + wave;
@@ -123,7 +126,17 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
 
     // Epilogue.  dot = K - 2*popcount; padding needs no correction because
     // padded taps were real all-zero words.
-    if constexpr (OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16) {
+    if constexpr (WAVE_EPILOGUE) {
+        uint32_t* my_tile = ep_tile + wave * (64 * valu::TROW);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m_first = mtile * (64 * TM) + i * 64;
+            if constexpr (OUT == OUT_I32)
+                valu::store_words_wave(s, t, m_first, lane, true, acc[i], static_cast<uint32_t*>(out), my_tile);
+            else
+                valu::module_store_wave<OUT == OUT_MODULE_F16, true>(s, ep, t, m_first, ctile, lane, acc[i], my_tile);
+        }
+    } else if constexpr (OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             if (live[i])

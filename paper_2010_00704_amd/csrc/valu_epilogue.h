@@ -112,5 +112,148 @@ __device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp&
     if (ep.x_next) ep.x_next[(size_t)m * s.cwo + ctile] = word >> t.shift;
 }
 
+// ---- the same for a whole wave on a full tile, transposed through LDS -------
+// Written per lane, a store instruction touches 64 different cache lines with
+// 16 bytes each.  Here the wave parks its 64 pixels x 32 values in LDS (row =
+// lane = pixel), then lane l takes the four channels 4*(l%8).. of pixel
+// 8k + l/8, k = 0..7: eight lanes cover the 128 (64) contiguous bytes of one
+// pixel, an instruction moves eight whole pixels, and the packed word of a pixel
+// is the OR of eight nibbles (three DPP steps).  Every lane of the wave must
+// call these, live pixel or not.
+constexpr int TROW = TN + 4;   // LDS row in words: rows stay 16-byte aligned, banks skewed by 4
+
+template <typename V>
+__device__ __forceinline__ void park_values(uint32_t* tile, int lane, int k_total, bool from_sums,
+                                            const V (&vals)[TN])
+{
+#pragma unroll
+    for (int q = 0; q < TN / 4; ++q) {
+        uint4 u;
+        if (from_sums) {
+            u.x = (uint32_t)(k_total - 2 * (int)vals[4 * q + 0]);
+            u.y = (uint32_t)(k_total - 2 * (int)vals[4 * q + 1]);
+            u.z = (uint32_t)(k_total - 2 * (int)vals[4 * q + 2]);
+            u.w = (uint32_t)(k_total - 2 * (int)vals[4 * q + 3]);
+        } else {
+            u.x = __float_as_uint((float)vals[4 * q + 0]);
+            u.y = __float_as_uint((float)vals[4 * q + 1]);
+            u.z = __float_as_uint((float)vals[4 * q + 2]);
+            u.w = __float_as_uint((float)vals[4 * q + 3]);
+        }
+        *reinterpret_cast<uint4*>(tile + lane * TROW + 4 * q) = u;
+    }
+}
+
+// Plain 32-bit outputs (int32 sums of a convolution, float sums of a branch
+// convolution): out is [m][c_out] of 4-byte elements.
+template <typename V>
+__device__ __forceinline__ void store_words_wave(const ConvShape& s, const Tile<true>& t, int m_first, int lane,
+                                                 bool from_sums, const V (&vals)[TN], uint32_t* out, uint32_t* tile)
+{
+    park_values(tile, lane, s.k, from_sums, vals);
+    const int cg = lane & 7;
+    const bool vec = (s.c_out % 4 == 0) && ((reinterpret_cast<uintptr_t>(out) & 15) == 0);
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int px = 8 * k + (lane >> 3);
+        const int m = m_first + px;
+        const uint4 q = *reinterpret_cast<const uint4*>(tile + px * TROW + 4 * cg);
+        if (m < s.m) {
+            uint32_t* dstp = out + (size_t)m * s.c_out + t.o0 + 4 * cg;
+            if (vec) {
+                if (4 * cg >= t.shift) __builtin_nontemporal_store(u4{q.x, q.y, q.z, q.w}, reinterpret_cast<u4*>(dstp));
+            } else {
+                if (4 * cg + 0 >= t.shift) dstp[0] = q.x;
+                if (4 * cg + 1 >= t.shift) dstp[1] = q.y;
+                if (4 * cg + 2 >= t.shift) dstp[2] = q.z;
+                if (4 * cg + 3 >= t.shift) dstp[3] = q.w;
+            }
+        }
+    }
+}
+
+template <bool HALF, bool FROM_SUMS, typename V>
+__device__ __forceinline__ void module_store_wave(const ConvShape& s, const ModuleEp& ep, const Tile<true>& t,
+                                                  int m_first, int ctile, int lane, const V (&vals)[TN],
+                                                  uint32_t* tile)
+{
+    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+    typedef real_t real4 __attribute__((ext_vector_type(4)));
+    park_values(tile, lane, s.k, FROM_SUMS, vals);
+    const int cg = lane & 7;
+    const int c0 = t.o0 + 4 * cg;                      // the lane's four channels (all real: full tile)
+    float pg[4], pb[4], pa[4], pc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        pg[j] = FROM_SUMS ? ep.scale[c0 + j] : 1.0f;
+        pb[j] = FROM_SUMS ? ep.bias[c0 + j] : 0.0f;
+        pa[j] = ep.slope ? ep.slope[c0 + j] : 1.0f;
+        pc[j] = ep.next_bias ? ep.next_bias[c0 + j] : 0.0f;
+    }
+    // the identity stream may have fewer channels than the output (replication by
+    // bookkeeping): channel o reads o mod id_channels
+    const int idc = ep.id_channels;
+    const int id0 = c0 % idc;
+    constexpr uintptr_t AL = HALF ? 7 : 15;
+    const bool vec = (s.c_out % 4 == 0) && (idc % 4 == 0) &&
+                     ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & AL) == 0;
+    // all identity vectors first: the stream may be updated in place
+    real4 idv[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int m = m_first + 8 * k + (lane >> 3);
+        real4 v4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
+        if (ep.identity && m < s.m) {
+            const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * idc;
+            if (vec) {
+                v4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(idrow + id0));
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v4[j] = idrow[(id0 + j) % idc];
+            }
+        }
+        idv[k] = v4;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int px = 8 * k + (lane >> 3);
+        const int m = m_first + px;
+        const uint4 q = *reinterpret_cast<const uint4*>(tile + px * TROW + 4 * cg);
+        const uint32_t qv[4] = {q.x, q.y, q.z, q.w};
+        float v[4];
+        uint32_t nib = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (FROM_SUMS)
+                v[j] = module_value<HALF>((float)(int)qv[j], pg[j], pb[j], ep.identity != nullptr, (float)idv[k][j],
+                                          ep.slope != nullptr, pa[j]);
+            else
+                v[j] = module_tail<HALF>(__uint_as_float(qv[j]), ep.identity != nullptr, (float)idv[k][j],
+                                         ep.slope != nullptr, pa[j]);
+            nib |= (uint32_t)(v[j] + pc[j] >= 0.0f) << j;
+        }
+        if (ep.r && m < s.m) {
+            real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + c0;
+            if (vec) {
+                real4 u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) u[j] = (real_t)v[j];
+                if (4 * cg >= t.shift) *reinterpret_cast<real4*>(rp) = u;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (4 * cg + j >= t.shift) rp[j] = (real_t)v[j];
+            }
+        }
+        // the eight lanes of a pixel hold the 32 channels of its packed word
+        uint32_t wd = nib << (4 * cg);
+        wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+        wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+        wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x141, 0xF, 0xF, true);  // row_half_mirror
+        if (ep.x_next && cg == 0 && m < s.m) ep.x_next[(size_t)m * s.cwo + ctile] = wd >> t.shift;
+    }
+}
+
 }  // namespace valu
 }  // namespace bcnn
