@@ -1,0 +1,175 @@
+"""Seeded random shapes through every convolution entry point (plain, fused,
+module, branch, branch + module tail), each compared bit for bit with the CPU
+oracle.  The fixed shape lists of the other GPU tests aim at known tile edges;
+this one looks for the edges nobody thought of.  Shapes stay inside what the
+header documents as supported; a variant that does not cover a shape skips.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2010_00704_amd import binding as B
+from paper_2010_00704_amd import workloads as W
+from gpu_helpers import Guarded, gpu_device, i32, oracle_bits_of_sign, oracle_pack_nchw, oracle_pack_vectors, up
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return gpu_device()
+
+
+def draw_shape(rng, mfma_friendly):
+    k = int(rng.choice([1, 3]))
+    stride = int(rng.choice([1, 2]))
+    pad = int(rng.integers(0, 2)) if k == 3 else 0
+    if mfma_friendly:
+        c_in = int(rng.choice([128, 256, 384, 512]))
+        c_out = int(rng.choice([64, 96, 100, 128, 130, 192, 257]))
+        n = int(rng.integers(1, 5))
+        h, w = int(rng.integers(12, 30)), int(rng.integers(12, 30))
+    else:
+        c_in = int(rng.integers(1, 200))
+        c_out = int(rng.integers(1, 150))
+        n = int(rng.integers(1, 4))
+        h, w = int(rng.integers(k, 16)), int(rng.integers(k, 16))
+    return n, c_in, h, w, c_out, k, stride, pad
+
+
+CASES = [(seed, seed % 2 == 0) for seed in range(40)]
+
+
+@pytest.mark.parametrize("seed,mfma_friendly", CASES)
+def test_random_plain_and_fused(dev, seed, mfma_friendly):
+    rng = np.random.default_rng(12000 + seed)
+    n, c, h, w, o, k, stride, pad = draw_shape(rng, mfma_friendly)
+    x = W.pm1(12100 + seed, (n, c, h, w), float(rng.choice([0.3, 0.5, 0.7])))
+    wt = W.pm1(12200 + seed, (o, c, k, k))
+    y = oracle.conv2d_pm1(x, wt, stride, pad)
+    kk = c * k * k
+    thr = W.thresholds(12300 + seed, o, max(1, int(2 * np.sqrt(kk))))
+    want_bits = oracle_bits_of_sign(oracle.threshold_sign(y, thr))
+    desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
+    xp = up(i32(oracle_pack_nchw(x)), dev)
+    wp = up(i32(oracle_pack_nchw(wt)), dev)
+    variants = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU]
+    if mfma_friendly:
+        variants += [B.BCNN_VARIANT_MFMA_FP4_T4, B.BCNN_VARIANT_MFMA_FP4_T7, B.BCNN_VARIANT_MFMA_I8]
+    ran = 0
+    for v in variants:
+        out = Guarded(y.size, dev)
+        rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, None, out.ptr, v)
+        if rc != B.BCNN_ERR_UNSUPPORTED:
+            B.check(rc, "conv")
+            assert np.array_equal(out.get(np.int32).reshape(y.shape), y), "variant %d sums" % v
+            ran += 1
+        bits = Guarded(want_bits.size, dev)
+        rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, up(thr, dev), bits.ptr, v)
+        if rc != B.BCNN_ERR_UNSUPPORTED:
+            B.check(rc, "fused")
+            assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits), "variant %d bits" % v
+            ran += 1
+    assert ran >= 4
+
+
+@pytest.mark.parametrize("seed,mfma_friendly", CASES[:24])
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_random_module(dev, seed, mfma_friendly, half):
+    rng = np.random.default_rng(13000 + seed)
+    n, c, h, w, o, k, stride, pad = draw_shape(rng, mfma_friendly)
+    x = W.pm1(13100 + seed, (n, c, h, w))
+    wt = W.pm1(13200 + seed, (o, c, k, k))
+    y = oracle.conv2d_pm1(x, wt, stride, pad)
+    _, ho, wo, _ = y.shape
+    m = n * ho * wo
+    g = W.uniform_f32(13300 + seed, (o,), -1.5, 1.5)
+    b = W.uniform_f32(13400 + seed, (o,), -20.0, 20.0)
+    idc = o if seed % 3 else max(1, o // 2)                      # sometimes a narrower, replicated identity
+    ident = W.uniform_f32(13500 + seed, (m, idc), -30.0, 30.0)
+    alpha = W.uniform_f32(13600 + seed, (o,), 0.0, 0.5)
+    cn = W.uniform_f32(13700 + seed, (o,), -5.0, 5.0)
+    if half:
+        ident = ident.astype(np.float16)
+    ident_full = oracle.replicate_channels(ident.astype(np.float32), -(-o // idc), axis=1)[:, :o]
+    _, r32 = oracle.module_epilogue(y, g, b, ident_full.reshape(y.shape), alpha)
+    stored = (r32.astype(np.float16) if half else r32).reshape(m, o)
+    sgn = oracle.sign_bias_f32(stored.astype(np.float32).reshape(m, o, 1), cn)
+    want_bits = oracle_bits_of_sign(sgn.reshape(n, ho, wo, o))
+    desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
+    xp = up(i32(oracle_pack_nchw(x)), dev)
+    wp = up(i32(oracle_pack_nchw(wt)), dev)
+    for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4):
+        rbuf = Guarded.of_bytes(m * o * (2 if half else 4), dev)
+        bits = Guarded(want_bits.size, dev)
+        rc = B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), up(ident, dev), up(alpha, dev),
+                                         up(cn, dev), B.BCNN_F16 if half else B.BCNN_F32, rbuf.ptr, bits.ptr, v,
+                                         identity_channels=idc)
+        if rc == B.BCNN_ERR_UNSUPPORTED:
+            continue
+        B.check(rc, "module")
+        assert np.array_equal(rbuf.get(np.float16 if half else np.float32, m * o).reshape(m, o), stored)
+        assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_branches(dev, seed):
+    rng = np.random.default_rng(14000 + seed)
+    mfma_friendly = seed % 2 == 0
+    k = 3 if seed % 3 else 1
+    p = 9 if k == 3 else int(rng.integers(1, 5))
+    stride = int(rng.choice([1, 2]))
+    pad = int(rng.integers(0, 2)) if k == 3 else 0
+    if mfma_friendly:
+        c, o = int(rng.choice([256, 512])), int(rng.choice([64, 100, 128, 160]))
+        n, h, w = int(rng.integers(2, 5)), int(rng.integers(10, 20)), int(rng.integers(10, 20))
+    else:
+        c, o = int(rng.integers(1, 150)), int(rng.integers(1, 120))
+        n, h, w = int(rng.integers(1, 3)), int(rng.integers(k, 12)), int(rng.integers(k, 12))
+    shared = bool(seed % 4 < 2)
+    xb = W.pm1(14100 + seed, (1 if shared else p, n, c, h, w), 0.45)
+    wt = W.pm1(14200 + seed, (o, c, p) if k == 1 else (o, c, k, k))
+    padv = W.pm1(14300 + seed, (p, c))
+    g = W.uniform_f32(14400 + seed, (p, o), -1.5, 1.5)
+    hb = W.uniform_f32(14500 + seed, (o,), -20.0, 20.0)
+    mode = ["minus", "words", "zero"][seed % 3] if k == 3 else "minus"
+    if mode == "minus":
+        padv_o, words, code = -np.ones((p, c), dtype=np.int8), None, B.BCNN_PAD_WORDS
+    elif mode == "words":
+        padv_o, words, code = padv, oracle_pack_vectors(padv), B.BCNN_PAD_WORDS
+    else:
+        padv_o, words, code = np.zeros((p, c), dtype=np.int8), None, B.BCNN_PAD_ZERO
+    z64, z32 = oracle.branches_pm1(xb, padv_o, wt, g, hb, stride, pad)
+    want_bits = oracle_bits_of_sign(oracle.sign_f32(z32))
+    _, ho, wo, _ = z32.shape
+    m = n * ho * wo
+    ident = W.uniform_f32(14600 + seed, (m, o), -30.0, 30.0)
+    alpha = W.uniform_f32(14700 + seed, (o,), 0.0, 0.5)
+    cn = W.uniform_f32(14800 + seed, (o,), -5.0, 5.0)
+    _, r32 = oracle.module_tail(z64, z32, ident.reshape(z32.shape), alpha)
+    tail_bits = oracle_bits_of_sign(oracle.sign_bias_f32(r32.reshape(m, o, 1), cn).reshape(n, ho, wo, o))
+    desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
+    cw = (c + 31) // 32
+    xp = up(i32(np.stack([oracle_pack_nchw(xb[t]) for t in range(xb.shape[0])])), dev)
+    wp = up(i32(oracle.pack_channels(wt.reshape(o, c, -1))), dev)
+    xs = 0 if shared else n * h * w * cw
+    pw = up(i32(words), dev) if words is not None else None
+    for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4):
+        out = Guarded(z32.size, dev)
+        rc = B.bcnn_conv2d_binary_branches(desc, p, xp, xs, wp, pw, code, up(g, dev), up(hb, dev), out.ptr, v)
+        if rc == B.BCNN_ERR_UNSUPPORTED:
+            continue
+        B.check(rc, "branches")
+        assert np.array_equal(out.get(np.float32).reshape(z32.shape), z32)
+        bits = Guarded(want_bits.size, dev)
+        B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, xs, wp, pw, code, up(g, dev), up(hb, dev),
+                                                        bits.ptr, v), "branches_sign_pack")
+        assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits)
+        if o >= 32:
+            rbuf = Guarded(m * o, dev)
+            tb = Guarded(tail_bits.size, dev)
+            B.check(B.bcnn_conv2d_binary_branches_module(desc, p, xp, xs, wp, pw, code, up(g, dev), up(hb, dev),
+                                                         up(ident, dev), up(alpha, dev), up(cn, dev), B.BCNN_F32,
+                                                         rbuf.ptr, tb.ptr, v), "branches_module")
+            assert np.array_equal(rbuf.get(np.float32).reshape(m, o), r32.reshape(m, o))
+            assert np.array_equal(tb.get(np.uint32).reshape(tail_bits.shape), tail_bits)
