@@ -10,7 +10,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "bcnn_oracle.c"), os.path.join(_HERE, "bcnn_branches_oracle.c")]
+_SRCS = [os.path.join(_HERE, name) for name in ("bcnn_oracle.c", "bcnn_branches_oracle.c", "bcnn_pool_oracle.c")]
 _LIB = os.path.join(_HERE, "libbcnn_oracle.so")
 _lib = None
 
@@ -62,6 +62,8 @@ def _load():
     lib.oracle_module_epilogue.restype = None
     lib.oracle_module_tail.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp]
     lib.oracle_module_tail.restype = None
+    lib.oracle_avgpool_nhwc.argtypes = [vp] + [i32] * 5 + [vp, vp]
+    lib.oracle_avgpool_nhwc.restype = i32
     _lib = lib
     return lib
 
@@ -300,3 +302,22 @@ def replicate_channels(x, r, axis=1):
     reps = [1] * x.ndim
     reps[axis] = int(r)
     return np.tile(x, reps)
+
+
+def avgpool_nhwc(a, s):
+    """S x S average pooling with stride S of a channel-last real map (paper,
+    Section 4.2.3): a [N, H, W, C] float32 -> (p64, p32), both
+    [N, H // s, W // s, C]: double sums, and the float chain in raster order."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.ndim != 4:
+        raise ValueError("a must be [N, H, W, C]")
+    n, h, w, c = a.shape
+    s = int(s)
+    if s < 1 or h // s < 1 or w // s < 1:
+        raise ValueError("empty pooled map")
+    p64 = np.empty((n, h // s, w // s, c), dtype=np.float64)
+    p32 = np.empty((n, h // s, w // s, c), dtype=np.float32)
+    rc = _load().oracle_avgpool_nhwc(_ptr(a), n, h, w, c, s, _ptr(p64), _ptr(p32))
+    if rc != 0:
+        raise ValueError("oracle_avgpool_nhwc failed: %d" % rc)
+    return p64, p32
