@@ -439,6 +439,28 @@ def aux_measurements(torch, B, dev, work):
             "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
             "tbops": round(2.0 * rows * ch * ch / (ms * 1e-3) / 1e12, 1)})
         del streams
+
+    # down-sampling identity path: 2x2/2 average pooling of the real stream + bias + sign + pack in one pass
+    # (4 elements read, 1 written per output element); a 205 MB fp32 map on rotating buffers and the level-1
+    # map of Table 1 at batch 32 in fp16
+    out["avgpool_bias_sign_pack"] = []
+    for name, tdt, code, esz, shape in (("f32", torch.float32, B.BCNN_F32, 4, (64, 56, 56, 256)),
+                                        ("f16", torch.float16, B.BCNN_F16, 2, (32, 112, 112, 64))):
+        nb, hh, ww, ch = shape
+        nbuf = 4
+        maps = [(torch.rand(shape, device=dev) * 80 - 40).to(tdt) for _ in range(nbuf)]
+        pooled = torch.empty((nb, hh // 2, ww // 2, ch), dtype=tdt, device=dev)
+        bits = torch.empty((nb, (hh // 2) * (ww // 2), (ch + 31) // 32), dtype=torch.int32, device=dev)
+        pbias = torch.from_numpy(W.uniform_f32(4600, (ch,), -10.0, 10.0)).to(dev)
+        for mp in maps:
+            B.check(B.bcnn_avgpool_bias_sign_pack(mp, code, nb, hh, ww, ch, 2, pbias, pooled, bits), "avgpool")
+        ms = graph_ms(lambda r: B.check(B.bcnn_avgpool_bias_sign_pack(
+            maps[r % nbuf], code, nb, hh, ww, ch, 2, pbias, pooled, bits), "avgpool"), reps)
+        nbytes = maps[0].numel() * esz + pooled.numel() * esz + bits.numel() * 4
+        out["avgpool_bias_sign_pack"].append({
+            "real": name, "shape": list(shape), "ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+        del maps
     return out
 
 

@@ -114,6 +114,32 @@ int bcnn_pack_bias_replicated(const void *src, int dtype, int64_t outer, int64_t
                               void *hip_stream);
 
 /*
+ * S x S average pooling with stride S of the channel-last real stream, fused
+ * with the bias + sign + pack of the binary 1x1 convolution module behind it
+ * (Section 4.2.3: identity path of a block that down-samples by S; Section
+ * 4.2.1, first paragraph: bias, then sign).  One pass writes both consumers of
+ * the pooled map:
+ *   pooled[n][oh][ow][c]   = (sum over the window, raster order, float32,
+ *                             one rounding per addition) / float(S*S), stored
+ *                             in the stream's type (half: round to nearest even)
+ *   x_packed[n][oh][ow][.] : bit c = (float(pooled as stored) + bias[c] >= 0)
+ * Windows are not padded; rows and columns that do not fill a window are
+ * dropped (h_out = h / S, w_out = w / S, rounded down).
+ *   src        : device, [n][h][w][channels] of real_dtype (BCNN_F32 or BCNN_F16)
+ *   bias       : device, float32 [channels], or NULL for no bias
+ *   pooled     : device, [n][h_out][w_out][channels] of real_dtype, or NULL
+ *   x_packed   : device, [n][h_out][w_out][ceil(channels/32)], tail bits 0, or NULL
+ * Errors: INVALID_ARG for NULL src, both outputs NULL, non-positive sizes, an
+ * empty pooled map or an output that is the input; UNSUPPORTED for another
+ * dtype, S > 8 or more than 2^31-1 output words * 8; ALIGNMENT for pointers
+ * not aligned to their element size.  Rows of 4-element-aligned tensors with
+ * channels a multiple of 4 take the fast path.
+ */
+int bcnn_avgpool_bias_sign_pack(const void *src, int real_dtype, int32_t n, int32_t h, int32_t w,
+                                int32_t channels, int32_t s, const float *bias, void *pooled,
+                                uint32_t *x_packed, void *hip_stream);
+
+/*
  * Binary convolution, integer sums (Section 1 operator, Section 4.2.1
  * operands):
  *   y[n][oh][ow][o] = sum_{u,v,c} X~[n][oh*s-p+u][ow*s-p+v][c] * W[o][u][v][c]

@@ -29,7 +29,7 @@ EXPORTS = (
     "bcnn_status_string", "bcnn_diag_copy_u32", "bcnn_diag_valu_peak",
     "bcnn_pack_bias", "bcnn_conv2d_binary_branches", "bcnn_conv2d_binary_branches_sign_pack",
     "bcnn_conv2d_binary_module", "bcnn_pack_bias_replicated", "bcnn_diag_mfma_fp4_peak",
-    "bcnn_conv2d_binary_branches_module",
+    "bcnn_conv2d_binary_branches_module", "bcnn_avgpool_bias_sign_pack",
 )
 
 
@@ -84,6 +84,7 @@ def lib():
         L.bcnn_conv2d_binary_branches_module.argtypes = [
             dp, i32, vp, i64, vp, vp, ctypes.c_int, vp, vp, ctypes.POINTER(bcnn_module_epilogue), vp, vp,
             ctypes.c_int, vp]
+        L.bcnn_avgpool_bias_sign_pack.argtypes = [vp, ctypes.c_int, i32, i32, i32, i32, i32, vp, vp, vp, vp]
         for name in EXPORTS:
             if name != "bcnn_status_string":
                 getattr(L, name).restype = ctypes.c_int
@@ -152,6 +153,11 @@ def bcnn_conv2d_binary_branches_sign_pack(desc, branches, x_packed, x_branch_str
 def bcnn_pack_bias_replicated(src, dtype, outer, src_channels, inner, replication, bias, dst, stream=None):
     return lib().bcnn_pack_bias_replicated(_ptr(src), dtype, outer, src_channels, inner, int(replication),
                                            _ptr(bias), _ptr(dst), _stream(stream))
+
+
+def bcnn_avgpool_bias_sign_pack(src, real_dtype, n, h, w, channels, s, bias, pooled, x_packed, stream=None):
+    return lib().bcnn_avgpool_bias_sign_pack(_ptr(src), int(real_dtype), n, h, w, channels, s, _ptr(bias),
+                                             _ptr(pooled), _ptr(x_packed), _stream(stream))
 
 
 def bcnn_conv2d_binary_module(desc, x_packed, w_packed, bn_scale, bn_bias, identity, prelu_slope, next_bias,

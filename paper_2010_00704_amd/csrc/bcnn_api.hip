@@ -207,6 +207,28 @@ int bcnn_pack_bias_replicated(const void* src, int dtype, int64_t outer, int64_t
                       hip_stream);
 }
 
+int bcnn_avgpool_bias_sign_pack(const void* src, int real_dtype, int32_t n, int32_t h, int32_t w,
+                                int32_t channels, int32_t s, const float* bias, void* pooled,
+                                uint32_t* x_packed, void* hip_stream)
+{
+    if (!src || (!pooled && !x_packed)) return BCNN_ERR_INVALID_ARG;
+    if (n < 1 || h < 1 || w < 1 || channels < 1 || s < 1) return BCNN_ERR_INVALID_ARG;
+    if (real_dtype != BCNN_F32 && real_dtype != BCNN_F16) return BCNN_ERR_UNSUPPORTED;
+    if (s > 8) return BCNN_ERR_UNSUPPORTED;
+    const int64_t ho = h / s, wo = w / s;
+    if (ho < 1 || wo < 1) return BCNN_ERR_INVALID_ARG;
+    const int64_t cw = (channels + 31) / 32;
+    if ((double)n * (double)ho * (double)wo * 8.0 * (double)cw > (double)INT_MAX) return BCNN_ERR_UNSUPPORTED;
+    const uintptr_t esz = real_dtype == BCNN_F32 ? 4 : 2;
+    if (!bcnn::aligned(src, esz) || !bcnn::aligned(pooled, esz) || !bcnn::aligned(x_packed, 4) ||
+        !bcnn::aligned(bias, 4))
+        return BCNN_ERR_ALIGNMENT;
+    if (src == pooled || src == static_cast<const void*>(x_packed)) return BCNN_ERR_INVALID_ARG;
+    const hipError_t e = bcnn::launch_avgpool_pack(src, real_dtype == BCNN_F16, n, h, w, channels, s, bias, pooled,
+                                                   x_packed, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
+}
+
 static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const uint32_t* x,
                           int64_t x_branch_stride, const bcnn::ModuleEp* tail,
                           const uint32_t* w, const uint32_t* pad_words, int pad_mode,

@@ -93,6 +93,10 @@ hipError_t launch_conv_branches(const ConvShape& s, const BranchArgs& a, hipStre
 // the same on the matrix cores; `supported` says whether it covers the call
 bool conv_branches_mfma_supported(const ConvShape& s, const BranchArgs& a);
 hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& a, hipStream_t stream);
+// S x S / S average pooling of a channel-last real map [n][h][w][c] (float, or half when `half`), fused
+// with bias + sign + pack of the pooled map; pooled or bits may be nullptr, bias too (zero)
+hipError_t launch_avgpool_pack(const void* src, bool half, int n, int h, int w, int c, int s, const float* bias,
+                               void* pooled, uint32_t* bits, hipStream_t stream);
 hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
 
 }  // namespace bcnn

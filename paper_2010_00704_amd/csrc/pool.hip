@@ -1,0 +1,210 @@
+// S x S / S average pooling of the channel-last real stream, fused with the
+// bias + sign + pack of the binary 1x1 convolution module behind it (BCNN
+// paper, Section 4.2.3: identity path of a down-sampling block; Section 4.2.1,
+// first paragraph: bias, then sign, in front of the binary convolution).
+//
+// One pass reads the S*S source vectors of an output element once and writes
+// both consumers of the pooled map: the real map itself (the identity input of
+// the module) and its packed sign bits (the module's binary operand).  HBM
+// bound: S*S*esz bytes read, esz + 1/8 bytes written per output element.
+//
+// The arithmetic is fixed so that the bits are reproducible: the window's
+// values are added in raster order in float32, one rounding per addition, the
+// sum is divided by float(S*S), the quotient is stored (rounded to nearest
+// even if the stream is half precision), and bit = (stored + bias >= 0) with
+// the sum rounded to float32.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "bcnn_common.h"
+
+namespace bcnn {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+struct PoolShape {
+    int n, h, w, c, s, ho, wo;
+    int cw;          // packed words per output pixel
+    int units;       // vector kernel: output pixels * 8 * cw lanes of four channels (the caller keeps it below 2^31)
+};
+
+__device__ __forceinline__ f4 load4(const float* p) { return *reinterpret_cast<const f4*>(p); }
+__device__ __forceinline__ f4 load4(const __half* p)
+{
+    const uint2 raw = *reinterpret_cast<const uint2*>(p);
+    const __half2 lo = *reinterpret_cast<const __half2*>(&raw.x);
+    const __half2 hi = *reinterpret_cast<const __half2*>(&raw.y);
+    return f4{__low2float(lo), __high2float(lo), __low2float(hi), __high2float(hi)};
+}
+// Stores the four values in the stream's type and returns them as stored.
+__device__ __forceinline__ f4 round_and_store4(float* p, f4 v, bool store)
+{
+    if (store) *reinterpret_cast<f4*>(p) = v;
+    return v;
+}
+__device__ __forceinline__ f4 round_and_store4(__half* p, f4 v, bool store)
+{
+    const __half2 lo = __halves2half2(__float2half_rn(v[0]), __float2half_rn(v[1]));
+    const __half2 hi = __halves2half2(__float2half_rn(v[2]), __float2half_rn(v[3]));
+    if (store) {
+        uint2 raw;
+        raw.x = *reinterpret_cast<const uint32_t*>(&lo);
+        raw.y = *reinterpret_cast<const uint32_t*>(&hi);
+        *reinterpret_cast<uint2*>(p) = raw;
+    }
+    return f4{__low2float(lo), __high2float(lo), __low2float(hi), __high2float(hi)};
+}
+__device__ __forceinline__ float as_float(float v) { return v; }
+__device__ __forceinline__ float as_float(__half v) { return __half2float(v); }
+__device__ __forceinline__ float round_and_store1(float* p, float v, bool store)
+{
+    if (store) *p = v;
+    return v;
+}
+__device__ __forceinline__ float round_and_store1(__half* p, float v, bool store)
+{
+    const __half hv = __float2half_rn(v);
+    if (store) *p = hv;
+    return __half2float(hv);
+}
+
+// Channels a multiple of 4, 16-byte (float) / 8-byte (half) aligned rows: a
+// lane owns four consecutive channels of one output pixel, eight neighbouring
+// lanes own the 32 channels of a packed word and OR their nibbles with three
+// DPP exchanges.  Lanes past the last channel of a ragged last word idle.
+// SF: window size known at compile time (all S*S loads in flight), 0 = p.s.
+template <typename T, int SF>
+__global__ __launch_bounds__(256) void avgpool_pack4_kernel(const T* __restrict__ src,
+                                                            const float* __restrict__ bias, PoolShape p,
+                                                            T* __restrict__ pooled, uint32_t* __restrict__ bits)
+{
+    const int s = SF ? SF : p.s;
+    const float count = (float)(s * s);
+    const int upp = 8 * p.cw;                       // lanes per output pixel
+    const int lane8 = threadIdx.x & 7;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t u64 = (int64_t)blockIdx.x * 256 + threadIdx.x; u64 < p.units; u64 += stride) {
+        const int u = (int)u64;
+        const int pixel = u / upp;
+        const int q = u - pixel * upp;
+        const int c0 = 4 * q;
+        const bool live = c0 < p.c;
+        const int rowo = pixel / p.wo;
+        const int ow = pixel - rowo * p.wo;
+        const int n = rowo / p.ho;
+        const int oh = rowo - n * p.ho;
+        const T* win = src + (((int64_t)n * p.h + (int64_t)oh * s) * p.w + (int64_t)ow * s) * p.c + (live ? c0 : 0);
+        f4 acc;
+        if constexpr (SF != 0) {
+            f4 v[SF * SF];
+#pragma unroll
+            for (int a = 0; a < SF; ++a)
+#pragma unroll
+                for (int b = 0; b < SF; ++b) v[a * SF + b] = load4(win + ((int64_t)a * p.w + b) * p.c);
+            acc = v[0];
+#pragma unroll
+            for (int k = 1; k < SF * SF; ++k) acc = acc + v[k];
+        } else {
+            acc = load4(win);
+            for (int a = 0; a < s; ++a)
+                for (int b = (a == 0 ? 1 : 0); b < s; ++b) acc = acc + load4(win + ((int64_t)a * p.w + b) * p.c);
+        }
+        const f4 mean = acc / count;
+        const f4 kept = round_and_store4(pooled + (int64_t)pixel * p.c + (live ? c0 : 0), mean, live && pooled);
+        if (bits) {
+            f4 b4 = f4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (bias && live) b4 = load4(bias + c0);
+            const f4 t = kept + b4;
+            uint32_t w = ((uint32_t)(t[0] >= 0.0f) | ((uint32_t)(t[1] >= 0.0f) << 1) |
+                          ((uint32_t)(t[2] >= 0.0f) << 2) | ((uint32_t)(t[3] >= 0.0f) << 3))
+                         << (4 * lane8);
+            w = live ? w : 0u;
+            // OR over the 8 lanes of the word: neighbours, pairs, then the other quad
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, true);  // row_half_mirror
+            if (lane8 == 0) bits[(int64_t)pixel * p.cw + (q >> 3)] = w;
+        }
+    }
+}
+
+// Any channel count and alignment: a wave takes 64 consecutive channels of one
+// output pixel, lanes along channels; the wave-wide ballot is the word pair.
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_pack_kernel(const T* __restrict__ src,
+                                                           const float* __restrict__ bias, PoolShape p,
+                                                           T* __restrict__ pooled, uint32_t* __restrict__ bits)
+{
+    const int lane = threadIdx.x & 63;
+    const int groups = (p.c + 63) / 64;
+    const int64_t waves = (int64_t)p.n * p.ho * p.wo * groups;   // below 2^31 as well
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    const float count = (float)(p.s * p.s);
+    for (int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); wv < waves; wv += stride) {
+        const int pixel = (int)wv / groups;
+        const int g = (int)wv - pixel * groups;
+        const int c = 64 * g + lane;
+        const bool live = c < p.c;
+        const int rowo = pixel / p.wo;
+        const int ow = pixel - rowo * p.wo;
+        const int n = rowo / p.ho;
+        const int oh = rowo - n * p.ho;
+        const T* win = src + (((int64_t)n * p.h + (int64_t)oh * p.s) * p.w + (int64_t)ow * p.s) * p.c + (live ? c : 0);
+        float acc = as_float(win[0]);
+        for (int a = 0; a < p.s; ++a)
+            for (int b = (a == 0 ? 1 : 0); b < p.s; ++b) acc = acc + as_float(win[((int64_t)a * p.w + b) * p.c]);
+        const float mean = acc / count;
+        const float kept = round_and_store1(pooled + (int64_t)pixel * p.c + (live ? c : 0), mean, live && pooled);
+        if (bits) {
+            const float t = kept + ((bias && live) ? bias[c] : 0.0f);
+            const uint64_t mask = __ballot(live && t >= 0.0f);
+            if (lane < 2 && 2 * g + lane < p.cw) bits[(int64_t)pixel * p.cw + 2 * g + lane] = (uint32_t)(mask >> (32 * lane));
+        }
+    }
+}
+
+template <typename T>
+hipError_t launch_typed(const T* src, const float* bias, PoolShape p, T* pooled, uint32_t* bits, hipStream_t stream)
+{
+    const uintptr_t vec = 4 * sizeof(T);
+    const bool vector_ok = p.c % 4 == 0 && (reinterpret_cast<uintptr_t>(src) % vec) == 0 &&
+                           (reinterpret_cast<uintptr_t>(pooled) % vec) == 0 &&
+                           (reinterpret_cast<uintptr_t>(bias) % 16) == 0;
+    const int64_t m = (int64_t)p.n * p.ho * p.wo;
+    if (vector_ok) {
+        p.units = (int)(m * 8 * p.cw);
+        int64_t blocks = ((int64_t)p.units + 255) / 256;
+        if (blocks > 16384) blocks = 16384;   // grid-stride beyond that
+        const dim3 grid((unsigned)blocks), block(256);
+        switch (p.s) {
+        case 2: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 2>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
+        case 3: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 3>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
+        case 4: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 4>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
+        default: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 0>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
+        }
+        return hipGetLastError();
+    }
+    const int64_t waves = m * ((p.c + 63) / 64);
+    int64_t blocks = (waves + 3) / 4;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL((avgpool_pack_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, stream, src, bias, p, pooled, bits);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_avgpool_pack(const void* src, bool half, int n, int h, int w, int c, int s, const float* bias,
+                               void* pooled, uint32_t* bits, hipStream_t stream)
+{
+    PoolShape p;
+    p.n = n; p.h = h; p.w = w; p.c = c; p.s = s;
+    p.ho = h / s; p.wo = w / s;
+    p.cw = (c + 31) / 32;
+    p.units = 0;
+    if (half)
+        return launch_typed(static_cast<const __half*>(src), bias, p, static_cast<__half*>(pooled), bits, stream);
+    return launch_typed(static_cast<const float*>(src), bias, p, static_cast<float*>(pooled), bits, stream);
+}
+
+}  // namespace bcnn

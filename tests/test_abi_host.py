@@ -138,7 +138,7 @@ def test_config_table_matches_the_stated_shapes():
 
 
 def test_widened_entry_points_reject_bad_arguments():
-    """bcnn_pack_bias[_replicated], the branch calls and the module call check
+    """bcnn_pack_bias[_replicated], the pooling call, the branch calls and the module call check
     their arguments on the host before any launch."""
     L = B.lib()
     d3 = B.bcnn_conv_desc(n=1, c_in=64, h=8, w=8, c_out=32, kh=3, kw=3, stride=1, pad=1)
@@ -151,6 +151,18 @@ def test_widened_entry_points_reject_bad_arguments():
     assert L.bcnn_pack_bias_replicated(x, B.BCNN_F32, 1, 32, 4, 0, g, z, None) == B.BCNN_ERR_INVALID_ARG
     assert L.bcnn_pack_bias_replicated(x, B.BCNN_F32, 1, 0, 4, 2, g, z, None) == B.BCNN_ERR_INVALID_ARG
     assert L.bcnn_pack_bias_replicated(x, B.BCNN_F32, 1, 1 << 30, 4, 4, g, z, None) == B.BCNN_ERR_UNSUPPORTED
+    # average pooling + bias + sign + pack
+    a = L.bcnn_avgpool_bias_sign_pack
+    assert a(None, B.BCNN_F32, 1, 4, 4, 8, 2, None, z, p, None) == B.BCNN_ERR_INVALID_ARG
+    assert a(x, B.BCNN_F32, 1, 4, 4, 8, 2, None, None, None, None) == B.BCNN_ERR_INVALID_ARG
+    assert a(x, B.BCNN_F32, 1, 4, 4, 8, 0, None, z, p, None) == B.BCNN_ERR_INVALID_ARG
+    assert a(x, B.BCNN_F32, 1, 4, 4, 8, 5, None, z, p, None) == B.BCNN_ERR_INVALID_ARG       # empty pooled map
+    assert a(x, B.BCNN_F32, 1, 64, 64, 8, 9, None, z, p, None) == B.BCNN_ERR_UNSUPPORTED
+    assert a(x, B.BCNN_I8, 1, 4, 4, 8, 2, None, z, p, None) == B.BCNN_ERR_UNSUPPORTED
+    assert a(x, B.BCNN_F32, 1, 4, 4, 8, 2, None, x, p, None) == B.BCNN_ERR_INVALID_ARG        # in place
+    assert a(x, B.BCNN_F32, 1, 4, 4, 8, 2, g + 2, z, p, None) == B.BCNN_ERR_ALIGNMENT
+    assert a(x, B.BCNN_F16, 1, 4, 4, 8, 2, None, z + 1, p, None) == B.BCNN_ERR_ALIGNMENT
+    assert a(x, B.BCNN_F32, 1 << 20, 1 << 10, 1 << 10, 8, 2, None, z, p, None) == B.BCNN_ERR_UNSUPPORTED
     # branches
     f = L.bcnn_conv2d_binary_branches
     assert f(ctypes.byref(d3), 9, x, 0, w, None, 0, g, None, None, 0, None) == B.BCNN_ERR_INVALID_ARG
