@@ -428,8 +428,9 @@ hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int6
     if (c_out % 32 == 0 && ((reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(thr)) & 15) == 0) {
         constexpr int UNROLL = 4;
         const int64_t units = rows * (c_out / 4);
-        int64_t blocks = (units + 256 * UNROLL - 1) / (256 * UNROLL);
-        if (blocks > 4096) blocks = 4096;   // grid-stride beyond that
+        // one round per block: blocks that finish early make room for the rest, so the tail stays short
+        // (the kernel's loop only matters beyond 2^31 - 1 blocks, which the row limit excludes)
+        const int64_t blocks = (units + 256 * UNROLL - 1) / (256 * UNROLL);
         hipLaunchKernelGGL((threshold_sign_pack4_kernel<UNROLL>), dim3((unsigned)blocks), dim3(256), 0,
                            stream, y, thr, units, (int)c_out, y_packed);
         return hipGetLastError();

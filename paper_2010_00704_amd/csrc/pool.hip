@@ -174,8 +174,7 @@ hipError_t launch_typed(const T* src, const float* bias, PoolShape p, T* pooled,
     const int64_t m = (int64_t)p.n * p.ho * p.wo;
     if (vector_ok) {
         p.units = (int)(m * 8 * p.cw);
-        int64_t blocks = ((int64_t)p.units + 255) / 256;
-        if (blocks > 16384) blocks = 16384;   // grid-stride beyond that
+        const int64_t blocks = ((int64_t)p.units + 255) / 256;   // one unit per lane: early blocks make room for the rest
         const dim3 grid((unsigned)blocks), block(256);
         switch (p.s) {
         case 2: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 2>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
