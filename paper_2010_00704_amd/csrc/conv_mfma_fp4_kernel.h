@@ -207,6 +207,18 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // For input block i of this wave: word offset of the row's window top-left
     // tap (may point outside the image; only used where the tap's validity
     // bit is set) and one validity bit per tap.
+    // One validity bit per tap (bit u*ks + v) of the window whose top-left input
+    // position is (ph, pw).  The filter is 1x1 (no padding, every branch is
+    // inside) or 3x3: three column bits, placed once per valid row.
+    auto tap_mask = [&](int ph, int pw) -> uint32_t {
+        if (s.ks == 1) return 0xFFFFFFFFu;
+        uint32_t cols = 0, vm = 0;
+#pragma unroll
+        for (int v = 0; v < 3; ++v) cols |= (uint32_t)((uint32_t)(pw + v) < (uint32_t)s.w) << v;
+#pragma unroll
+        for (int u = 0; u < 3; ++u) vm |= ((uint32_t)(ph + u) < (uint32_t)s.h) ? cols << (3 * u) : 0u;
+        return vm;
+    };
     int rbase[NL - 1];
     uint32_t vmask[NL - 1];
     int bblk[NL - 1];
@@ -225,13 +237,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         const int ph = oh * s.stride - s.pad;
         const int pw = (r - oh * s.wo) * s.stride - s.pad;
         rbase[i] = ((n * s.h + ph) * s.w + pw) * s.cw;
-        uint32_t vm = s.ks == 1 ? 0xFFFFFFFFu : 0u;   // 1x1: no padding, every branch is inside
-        for (int u = 0; u < s.ks; ++u)
-            for (int v = 0; v < s.ks; ++v) {
-                const int ih = ph + u, iw = pw + v;
-                if (ih >= 0 && ih < s.h && iw >= 0 && iw < s.w) vm |= 1u << (u * s.ks + v);
-            }
-        vmask[i] = vm;
+        vmask[i] = tap_mask(ph, pw);
     }
 
     // ---- position of the chunk to fetch next along K.
@@ -302,8 +308,11 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     const uint32_t stage_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)stage;
     auto dma16 = [&](const v4i& rsrc, uint32_t lds_byte, uint32_t offset, uint32_t mask) {
         uint32_t tmp;
+        // wave-uniform by construction; the compiler may still park it in a vector register when
+        // scalar registers run short, and the "s" constraint alone does not move it back
+        const uint32_t lds_s = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_byte);
         asm volatile("s_mov_b32 m0, %1\n\tv_bfi_b32 %0, %3, %2, -16\n\tbuffer_load_dwordx4 %0, %4, 0 offen lds"
-                     : "=&v"(tmp) : "s"(lds_byte), "v"(offset), "v"(mask), "s"(rsrc) : "memory");
+                     : "=&v"(tmp) : "s"(lds_s), "v"(offset), "v"(mask), "s"(rsrc) : "memory");
     };
     // per chunk, before its fetch_piece calls
     int f_real = -1, f_tap = 0, f_off = 0, f_woff = 0;
@@ -380,13 +389,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             const int ph = oh * s.stride - s.pad;
             const int pw_ = (r - oh * s.wo) * s.stride - s.pad;
             (void)n;
-            uint32_t vm = s.ks == 1 ? 0xFFFFFFFFu : 0u;
-            for (int u = 0; u < s.ks; ++u)
-                for (int v = 0; v < s.ks; ++v) {
-                    const int ih = ph + u, iw = pw_ + v;
-                    if (ih >= 0 && ih < s.h && iw >= 0 && iw < s.w) vm |= 1u << (u * s.ks + v);
-                }
-            vmask_d[pb] = vm;
+            vmask_d[pb] = tap_mask(ph, pw_);
         }
     }
 
@@ -720,12 +723,16 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         constexpr int AHEAD = HALF ? 2 : 1;                    // blocks in flight ahead of the one in work
         real4 ids[AHEAD + 1][8];
         const int id0 = MODULE ? c0 % (ep.id_channels > 0 ? ep.id_channels : 1) : 0;   // channel of the identity stream
-        auto load_ids = [&](int pb, real4 (&dst)[8]) {
+        auto load_ids = [&](auto fast_tag, int pb, real4 (&dst)[8]) {
+            constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
             for (int g = 0; g < 8; ++g) {
                 const int m = m0 + 32 * (PB * wp + pb) + 4 * g + prow;
                 real4 t4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
-                if (ep.identity && m < s.m) {
+                if constexpr (FAST) {
+                    t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(
+                        static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels + id0));
+                } else if (ep.identity && m < s.m) {
                     // the identity stream may have fewer channels than the output
                     // (replication by bookkeeping): channel o reads o mod id_channels
                     const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels;
@@ -740,9 +747,26 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 dst[g] = t4;
             }
         };
+        if constexpr (MODULE && !BRANCH) {
+            // the per-channel terms leave the accumulators now, before the identity vectors and the
+            // module's parameters occupy registers: sub[][] is dead from here on
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[cb][pb][r] -= sub[cb][r];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // FAST: the whole workgroup tile lies inside the output, rows and channels
+        // are vector aligned and the module has every part (identity, real stream
+        // out, next bits): no per-element predicates, so the loads and stores of a
+        // block issue back to back.  Everything else takes the general path.
+        auto run = [&](auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
         if constexpr (MODULE) {
 #pragma unroll
-            for (int k = 0; k < AHEAD && k < PB; ++k) load_ids(k, ids[k]);
+            for (int k = 0; k < AHEAD && k < PB; ++k) load_ids(fast_tag, k, ids[k]);
         }
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
@@ -756,6 +780,11 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                         q.y = __float_as_int(tot[cb][pb][r + 1]);
                         q.z = __float_as_int(tot[cb][pb][r + 2]);
                         q.w = __float_as_int(tot[cb][pb][r + 3]);
+                    } else if constexpr (MODULE) {    // the sum is an integer held exactly in a float: it stays one
+                        q.x = __float_as_int(acc[cb][pb][r + 0]);
+                        q.y = __float_as_int(acc[cb][pb][r + 1]);
+                        q.z = __float_as_int(acc[cb][pb][r + 2]);
+                        q.w = __float_as_int(acc[cb][pb][r + 3]);
                     } else {
                         q.x = (int)(acc[cb][pb][r + 0] - sub[cb][r + 0]);
                         q.y = (int)(acc[cb][pb][r + 1] - sub[cb][r + 1]);
@@ -765,7 +794,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     *reinterpret_cast<int4*>(tile + j * ROW_WORDS + 32 * cb + 16 * hsel + r) = q;
                 }
             if constexpr (MODULE) {
-                if (pb + AHEAD < PB) load_ids(pb + AHEAD, ids[(pb + AHEAD) % (AHEAD + 1)]);
+                if (pb + AHEAD < PB) load_ids(fast_tag, pb + AHEAD, ids[(pb + AHEAD) % (AHEAD + 1)]);
             }
             // same wave wrote and reads: LDS operations of a wave complete in order
 #pragma unroll
@@ -788,21 +817,24 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     }
                 } else {
                     real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + c0;
-                    const bool whole = vec_ok && c0 + 4 <= s.c_out;
+                    const bool whole = FAST || (vec_ok && c0 + 4 <= s.c_out);
                     const int qv[4] = {q.x, q.y, q.z, q.w};
                     float v[4];
                     uint32_t nib = 0;
+                    // a missing slope is the slope 1 (pa = 1: 1 * t is t), so FAST always multiplies
+                    const bool has_id = FAST || ep.identity != nullptr;
+                    const bool has_slope = FAST || ep.slope != nullptr;
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         if constexpr (BRANCH)
-                            v[k] = module_tail<HALF>(__int_as_float(qv[k]), ep.identity != nullptr,
-                                                     (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
+                            v[k] = module_tail<HALF>(__int_as_float(qv[k]), has_id,
+                                                     (float)ids[pb % (AHEAD + 1)][g][k], has_slope, pa[k]);
                         else
-                            v[k] = module_value<HALF>((float)qv[k], pg[k], pb_[k], ep.identity != nullptr,
-                                                      (float)ids[pb % (AHEAD + 1)][g][k], ep.slope != nullptr, pa[k]);
-                        nib |= (uint32_t)(c0 + k < s.c_out && v[k] + pc[k] >= 0.0f) << k;
+                            v[k] = module_value<HALF>(__int_as_float(qv[k]), pg[k], pb_[k], has_id,
+                                                      (float)ids[pb % (AHEAD + 1)][g][k], has_slope, pa[k]);
+                        nib |= (uint32_t)((FAST || c0 + k < s.c_out) && v[k] + pc[k] >= 0.0f) << k;
                     }
-                    if (ep.r && row_ok) {
+                    if (FAST || (ep.r && row_ok)) {
                         if (whole) {
                             real4 t4;
 #pragma unroll
@@ -820,11 +852,19 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
                     wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x141, 0xF, 0xF, true);  // row_half_mirror
                     const int wi = ((o0 + 64 * wc) >> 5) + (cgrp >> 3);
-                    if (ep.x_next && row_ok && (cgrp & 7) == 0 && wi < s.cwo)
+                    if ((FAST || (ep.x_next && row_ok && wi < s.cwo)) && (cgrp & 7) == 0)
                         ep.x_next[(size_t)m * s.cwo + wi] = wd;
+                    if constexpr (FAST && !HALF) {     // keeps the live set inside the register budget
+                        if (g & 1) __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
         }
+        };   // run
+        const bool fast = MODULE && vec_ok && ep.identity && ep.r && ep.x_next &&
+                          m0 + WG_PX <= s.m && o0 + WG_CH <= s.c_out;
+        if (fast) run(std::true_type{});
+        else run(std::false_type{});
     }
 }
 

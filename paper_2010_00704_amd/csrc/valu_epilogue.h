@@ -173,14 +173,15 @@ __device__ __forceinline__ void store_words_wave(const ConvShape& s, const Tile<
     }
 }
 
-template <bool HALF, bool FROM_SUMS, typename V>
-__device__ __forceinline__ void module_store_wave(const ConvShape& s, const ModuleEp& ep, const Tile<true>& t,
-                                                  int m_first, int ctile, int lane, const V (&vals)[TN],
-                                                  uint32_t* tile)
+// FAST: all 64 pixels exist, the tile is not a shifted last tile, rows are
+// vector aligned and the module has every part (identity, real stream out,
+// next bits): no per-element predicates, loads and stores issue back to back.
+template <bool HALF, bool FROM_SUMS, bool FAST>
+__device__ __forceinline__ void module_store_wave_parked(const ConvShape& s, const ModuleEp& ep, const Tile<true>& t,
+                                                         int m_first, int ctile, int lane, const uint32_t* tile)
 {
     using real_t = typename std::conditional<HALF, _Float16, float>::type;
     typedef real_t real4 __attribute__((ext_vector_type(4)));
-    park_values(tile, lane, s.k, FROM_SUMS, vals);
     const int cg = lane & 7;
     const int c0 = t.o0 + 4 * cg;                      // the lane's four channels (all real: full tile)
     float pg[4], pb[4], pa[4], pc[4];
@@ -196,15 +197,20 @@ __device__ __forceinline__ void module_store_wave(const ConvShape& s, const Modu
     const int idc = ep.id_channels;
     const int id0 = c0 % idc;
     constexpr uintptr_t AL = HALF ? 7 : 15;
-    const bool vec = (s.c_out % 4 == 0) && (idc % 4 == 0) &&
-                     ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & AL) == 0;
+    const bool vec = FAST || ((s.c_out % 4 == 0) && (idc % 4 == 0) &&
+                              ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & AL) == 0);
+    const bool has_id = FAST || ep.identity != nullptr;
+    const bool has_slope = FAST || ep.slope != nullptr;    // a missing slope is the slope 1 (pa = 1: 1 * t is t)
     // all identity vectors first: the stream may be updated in place
     real4 idv[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const int m = m_first + 8 * k + (lane >> 3);
         real4 v4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
-        if (ep.identity && m < s.m) {
+        if constexpr (FAST) {
+            v4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(
+                static_cast<const real_t*>(ep.identity) + (size_t)m * idc + id0));
+        } else if (ep.identity && m < s.m) {
             const real_t* idrow = static_cast<const real_t*>(ep.identity) + (size_t)m * idc;
             if (vec) {
                 v4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(idrow + id0));
@@ -226,20 +232,18 @@ __device__ __forceinline__ void module_store_wave(const ConvShape& s, const Modu
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if constexpr (FROM_SUMS)
-                v[j] = module_value<HALF>((float)(int)qv[j], pg[j], pb[j], ep.identity != nullptr, (float)idv[k][j],
-                                          ep.slope != nullptr, pa[j]);
+                v[j] = module_value<HALF>((float)(int)qv[j], pg[j], pb[j], has_id, (float)idv[k][j], has_slope, pa[j]);
             else
-                v[j] = module_tail<HALF>(__uint_as_float(qv[j]), ep.identity != nullptr, (float)idv[k][j],
-                                         ep.slope != nullptr, pa[j]);
+                v[j] = module_tail<HALF>(__uint_as_float(qv[j]), has_id, (float)idv[k][j], has_slope, pa[j]);
             nib |= (uint32_t)(v[j] + pc[j] >= 0.0f) << j;
         }
-        if (ep.r && m < s.m) {
+        if (FAST || (ep.r && m < s.m)) {
             real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + c0;
             if (vec) {
                 real4 u;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) u[j] = (real_t)v[j];
-                if (4 * cg >= t.shift) *reinterpret_cast<real4*>(rp) = u;
+                if (FAST || 4 * cg >= t.shift) *reinterpret_cast<real4*>(rp) = u;
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -251,8 +255,26 @@ __device__ __forceinline__ void module_store_wave(const ConvShape& s, const Modu
         wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
         wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
         wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x141, 0xF, 0xF, true);  // row_half_mirror
-        if (ep.x_next && cg == 0 && m < s.m) ep.x_next[(size_t)m * s.cwo + ctile] = wd >> t.shift;
+        if constexpr (FAST) {
+            if (cg == 0) ep.x_next[(size_t)m * s.cwo + ctile] = wd;
+        } else {
+            if (ep.x_next && cg == 0 && m < s.m) ep.x_next[(size_t)m * s.cwo + ctile] = wd >> t.shift;
+        }
     }
+}
+
+template <bool HALF, bool FROM_SUMS, typename V>
+__device__ __forceinline__ void module_store_wave(const ConvShape& s, const ModuleEp& ep, const Tile<true>& t,
+                                                  int m_first, int ctile, int lane, const V (&vals)[TN],
+                                                  uint32_t* tile)
+{
+    park_values(tile, lane, s.k, FROM_SUMS, vals);
+    constexpr uintptr_t AL = HALF ? 7 : 15;
+    const bool fast = ep.identity && ep.r && ep.x_next && t.shift == 0 && m_first + 64 <= s.m &&
+                      s.c_out % 4 == 0 && ep.id_channels % 4 == 0 &&
+                      ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & AL) == 0;
+    if (fast) module_store_wave_parked<HALF, FROM_SUMS, true>(s, ep, t, m_first, ctile, lane, tile);
+    else module_store_wave_parked<HALF, FROM_SUMS, false>(s, ep, t, m_first, ctile, lane, tile);
 }
 
 }  // namespace valu
