@@ -230,14 +230,19 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         const int row = 32 * b + j;
         int m = m0 + row;
         m = m < s.m ? m : s.m - 1;
-        const int hw = s.ho * s.wo;
-        const int n = m / hw;
-        const int r = m - n * hw;
-        const int oh = r / s.wo;
-        const int ph = oh * s.stride - s.pad;
-        const int pw = (r - oh * s.wo) * s.stride - s.pad;
-        rbase[i] = ((n * s.h + ph) * s.w + pw) * s.cw;
-        vmask[i] = tap_mask(ph, pw);
+        if (s.ks == 1 && s.stride == 1) {   // 1x1, unit stride: output pixel m is input pixel m, no divisions
+            rbase[i] = m * s.cw;
+            vmask[i] = 0xFFFFFFFFu;
+        } else {
+            const int hw = s.ho * s.wo;
+            const int n = m / hw;
+            const int r = m - n * hw;
+            const int oh = r / s.wo;
+            const int ph = oh * s.stride - s.pad;
+            const int pw = (r - oh * s.wo) * s.stride - s.pad;
+            rbase[i] = ((n * s.h + ph) * s.w + pw) * s.cw;
+            vmask[i] = tap_mask(ph, pw);
+        }
     }
 
     // ---- position of the chunk to fetch next along K.
@@ -403,6 +408,42 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         for (int pb = 0; pb < PB; ++pb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+
+    // ---- module output: is this workgroup's tile the plain case (whole tile
+    // inside the output, vector-aligned rows, identity / real stream / next bits
+    // all present)?  Then its epilogue runs without per-element predicates, and
+    // the identity vectors of the first pixel block(s) are fetched right here,
+    // so that their trip to HBM hides behind the K loop instead of starting
+    // after it (the real stream may be updated in place: these are reads of
+    // elements only this workgroup writes, and it writes them later).
+    constexpr bool MODULE = OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16 || KIND >= KIND_TAIL_F32;
+    constexpr bool HALF = OUT == OUT_MODULE_F16 || KIND == KIND_TAIL_F16;
+    // (only where 32 registers can be held through the loop: the half-precision stream outside branch mode)
+    constexpr bool EARLY_IDS = MODULE && !BRANCH && HALF;
+    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+    typedef real_t real4 __attribute__((ext_vector_type(4)));
+    constexpr int AHEAD = HALF ? 2 : 1;                    // pixel blocks in flight ahead of the one in work
+    real4 early_ids[EARLY_IDS ? AHEAD : 1][8];
+    bool module_fast = false;
+    if constexpr (MODULE) {
+        const uintptr_t both = reinterpret_cast<uintptr_t>(ep.r) | reinterpret_cast<uintptr_t>(ep.identity);
+        module_fast = ep.identity && ep.r && ep.x_next && s.c_out % 4 == 0 && ep.id_channels % 4 == 0 &&
+                      (both & (HALF ? 7 : 15)) == 0 && m0 + WG_PX <= s.m && o0 + WG_CH <= s.c_out;
+        if constexpr (EARLY_IDS) {
+            if (module_fast) {
+                const int e_c0 = o0 + 64 * wc + 4 * (lane & 15);
+                const int e_id0 = e_c0 % ep.id_channels;
+#pragma unroll
+                for (int k = 0; k < AHEAD && k < PB; ++k)
+#pragma unroll
+                    for (int g = 0; g < 8; ++g) {
+                        const int m = m0 + 32 * (PB * wp + k) + 4 * g + (lane >> 4);
+                        early_ids[k][g] = __builtin_nontemporal_load(reinterpret_cast<const real4*>(
+                            static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels + e_id0));
+                    }
+            }
+        }
+    }
 
     // ---- main loop, software pipelined by hand.
     // A wave issues in order, so whatever follows a run of MFMAs in program
@@ -688,8 +729,6 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         // (the stages are free now); afterwards a lane holds 4 consecutive
         // channels of a pixel, 16 lanes one pixel's 64 channels, and a store
         // instruction writes 256 contiguous bytes per pixel, four pixels at a time.
-        constexpr bool MODULE = OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16 || KIND >= KIND_TAIL_F32;
-        constexpr bool HALF = OUT == OUT_MODULE_F16 || KIND == KIND_TAIL_F16;
         int32_t* y = static_cast<int32_t*>(out);
         constexpr int ROW_WORDS = 64 + 4;                      // padded row: 64 channels
         static_assert(4 * 32 * ROW_WORDS * 4 <= 3 * STAGE_BYTES, "transpose tiles must fit the stages");
@@ -718,9 +757,6 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         // their use and before any store of that block: the real stream may be
         // updated in place, so the compiler must not be left to order these
         // loads against the stores, and issued together they overlap.
-        using real_t = typename std::conditional<HALF, _Float16, float>::type;
-        typedef real_t real4 __attribute__((ext_vector_type(4)));
-        constexpr int AHEAD = HALF ? 2 : 1;                    // blocks in flight ahead of the one in work
         real4 ids[AHEAD + 1][8];
         const int id0 = MODULE ? c0 % (ep.id_channels > 0 ? ep.id_channels : 1) : 0;   // channel of the identity stream
         auto load_ids = [&](auto fast_tag, int pb, real4 (&dst)[8]) {
@@ -766,7 +802,14 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         constexpr bool FAST = decltype(fast_tag)::value;
         if constexpr (MODULE) {
 #pragma unroll
-            for (int k = 0; k < AHEAD && k < PB; ++k) load_ids(fast_tag, k, ids[k]);
+            for (int k = 0; k < AHEAD && k < PB; ++k) {
+                if constexpr (FAST && EARLY_IDS) {
+#pragma unroll
+                    for (int g = 0; g < 8; ++g) ids[k][g] = early_ids[k][g];     // fetched before the K loop
+                } else {
+                    load_ids(fast_tag, k, ids[k]);
+                }
+            }
         }
 #pragma unroll
         for (int pb = 0; pb < PB; ++pb) {
@@ -861,9 +904,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             }
         }
         };   // run
-        const bool fast = MODULE && vec_ok && ep.identity && ep.r && ep.x_next &&
-                          m0 + WG_PX <= s.m && o0 + WG_CH <= s.c_out;
-        if (fast) run(std::true_type{});
+        if (module_fast) run(std::true_type{});
         else run(std::false_type{});
     }
 }

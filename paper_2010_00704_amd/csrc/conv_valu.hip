@@ -62,19 +62,25 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
     if (mtile >= n_mtiles) return;
     const Tile<FULL> t = Tile<FULL>::make(ctile, s.c_out);
 
-    int pn[TM], ph[TM], pw[TM];
+    // 1x1 with unit stride: output pixel m reads input pixel m, no coordinates needed
+    const bool direct = s.ks == 1 && s.stride == 1;
+    int pn[TM], ph[TM], pw[TM], pm[TM];
     bool live[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = mtile * (64 * TM) + i * 64 + lane;
         live[i] = m < s.m;
         const int mc = live[i] ? m : s.m - 1;
-        const int hw = s.ho * s.wo;
-        pn[i] = mc / hw;
-        const int r = mc - pn[i] * hw;
-        const int oh = r / s.wo;
-        ph[i] = oh * s.stride - s.pad;
-        pw[i] = (r - oh * s.wo) * s.stride - s.pad;
+        pm[i] = mc;
+        pn[i] = ph[i] = pw[i] = 0;
+        if (!direct) {
+            const int hw = s.ho * s.wo;
+            pn[i] = mc / hw;
+            const int r = mc - pn[i] * hw;
+            const int oh = r / s.wo;
+            ph[i] = oh * s.stride - s.pad;
+            pw[i] = (r - oh * s.wo) * s.stride - s.pad;
+        }
     }
 
     int32_t acc[TM][TN];
@@ -92,10 +98,15 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
         bool inb[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int ih = ph[i] + u, iw = pw[i] + v;
-            inb[i] = ih >= 0 && ih < s.h && iw >= 0 && iw < s.w;
-            const int ihc = inb[i] ? ih : 0, iwc = inb[i] ? iw : 0;
-            xp[i] = x + ((size_t)(pn[i] * s.h + ihc) * s.w + iwc) * s.cw;
+            if (direct) {
+                inb[i] = true;
+                xp[i] = x + (size_t)pm[i] * s.cw;
+            } else {
+                const int ih = ph[i] + u, iw = pw[i] + v;
+                inb[i] = ih >= 0 && ih < s.h && iw >= 0 && iw < s.w;
+                const int ihc = inb[i] ? ih : 0, iwc = inb[i] ? iw : 0;
+                xp[i] = x + ((size_t)(pn[i] * s.h + ihc) * s.w + iwc) * s.cw;
+            }
         }
         const uint32_t* wt = w + (uint32_t)(tap * s.cw);
         for (int j0 = 0; j0 < s.cw; j0 += VEC) {
