@@ -123,6 +123,63 @@ __device__ __forceinline__ Fp4Masks fp4_masks()
     return k;
 }
 
+// The loader's work of one chunk (the global -> LDS loads of the chunk fetched
+// ahead and the bookkeeping around them) is cut into small statements, each
+// issued behind a chosen MFMA of the chunk's slot program.  A wave issues in
+// order and roughly one instruction per four cycles, so a 32-cycle MFMA hides
+// about seven other instructions; bunched behind the first MFMAs of a chunk the
+// loader left the matrix core idle.
+//   K-steps 0-1: the loads.  Statement 0 is the weight block; then per input
+//                block: validity mask / offset / load.  In order, each goes to
+//                the next slot whose own fragment work leaves room (a slot
+//                without a share of the weight expansion takes anything); all
+//                are issued before the last slot of K-step 1, where the wave
+//                waits for the chunk fetched earlier.
+//   K-step 2   : the advance to the next fetch position, in four or five parts.
+//   K-step 3   : the position of the next chunk's fetch (two parts) and the
+//                bit counts of the weight words read ahead (two halves each).
+template <int N> struct LoaderSlots { int v[N]; };
+// instructions a slot holds anyway: two for its input half-fragment, three more where one of the
+// eight weight-fragment registers of the next K-step falls into it
+template <int NS> constexpr int slot_base(int slot)
+{
+    const int sl = slot % NS;
+    return 2 + 3 * ((sl + 1) * 8 / NS - sl * 8 / NS);
+}
+template <int NS, int NL>
+constexpr LoaderSlots<1 + 3 * (NL - 1)> loader_slots()
+{
+    constexpr int N = 1 + 3 * (NL - 1);
+    constexpr int CAP = 7;
+    int cost[N] = {};
+    cost[0] = 5;
+    for (int p = 0; p < NL - 1; ++p) { cost[1 + 3 * p] = 3; cost[2 + 3 * p] = 1; cost[3 + 3 * p] = 4; }
+    int minbase = slot_base<NS>(0);
+    for (int i = 1; i < NS; ++i) minbase = slot_base<NS>(i) < minbase ? slot_base<NS>(i) : minbase;
+    const int last = 2 * NS - 2;
+    LoaderSlots<N> r{};
+    // (the chunk's first slots also carry what the loop's back edge leaves behind: start behind them)
+    int slot = 2, used = slot_base<NS>(2);
+    for (int j = 0; j < N; ++j) {
+        while (!(used + cost[j] <= CAP || (used == slot_base<NS>(slot) && slot_base<NS>(slot) == minbase)) &&
+               (last - slot) > (N - 1 - j)) {
+            ++slot;
+            used = slot_base<NS>(slot);
+        }
+        r.v[j] = slot;
+        used += cost[j];
+    }
+    return r;
+}
+// n-th (from 1, up to 6) slot of a K-step that has no share of the weight expansion; evenly spread if there are none
+template <int NS> constexpr int light_slot(int n)
+{
+    int seen = 0;
+    for (int sl = 0; sl < NS; ++sl)
+        if (slot_base<NS>(sl) == 2 && ++seen == n) return sl;
+    return (n - 1) * NS / 6;
+}
+
 constexpr int PAD_LDS_WORDS = 9 * 64;   // pad words kept in LDS: taps * cw <= this
 constexpr int MAX_BRANCHES = 16;        // scales kept in LDS: taps <= this
 
@@ -349,6 +406,71 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         }
     };
 
+    // The same work cut into statements for the chunk loop (see loader_slots()).
+    constexpr int ADV_STMTS = EVEN ? 5 : 4;
+    constexpr int N_PIECE = 1 + 3 * (NL - 1);
+    int p_mask = 0;
+    uint32_t p_off = 0;
+    int adv_go = 0, adv_td = 0, adv_rd = 0;
+    auto piece_stmt = [&](auto jc, int buf) {
+        constexpr int j = decltype(jc)::value;
+        if constexpr (j == 0) {
+            fetch_piece(buf, 0);
+        } else {
+            constexpr int pi = (j - 1) / 3, part = (j - 1) % 3;      // input block pi of this wave
+            if constexpr (part == 0) {
+                p_mask = __builtin_amdgcn_sbfe((int)vmask[pi], (uint32_t)f_tap & 31u, 1u) & f_real;
+            } else if constexpr (part == 1) {
+                p_off = (uint32_t)(rbase[pi] + f_off) << 2;
+            } else {
+                dma16(xres, stage_lds + (uint32_t)(buf * NBLK + 4 + bblk[pi]) * 1024u, p_off, (uint32_t)p_mask);
+            }
+        }
+    };
+    auto advance_stmt = [&](auto kc) {
+        constexpr int part = decltype(kc)::value;
+        if constexpr (EVEN) {            // advance() in five parts
+            if constexpr (part == 0) {
+                adv_go = k0.unit + 1 < a.n_chunks ? 1 : 0;   // k0.unit counts chunks here; stop on the last one
+            } else if constexpr (part == 1) {
+                const int ut1 = k0.ut + adv_go;
+                adv_td = ut1 == (a.units_per_tap >> 1) ? 1 : 0;
+                k0.ut = adv_td ? 0 : ut1;
+            } else if constexpr (part == 2) {
+                k0.tap += adv_td;
+                const int v1 = k0.v + adv_td;
+                adv_rd = v1 == s.ks ? 1 : 0;
+                k0.v = adv_rd ? 0 : v1;
+            } else if constexpr (part == 3) {
+                k0.off += (adv_go ? 8 : 0) + (adv_td ? a.tap_step : 0);
+            } else {
+                k0.off += adv_rd ? row_jump : 0;
+                k0.unit += adv_go;
+                fetched += 1;
+            }
+        } else {
+            advance1(part < 2 ? k0 : k1, a.units_per_tap, 4, 1);
+        }
+    };
+    auto begin_stmt = [&](auto kc) {     // fetch_begin() in two parts
+        constexpr int part = decltype(kc)::value;
+        if constexpr (part == 0) {
+            if constexpr (EVEN) {
+                f_real = -(fetched < a.n_chunks ? 1 : 0);
+                f_tap = k0.tap;
+                f_off = k0.off;
+            } else {
+                const int unit = hsel ? k1.unit : k0.unit;
+                f_real = unit < a.n_units ? -1 : 0;
+                f_tap = hsel ? k1.tap : k0.tap;
+                f_off = hsel ? k1.off : k0.off;
+            }
+        } else {
+            if constexpr (EVEN) f_woff = wrow_bytes + k0.unit * 32;
+            else f_woff = wrow_bytes + (hsel ? k1.unit : k0.unit) * 16;
+        }
+    };
+
     // ---- branch mode: F x F as F*F shifted binary 1x1 branches (or P parallel
     // 1x1 branches), each with its own real scale per output channel (BCNN
     // paper, Section 4.2.1, last paragraph; Figure 2, bottom).  A tap's chunks
@@ -455,17 +577,21 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     //   every slot : half of an input fragment two blocks ahead (fragments
     //                live in a ring of four, so few registers hold them) and
     //                a share of the next K-step's two weight fragments
-    //   K-step 0   : global -> LDS loads of chunk c+2; loader bookkeeping
+    //   K-steps 0-1: global -> LDS loads of chunk c+2, a few instructions per
+    //                slot (loader_slots())
     //   K-step 1   : at its end, wait for this wave's loads of chunk c+1
-    //                (issued five K-steps earlier) and workgroup barrier
-    //   K-step 2   : LDS reads of chunk c+1's weight words
+    //                (issued at least four K-steps earlier) and workgroup barrier
+    //   K-step 2   : LDS reads of chunk c+1's weight words; the loader advances
     //   K-step 3   : LDS reads of chunk c+1's input words, each block's right
-    //                after that block's last use
+    //                after that block's last use; position of chunk c+3's fetch
     // Stage c%3 holds chunk c.  All of it is read during chunk c-1, whose
     // end every wave has reached behind chunk c's barrier; chunk c+3's loads
     // are issued a whole chunk after that.
     constexpr int NF = CB + PB;       // words per lane and K-step: weights first, then inputs
     constexpr int NS = CB * PB;       // MFMA slots per K-step
+    constexpr auto LSLOTS = loader_slots<NS, NL>();
+    static_assert(LSLOTS.v[N_PIECE - 1] <= 2 * NS - 2, "the loads must be issued before the wait of K-step 1");
+    static_assert(light_slot<NS>(ADV_STMTS + 1) < NS && light_slot<NS>(2 + 2 * CB) < NS, "bookkeeping slots must exist");
     static_assert(CB == 2, "slot program assumes two channel blocks");
     static_assert(NL + 2 <= NS && NF <= NS && 2 * NL <= 15, "side work must fit the MFMA slots of a K-step");
     const Fp4Masks masks = fp4_masks();
@@ -488,6 +614,22 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // lane's four pad words of that chunk).
     int wnext[CB] = {0, 0}, wpad[CB] = {0, 0}, wpadn[CB] = {0, 0};
     uint4 padq = make_uint4(0u, 0u, 0u, 0u);
+    int cnt_half[CB] = {0, 0};
+    auto count_unit_half = [&](const uint4& q, int f, int half) {   // the same in two halves for the chunk loop
+        if (half == 0) {
+            cnt_half[f] = __builtin_popcount(q.x & 0x77777777u) + __builtin_popcount(q.y & 0x77777777u);
+            return;
+        }
+        const int c = cnt_half[f] + __builtin_popcount(q.z & 0x77777777u) + __builtin_popcount(q.w & 0x77777777u);
+        if constexpr (BRANCH) {
+            wnext[f] = c;
+            if constexpr (PADMODE == 1)
+                wpadn[f] = __builtin_popcount(q.x ^ padq.x) + __builtin_popcount(q.y ^ padq.y) +
+                           __builtin_popcount(q.z ^ padq.z) + __builtin_popcount(q.w ^ padq.w);
+        } else {
+            wpop[f] += c;
+        }
+    };
     auto count_unit = [&](const uint4& q, int f) {   // well after the read, so nothing waits
         const int c = __builtin_popcount(q.x & 0x77777777u) + __builtin_popcount(q.y & 0x77777777u) +
                       __builtin_popcount(q.z & 0x77777777u) + __builtin_popcount(q.w & 0x77777777u);
@@ -556,10 +698,20 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             // set), input block pb in K-step 3 right after the block's last use
             if constexpr (ks == 2 && sl < CB) read_unit(pwn[sl], b1, sl);
             if constexpr (ks == 3 && cb == 1) read_unit(pw[CB + pb], b1, CB + pb);
-            if constexpr (ks == 0 && sl == 0) fetch_begin();
-            if constexpr (ks == 0 && sl < NL) fetch_piece(b2, sl);       // chunk c+2
-            if constexpr (ks == 0 && sl == NL) advance();                // on to the units of the next fetch
-            if constexpr (ks == 3 && sl >= NS - CB) count_unit(pwn[sl - (NS - CB)], sl - (NS - CB));
+            // chunk c+2's loads, then the loader's bookkeeping for chunk c+3, a statement at a time
+            static_for<N_PIECE>([&](auto jc) {
+                if constexpr (LSLOTS.v[decltype(jc)::value] == i) piece_stmt(jc, b2);
+            });
+            static_for<ADV_STMTS>([&](auto kc) {
+                if constexpr (i == 2 * NS + light_slot<NS>(decltype(kc)::value + 2)) advance_stmt(kc);
+            });
+            static_for<2>([&](auto kc) {
+                if constexpr (i == 3 * NS + light_slot<NS>(decltype(kc)::value + 1)) begin_stmt(kc);
+            });
+            static_for<2 * CB>([&](auto kc) {        // bit counts of the weight words read in K-step 2
+                constexpr int k = decltype(kc)::value;
+                if constexpr (i == 3 * NS + light_slot<NS>(k + 3)) count_unit_half(pwn[k >> 1], k >> 1, k & 1);
+            });
             __builtin_amdgcn_sched_barrier(0);
         });
 #pragma unroll
@@ -573,6 +725,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         for (int i = 0; i < NL; ++i) fetch_piece(c, i);
         advance();
     }
+    fetch_begin();                                       // chunk 2: the loop expects its position ready
     if constexpr (FUSED) {
         // |y| <= K, so thresholds beyond +-(K+1) decide nothing new and are clamped
         if (t < WG_CH)
