@@ -368,6 +368,11 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     const v4i xres = make_rsrc(x, a.x_bytes);
     const v4i wres = make_rsrc(w, a.w_bytes);
     const uint32_t stage_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)stage;
+    // LDS byte addresses, within a stage, of the blocks this wave fills (`buf` below is a stage's byte offset)
+    const uint32_t w_lds = stage_lds + (uint32_t)wave * 1024u;
+    uint32_t x_lds[NL - 1];
+#pragma unroll
+    for (int i = 0; i < NL - 1; ++i) x_lds[i] = stage_lds + (uint32_t)(4 + bblk[i]) * 1024u;
     auto dma16 = [&](const v4i& rsrc, uint32_t lds_byte, uint32_t offset, uint32_t mask) {
         uint32_t tmp;
         // wave-uniform by construction; the compiler may still park it in a vector register when
@@ -396,12 +401,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     };
     auto fetch_piece = [&](int buf, int i) {  // i = 0: weight block; i = 1..NL-1: input blocks
         if (i == 0) {
-            dma16(wres, stage_lds + (uint32_t)(buf * NBLK + wave) * 1024u, (uint32_t)f_woff, (uint32_t)f_real);
+            dma16(wres, w_lds + (uint32_t)buf, (uint32_t)f_woff, (uint32_t)f_real);
         } else {
             // validity bit of the tap, sign-extended to a mask
             int m = __builtin_amdgcn_sbfe((int)vmask[i - 1], (uint32_t)f_tap & 31u, 1u);
             m &= f_real;     // chunks past the end fetch nothing (an out-of-range offset returns 0 at once)
-            dma16(xres, stage_lds + (uint32_t)(buf * NBLK + 4 + bblk[i - 1]) * 1024u,
+            dma16(xres, x_lds[i - 1] + (uint32_t)buf,
                   (uint32_t)(rbase[i - 1] + f_off) << 2, (uint32_t)m);
         }
     };
@@ -423,7 +428,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             } else if constexpr (part == 1) {
                 p_off = (uint32_t)(rbase[pi] + f_off) << 2;
             } else {
-                dma16(xres, stage_lds + (uint32_t)(buf * NBLK + 4 + bblk[pi]) * 1024u, p_off, (uint32_t)p_mask);
+                dma16(xres, x_lds[pi] + (uint32_t)buf, p_off, (uint32_t)p_mask);
             }
         }
     };
@@ -606,7 +611,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // words during K-step 3, right after their last use.
     auto read_unit = [&](uint4& dst, int buf, int f) {
         const int blk = f < CB ? 2 * wc + f : 4 + PB * wp + (f - CB);
-        dst = *reinterpret_cast<const uint4*>(lds0 + buf * STAGE_BYTES + blk * 1024);
+        dst = *reinterpret_cast<const uint4*>(lds0 + buf + blk * 1024);
     };
     // Branch mode keeps the counts of the chunk read ahead apart (wnext, wpadn)
     // until the chunk loop knows which tap they belong to; wpadn counts the
@@ -722,7 +727,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     for (int c = 0; c < 2; ++c) {                        // chunks 0, 1 -> stages 0, 1
         fetch_begin();
 #pragma unroll
-        for (int i = 0; i < NL; ++i) fetch_piece(c, i);
+        for (int i = 0; i < NL; ++i) fetch_piece(c * STAGE_BYTES, i);
         advance();
     }
     fetch_begin();                                       // chunk 2: the loop expects its position ready
@@ -749,7 +754,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         for (int jj = 0; jj < 4; ++jj) fb[q][jj] = expand_x(pw[CB + q].x, jj);
 
     {
-        int b0 = 0, b1 = 1, b2 = 2;
+        int b0 = 0, b1 = STAGE_BYTES, b2 = 2 * STAGE_BYTES;   // byte offsets of the three stages
         int tap = 0, chunk_in_tap = 0, par = 0;
         const int c_in = 256 * a.chunks_per_tap;
         for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
