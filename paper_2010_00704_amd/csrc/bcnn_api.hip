@@ -116,9 +116,11 @@ int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w,
     hipError_t e;
     switch (variant) {
         case BCNN_VARIANT_AUTO:
-            // The matrix-core path wins wherever its 128 x 256 tiles are
-            // reasonably full; small or ragged problems stay on the vector ALUs.
-            if (conv_mfma_fp4_supported(s, x, w) && s.c_out >= 64 && s.m >= 1024)
+            // Measured over a grid of shapes (1x1 and 3x3, 128..1024 input and
+            // 32..512 output channels, 49..200 000 pixels): wherever the matrix-core
+            // kernel covers a shape it is faster than the vector-ALU kernel or within
+            // half a microsecond of it, tiny problems included.
+            if (conv_mfma_fp4_supported(s, x, w))
                 e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, nullptr, 0, st);
             else
                 e = launch_conv_valu(s, x, w, fused ? thr : nullptr, out, nullptr, st);
@@ -261,7 +263,8 @@ static int branches_entry(const bcnn_conv_desc* desc, int32_t branches, const ui
     hipError_t e;
     switch (variant) {
         case BCNN_VARIANT_AUTO:
-            if (mfma_ok && s.c_out >= 64 && s.m >= 1024) e = bcnn::launch_conv_branches_mfma(s, a, st);
+            // measured: the matrix-core kernel wins at every size it covers
+            if (mfma_ok) e = bcnn::launch_conv_branches_mfma(s, a, st);
             else e = bcnn::launch_conv_branches(s, a, st);
             break;
         case BCNN_VARIANT_VALU:
@@ -375,7 +378,10 @@ int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_pack
     const bool mfma_ok = bcnn::conv_mfma_fp4_supported(s, x_packed, w_packed);
     switch (variant) {
         case BCNN_VARIANT_AUTO:
-            if (mfma_ok && s.c_out >= 64 && s.m >= 1024)
+            // The module epilogue makes the matrix-core kernel's fixed cost about 12 us
+            // against 7 us on the vector ALUs, so it needs enough work to win: measured
+            // break-even at about 4e7 output elements x input words.
+            if (mfma_ok && (double)s.m * s.c_out * s.cw >= 4.0e7)
                 e = bcnn::launch_conv_mfma_fp4(s, x_packed, w_packed, nullptr, nullptr, &m, 0, st);
             else
                 e = bcnn::launch_conv_valu(s, x_packed, w_packed, nullptr, nullptr, &m, st);

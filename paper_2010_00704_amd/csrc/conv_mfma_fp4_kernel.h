@@ -191,7 +191,13 @@ constexpr int MAX_BRANCHES = 16;        // scales kept in LDS: taps <= this
 enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3, OUT_BRANCH = 4 };
 enum { KIND_F32 = 0, KIND_BITS = 1, KIND_TAIL_F32 = 2, KIND_TAIL_F16 = 3 };
 
-template <int PB, int OUT, bool EVEN>
+// PLAIN (module outputs outside branch mode only): the launcher has checked that
+// every tile is whole along the channels, rows are vector aligned and identity,
+// real stream and next bits are all present; the kernel then carries only the
+// predicate-free epilogue (rows past the end are the one thing it still checks)
+// instead of that and the general one: a third of the code, which a short
+// kernel would otherwise spend its time fetching.
+template <int PB, int OUT, bool EVEN, bool PLAIN = false>
 __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void conv_mfma_fp4_kernel(
     MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
     const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep, BranchEp bp)
@@ -551,11 +557,14 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     typedef real_t real4 __attribute__((ext_vector_type(4)));
     constexpr int AHEAD = HALF ? 2 : 1;                    // pixel blocks in flight ahead of the one in work
     real4 early_ids[EARLY_IDS ? AHEAD : 1][8];
-    bool module_fast = false;
+    static_assert(!PLAIN || (MODULE && !BRANCH), "PLAIN is a module-output variant");
+    bool module_fast = PLAIN;
     if constexpr (MODULE) {
-        const uintptr_t both = reinterpret_cast<uintptr_t>(ep.r) | reinterpret_cast<uintptr_t>(ep.identity);
-        module_fast = ep.identity && ep.r && ep.x_next && s.c_out % 4 == 0 && ep.id_channels % 4 == 0 &&
-                      (both & (HALF ? 7 : 15)) == 0 && m0 + WG_PX <= s.m && o0 + WG_CH <= s.c_out;
+        if constexpr (BRANCH) {      // branch mode decides per workgroup and carries both epilogues
+            const uintptr_t both = reinterpret_cast<uintptr_t>(ep.r) | reinterpret_cast<uintptr_t>(ep.identity);
+            module_fast = ep.identity && ep.r && ep.x_next && s.c_out % 4 == 0 && ep.id_channels % 4 == 0 &&
+                          (both & (HALF ? 7 : 15)) == 0 && m0 + WG_PX <= s.m && o0 + WG_CH <= s.c_out;
+        }
         if constexpr (EARLY_IDS) {
             if (module_fast) {
                 const int e_c0 = o0 + 64 * wc + 4 * (lane & 15);
@@ -564,7 +573,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 for (int k = 0; k < AHEAD && k < PB; ++k)
 #pragma unroll
                     for (int g = 0; g < 8; ++g) {
-                        const int m = m0 + 32 * (PB * wp + k) + 4 * g + (lane >> 4);
+                        int m = m0 + 32 * (PB * wp + k) + 4 * g + (lane >> 4);
+                        m = m < s.m ? m : s.m - 1;           // a row past the end reads the last row; never stored
                         early_ids[k][g] = __builtin_nontemporal_load(reinterpret_cast<const real4*>(
                             static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels + e_id0));
                     }
@@ -924,8 +934,9 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 const int m = m0 + 32 * (PB * wp + pb) + 4 * g + prow;
                 real4 t4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
                 if constexpr (FAST) {
+                    const int mc = m < s.m ? m : s.m - 1;    // a row past the end reads the last row; never stored
                     t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(
-                        static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels + id0));
+                        static_cast<const real_t*>(ep.identity) + (size_t)mc * ep.id_channels + id0));
                 } else if (ep.identity && m < s.m) {
                     // the identity stream may have fewer channels than the output
                     // (replication by bookkeeping): channel o reads o mod id_channels
@@ -952,10 +963,10 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     for (int r = 0; r < 16; ++r) acc[cb][pb][r] -= sub[cb][r];
             __builtin_amdgcn_sched_barrier(0);
         }
-        // FAST: the whole workgroup tile lies inside the output, rows and channels
-        // are vector aligned and the module has every part (identity, real stream
-        // out, next bits): no per-element predicates, so the loads and stores of a
-        // block issue back to back.  Everything else takes the general path.
+        // FAST: the workgroup tile is whole along the channels, rows are vector
+        // aligned and the module has every part (identity, real stream out, next
+        // bits): no per-element predicates except the row bound, so the loads and
+        // stores of a block issue back to back.  Everything else takes the general path.
         auto run = [&](auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
         if constexpr (MODULE) {
@@ -1035,7 +1046,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                                                       (float)ids[pb % (AHEAD + 1)][g][k], has_slope, pa[k]);
                         nib |= (uint32_t)((FAST || c0 + k < s.c_out) && v[k] + pc[k] >= 0.0f) << k;
                     }
-                    if (FAST || (ep.r && row_ok)) {
+                    if (FAST ? row_ok : (ep.r && row_ok)) {
                         if (whole) {
                             real4 t4;
 #pragma unroll
@@ -1053,7 +1064,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
                     wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x141, 0xF, 0xF, true);  // row_half_mirror
                     const int wi = ((o0 + 64 * wc) >> 5) + (cgrp >> 3);
-                    if ((FAST || (ep.x_next && row_ok && wi < s.cwo)) && (cgrp & 7) == 0)
+                    if ((FAST ? row_ok : (ep.x_next && row_ok && wi < s.cwo)) && (cgrp & 7) == 0)
                         ep.x_next[(size_t)m * s.cwo + wi] = wd;
                     if constexpr (FAST && !HALF) {     // keeps the live set inside the register budget
                         if (g & 1) __builtin_amdgcn_sched_barrier(0);
@@ -1062,8 +1073,14 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             }
         }
         };   // run
-        if (module_fast) run(std::true_type{});
-        else run(std::false_type{});
+        if constexpr (PLAIN) {
+            run(std::true_type{});
+        } else if constexpr (MODULE && BRANCH) {
+            if (module_fast) run(std::true_type{});
+            else run(std::false_type{});
+        } else {
+            run(std::false_type{});
+        }
     }
 }
 
@@ -1076,6 +1093,19 @@ hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int
     constexpr int WG_PX = 64 * PB;
     a.n_ptiles = (a.s.m + WG_PX - 1) / WG_PX;
     const unsigned blocks = (unsigned)(a.n_ptiles * a.n_ctiles);
+    if constexpr (OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16) {
+        // the plain case of a module call (see the kernel's PLAIN parameter)
+        const uintptr_t al = OUT == OUT_MODULE_F16 ? 7 : 15;
+        const bool plain = e.identity && e.r && e.x_next && a.s.c_out % WG_CH == 0 && e.id_channels % 4 == 0 &&
+                           ((reinterpret_cast<uintptr_t>(e.r) | reinterpret_cast<uintptr_t>(e.identity)) & al) == 0;
+        if (plain) {
+            if (a.units_per_tap % 2 == 0)
+                hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
+            else
+                hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, false, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
+            return hipGetLastError();
+        }
+    }
     if constexpr (OUT >= OUT_BRANCH) {
         hipLaunchKernelGGL((conv_mfma_fp4_kernel<PB, OUT, true>), dim3(blocks), dim3(256), 0, stream, a, x, w, thr, out, e, b);
     } else {
