@@ -173,3 +173,104 @@ def test_random_branches(dev, seed):
                                                          rbuf.ptr, tb.ptr, v), "branches_module")
             assert np.array_equal(rbuf.get(np.float32).reshape(m, o), r32.reshape(m, o))
             assert np.array_equal(tb.get(np.uint32).reshape(tail_bits.shape), tail_bits)
+
+
+TINY = [
+    # n, c_in, h, w, c_out, k, stride, pad: problems far smaller than one matrix-core tile, which AUTO
+    # still sends to the matrix-core kernel whenever the channel count allows it
+    (1, 128, 1, 1, 1, 1, 1, 0),
+    (1, 128, 1, 1, 32, 1, 1, 0),
+    (1, 256, 1, 2, 100, 1, 1, 0),
+    (1, 128, 3, 3, 7, 3, 1, 1),
+    (1, 256, 3, 3, 64, 3, 1, 0),        # a single output pixel from a 3x3 window
+    (2, 128, 4, 4, 33, 3, 2, 1),
+    (1, 384, 5, 7, 130, 3, 1, 1),       # c_in a multiple of 128 but not of 256
+    (1, 512, 7, 7, 512, 3, 1, 1),
+    (3, 256, 2, 5, 40, 1, 2, 0),
+]
+
+
+@pytest.mark.parametrize("shape", TINY, ids=lambda s: "x".join(map(str, s)))
+def test_tiny_problems_on_every_path(dev, shape):
+    n, c, h, w, o, k, stride, pad = shape
+    seed = 15000 + 31 * c + 7 * o + h
+    x = W.pm1(seed, (n, c, h, w))
+    wt = W.pm1(seed + 1, (o, c, k, k))
+    y = oracle.conv2d_pm1(x, wt, stride, pad)
+    thr = W.thresholds(seed + 2, o, max(1, int(2 * np.sqrt(c * k * k))))
+    want_bits = oracle_bits_of_sign(oracle.threshold_sign(y, thr))
+    desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
+    xp = up(i32(oracle_pack_nchw(x)), dev)
+    wp = up(i32(oracle_pack_nchw(wt)), dev)
+    for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4_T4, B.BCNN_VARIANT_MFMA_FP4_T7,
+              B.BCNN_VARIANT_MFMA_I8):
+        out = Guarded(y.size, dev)
+        rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, None, out.ptr, v)
+        if rc != B.BCNN_ERR_UNSUPPORTED:
+            B.check(rc, "conv")
+            assert np.array_equal(out.get(np.int32).reshape(y.shape), y), "variant %d sums" % v
+        bits = Guarded(want_bits.size, dev)
+        rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, up(thr, dev), bits.ptr, v)
+        if rc != B.BCNN_ERR_UNSUPPORTED:
+            B.check(rc, "fused")
+            assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits), "variant %d bits" % v
+    # the module call on the same tiny problem (AUTO stays on the vector ALUs here, the matrix cores are forced)
+    _, ho, wo, _ = y.shape
+    m = n * ho * wo
+    g = W.uniform_f32(seed + 3, (o,), -1.5, 1.5)
+    b = W.uniform_f32(seed + 4, (o,), -20.0, 20.0)
+    ident = W.uniform_f32(seed + 5, (m, o), -30.0, 30.0)
+    alpha = W.uniform_f32(seed + 6, (o,), 0.0, 0.5)
+    cn = W.uniform_f32(seed + 7, (o,), -5.0, 5.0)
+    _, r32 = oracle.module_epilogue(y, g, b, ident.reshape(y.shape), alpha)
+    mod_bits = oracle_bits_of_sign(oracle.sign_bias_f32(r32.reshape(m, o, 1), cn).reshape(n, ho, wo, o))
+    for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4):
+        rbuf = Guarded(m * o, dev)
+        nb = Guarded(mod_bits.size, dev)
+        rc = B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), up(ident, dev), up(alpha, dev),
+                                         up(cn, dev), B.BCNN_F32, rbuf.ptr, nb.ptr, v)
+        if rc == B.BCNN_ERR_UNSUPPORTED:
+            continue
+        B.check(rc, "module")
+        assert np.array_equal(rbuf.get(np.float32, m * o).reshape(m, o), r32.reshape(m, o)), "variant %d stream" % v
+        assert np.array_equal(nb.get(np.uint32).reshape(mod_bits.shape), mod_bits), "variant %d next bits" % v
+
+
+@pytest.mark.parametrize("shape", [(1, 256, 1, 1, 32, 1, 1, 0, 3), (1, 256, 3, 3, 64, 3, 1, 1, 9), (2, 512, 4, 5, 100, 3, 2, 1, 9),
+                                   (1, 256, 3, 3, 40, 3, 1, 0, 9), (3, 256, 2, 2, 1, 1, 1, 0, 2)],
+                         ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("mode", ["minus", "words", "zero"])
+def test_tiny_branch_problems_on_every_path(dev, shape, mode):
+    n, c, h, w, o, k, stride, pad, p = shape
+    if k == 1 and mode != "minus":
+        pytest.skip("unshifted branches have no padding")
+    seed = 16000 + 13 * o + h + 100 * ["minus", "words", "zero"].index(mode)
+    xb = W.pm1(seed, (p, n, c, h, w), 0.45)
+    wt = W.pm1(seed + 1, (o, c, p) if k == 1 else (o, c, k, k))
+    padv = W.pm1(seed + 2, (p, c))
+    g = W.uniform_f32(seed + 3, (p, o), -1.5, 1.5)
+    hb = W.uniform_f32(seed + 4, (o,), -20.0, 20.0)
+    if mode == "minus":
+        padv_o, words, code = -np.ones((p, c), dtype=np.int8), None, B.BCNN_PAD_WORDS
+    elif mode == "words":
+        padv_o, words, code = padv, oracle_pack_vectors(padv), B.BCNN_PAD_WORDS
+    else:
+        padv_o, words, code = np.zeros((p, c), dtype=np.int8), None, B.BCNN_PAD_ZERO
+    _, z32 = oracle.branches_pm1(xb, padv_o, wt, g, hb, stride, pad)
+    want_bits = oracle_bits_of_sign(oracle.sign_f32(z32))
+    desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
+    cw = (c + 31) // 32
+    xp = up(i32(np.stack([oracle_pack_nchw(xb[t]) for t in range(p)])), dev)
+    wp = up(i32(oracle.pack_channels(wt.reshape(o, c, -1))), dev)
+    pw = up(i32(words), dev) if words is not None else None
+    for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4):
+        out = Guarded(z32.size, dev)
+        rc = B.bcnn_conv2d_binary_branches(desc, p, xp, n * h * w * cw, wp, pw, code, up(g, dev), up(hb, dev), out.ptr, v)
+        if rc == B.BCNN_ERR_UNSUPPORTED:
+            continue
+        B.check(rc, "branches")
+        assert np.array_equal(out.get(np.float32).reshape(z32.shape), z32), "variant %d" % v
+        bits = Guarded(want_bits.size, dev)
+        B.check(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, n * h * w * cw, wp, pw, code, up(g, dev),
+                                                        up(hb, dev), bits.ptr, v), "branches_sign_pack")
+        assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits), "variant %d bits" % v
