@@ -290,6 +290,80 @@ __global__ __launch_bounds__(64) void conv_valu_small_kernel(
     }
 }
 
+// The same for int32 sums with only CT output channels per wave: the sums need
+// no packing, so the channels can be spread over eight times as many waves, each
+// with an eighth of the instruction chain (a tiny problem is nothing but that
+// chain: 64 waves of 430 instructions instead of 8 of 3500).
+template <int CT>
+__global__ __launch_bounds__(64) void conv_valu_small_split_kernel(
+    ConvShape s, int32_t n_ctiles, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
+    int32_t* __restrict__ y)
+{
+    static_assert(CT <= 32, "a lane half holds one channel per lane");
+    const int lane = threadIdx.x;
+    const int ctile = blockIdx.x % n_ctiles;
+    const int mtile = blockIdx.x / n_ctiles;
+    const int o0 = ctile * CT;
+
+    const int m = mtile * 64 + lane;
+    const bool live = m < s.m;
+    const int mc = live ? m : s.m - 1;
+    const int hw = s.ho * s.wo;
+    const int pn = mc / hw;
+    const int rr = mc - pn * hw;
+    const int oh = rr / s.wo;
+    const int ph = oh * s.stride - s.pad;
+    const int pw = (rr - oh * s.wo) * s.stride - s.pad;
+
+    const int row_words = s.ks * s.ks * s.cw;
+    // weights: lane l < 32 holds even words of channel o0 + l % CT, lane 32 + l the odd ones
+    int wch = o0 + (lane & 31) % CT;
+    wch = wch < s.c_out ? wch : s.c_out - 1;
+    const uint32_t* wrow = w + (size_t)wch * row_words + (lane >> 5);
+    uint32_t wr[SMALL_REGS];
+#pragma unroll
+    for (int r = 0; r < SMALL_REGS; ++r) {
+        const int word = 2 * r + (lane >> 5);
+        wr[r] = word < row_words ? wrow[2 * r] : 0u;
+    }
+    uint32_t xr[2 * SMALL_REGS];
+    {
+        int j = 0, u = 0, v = 0;                 // channel word, filter row, filter column of word k
+#pragma unroll
+        for (int k = 0; k < 2 * SMALL_REGS; ++k) {
+            const int ih = ph + u, iw = pw + v;
+            const bool ok = k < row_words && ih >= 0 && ih < s.h && iw >= 0 && iw < s.w;
+            xr[k] = ok ? x[((size_t)(pn * s.h + ih) * s.w + iw) * s.cw + j] : 0u;
+            if (++j == s.cw) {
+                j = 0;
+                if (++v == s.ks) { v = 0; ++u; }
+            }
+        }
+    }
+    int32_t acc[CT];
+#pragma unroll
+    for (int o = 0; o < CT; ++o) acc[o] = 0;
+#pragma unroll
+    for (int r = 0; r < SMALL_REGS; ++r) {
+        if (2 * r < row_words) {
+#pragma unroll
+            for (int o = 0; o < CT; ++o)
+                acc[o] += __builtin_popcount(xr[2 * r] ^ (uint32_t)__builtin_amdgcn_readlane((int)wr[r], o));
+        }
+        if (2 * r + 1 < row_words) {
+#pragma unroll
+            for (int o = 0; o < CT; ++o)
+                acc[o] += __builtin_popcount(xr[2 * r + 1] ^ (uint32_t)__builtin_amdgcn_readlane((int)wr[r], 32 + o));
+        }
+    }
+    if (live) {
+        int32_t* row = y + (size_t)m * s.c_out + o0;
+#pragma unroll
+        for (int o = 0; o < CT; ++o)
+            if (o0 + o < s.c_out) row[o] = s.k - 2 * acc[o];
+    }
+}
+
 // Whether the tiny-problem kernel applies, and its launch.
 bool small_applies(const ConvShape& s)
 {
@@ -305,14 +379,15 @@ hipError_t launch_small(const ConvShape& s, const uint32_t* x, const uint32_t* w
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3(blocks), dim3(64), 0, stream, s, n_ctiles, x, w, thr, out);
     };
-    const bool full = s.c_out >= TN;
-    if (thr) {
-        if (full) go(conv_valu_small_kernel<OUT_BITS, true>);
-        else go(conv_valu_small_kernel<OUT_BITS, false>);
-    } else {
-        if (full) go(conv_valu_small_kernel<OUT_I32, true>);
-        else go(conv_valu_small_kernel<OUT_I32, false>);
+    if (!thr) {        // int32 sums: four channels per wave
+        constexpr int CT = 4;
+        const int split_ctiles = (s.c_out + CT - 1) / CT;
+        hipLaunchKernelGGL((conv_valu_small_split_kernel<CT>), dim3((unsigned)(split_ctiles * ((s.m + 63) / 64))),
+                           dim3(64), 0, stream, s, split_ctiles, x, w, static_cast<int32_t*>(out));
+        return hipGetLastError();
     }
+    if (s.c_out >= TN) go(conv_valu_small_kernel<OUT_BITS, true>);
+    else go(conv_valu_small_kernel<OUT_BITS, false>);
     return hipGetLastError();
 }
 
