@@ -608,6 +608,9 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     static_assert(LSLOTS.v[N_PIECE - 1] <= 2 * NS - 2, "the loads must be issued before the wait of K-step 1");
     static_assert(light_slot<NS>(ADV_STMTS + 1) < NS && light_slot<NS>(2 + 2 * CB) < NS, "bookkeeping slots must exist");
     static_assert(CB == 2, "slot program assumes two channel blocks");
+    // the fragments of the next chunk's blocks 0 and 1 are expanded behind pixel blocks PB-2 and PB-1 of
+    // K-step 3, from words re-read behind blocks 0 and 1 of the same K-step: that needs a few slots between
+    static_assert(PB >= 4, "slot program needs at least four pixel blocks per wave");
     static_assert(NL + 2 <= NS && NF <= NS && 2 * NL <= 15, "side work must fit the MFMA slots of a K-step");
     const Fp4Masks masks = fp4_masks();
     int fa[2][CB][4];                 // weight fragments, double buffered over K-steps
