@@ -27,6 +27,7 @@ struct PoolShape {
     int n, h, w, c, s, ho, wo;
     int cw;          // packed words per output pixel
     int units;       // vector kernel: output pixels * 8 * cw lanes of four channels (the caller keeps it below 2^31)
+    int upp_shift;   // log2(8 * cw) when that is a power of two, else -1
 };
 
 __device__ __forceinline__ f4 load4(const float* p) { return *reinterpret_cast<const f4*>(p); }
@@ -79,52 +80,77 @@ __global__ __launch_bounds__(256) void avgpool_pack4_kernel(const T* __restrict_
                                                             const float* __restrict__ bias, PoolShape p,
                                                             T* __restrict__ pooled, uint32_t* __restrict__ bits)
 {
+    // units per lane and round: small windows have few loads each, so a lane takes several units
+    // (256 apart, which keeps the eight lanes of a word together) and issues all their loads first
+    constexpr int U = SF == 1 ? 4 : SF == 2 ? 2 : 1;
+    constexpr int NV = SF ? SF * SF : 1;
     const int s = SF ? SF : p.s;
     const float count = (float)(s * s);
     const int upp = 8 * p.cw;                       // lanes per output pixel
     const int lane8 = threadIdx.x & 7;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t u64 = (int64_t)blockIdx.x * 256 + threadIdx.x; u64 < p.units; u64 += stride) {
-        const int u = (int)u64;
-        const int pixel = u / upp;
-        const int q = u - pixel * upp;
-        const int c0 = 4 * q;
-        const bool live = c0 < p.c;
-        const int rowo = pixel / p.wo;
-        const int ow = pixel - rowo * p.wo;
-        const int n = rowo / p.ho;
-        const int oh = rowo - n * p.ho;
-        const T* win = src + (((int64_t)n * p.h + (int64_t)oh * s) * p.w + (int64_t)ow * s) * p.c + (live ? c0 : 0);
-        f4 acc;
-        if constexpr (SF != 0) {
-            f4 v[SF * SF];
+    const int64_t stride = (int64_t)gridDim.x * (256 * U);
+    for (int64_t u0 = (int64_t)blockIdx.x * (256 * U) + threadIdx.x; u0 < p.units; u0 += stride) {
+        f4 v[U][NV];
+        int pixel[U], q[U];
+        bool in[U], live[U];
 #pragma unroll
-            for (int a = 0; a < SF; ++a)
+        for (int k = 0; k < U; ++k) {
+            const int64_t u64 = u0 + 256 * k;
+            in[k] = u64 < p.units;                  // the same for the eight lanes of a word
+            const uint32_t u = in[k] ? (uint32_t)u64 : 0u;
+            // the divisions below are most of this kernel's instructions for small windows: the common
+            // cases (a power-of-two word count, a map that is one row of pixels) go without
+            if (p.upp_shift >= 0) {
+                pixel[k] = (int)(u >> p.upp_shift);
+                q[k] = (int)(u & (uint32_t)(upp - 1));
+            } else {
+                pixel[k] = (int)(u / (uint32_t)upp);
+                q[k] = (int)(u - (uint32_t)pixel[k] * (uint32_t)upp);
+            }
+            const int c0 = 4 * q[k];
+            live[k] = in[k] && c0 < p.c;
+            int n = pixel[k], oh = 0, ow = 0;
+            if (p.ho != 1 || p.wo != 1) {
+                const uint32_t rowo = (uint32_t)pixel[k] / (uint32_t)p.wo;
+                ow = (int)((uint32_t)pixel[k] - rowo * (uint32_t)p.wo);
+                n = (int)(rowo / (uint32_t)p.ho);
+                oh = (int)(rowo - (uint32_t)n * (uint32_t)p.ho);
+            }
+            const T* win = src + (((int64_t)n * p.h + (int64_t)oh * s) * p.w + (int64_t)ow * s) * p.c + (live[k] ? c0 : 0);
+            if constexpr (SF != 0) {
 #pragma unroll
-                for (int b = 0; b < SF; ++b) v[a * SF + b] = load4(win + ((int64_t)a * p.w + b) * p.c);
-            acc = v[0];
+                for (int a = 0; a < SF; ++a)
 #pragma unroll
-            for (int k = 1; k < SF * SF; ++k) acc = acc + v[k];
-        } else {
-            acc = load4(win);
-            for (int a = 0; a < s; ++a)
-                for (int b = (a == 0 ? 1 : 0); b < s; ++b) acc = acc + load4(win + ((int64_t)a * p.w + b) * p.c);
+                    for (int b = 0; b < SF; ++b) v[k][a * SF + b] = load4(win + ((int64_t)a * p.w + b) * p.c);
+            } else {
+                f4 acc = load4(win);
+                for (int a = 0; a < s; ++a)
+                    for (int b = (a == 0 ? 1 : 0); b < s; ++b) acc = acc + load4(win + ((int64_t)a * p.w + b) * p.c);
+                v[k][0] = acc;
+            }
         }
-        const f4 mean = acc / count;
-        const f4 kept = round_and_store4(pooled + (int64_t)pixel * p.c + (live ? c0 : 0), mean, live && pooled);
-        if (bits) {
-            f4 b4 = f4{0.0f, 0.0f, 0.0f, 0.0f};
-            if (bias && live) b4 = load4(bias + c0);
-            const f4 t = kept + b4;
-            uint32_t w = ((uint32_t)(t[0] >= 0.0f) | ((uint32_t)(t[1] >= 0.0f) << 1) |
-                          ((uint32_t)(t[2] >= 0.0f) << 2) | ((uint32_t)(t[3] >= 0.0f) << 3))
-                         << (4 * lane8);
-            w = live ? w : 0u;
-            // OR over the 8 lanes of the word: neighbours, pairs, then the other quad
-            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
-            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
-            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, true);  // row_half_mirror
-            if (lane8 == 0) bits[(int64_t)pixel * p.cw + (q >> 3)] = w;
+#pragma unroll
+        for (int k = 0; k < U; ++k) {
+            f4 acc = v[k][0];
+#pragma unroll
+            for (int i = 1; i < NV; ++i) acc = acc + v[k][i];
+            const f4 mean = acc / count;
+            const int c0 = live[k] ? 4 * q[k] : 0;
+            const f4 kept = round_and_store4(pooled + (int64_t)pixel[k] * p.c + c0, mean, live[k] && pooled);
+            if (bits) {
+                f4 b4 = f4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (bias && live[k]) b4 = load4(bias + c0);
+                const f4 t = kept + b4;
+                uint32_t w = ((uint32_t)(t[0] >= 0.0f) | ((uint32_t)(t[1] >= 0.0f) << 1) |
+                              ((uint32_t)(t[2] >= 0.0f) << 2) | ((uint32_t)(t[3] >= 0.0f) << 3))
+                             << (4 * lane8);
+                w = live[k] ? w : 0u;
+                // OR over the 8 lanes of the word: neighbours, pairs, then the other quad
+                w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+                w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
+                w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, true);  // row_half_mirror
+                if (lane8 == 0 && in[k]) bits[(int64_t)pixel[k] * p.cw + (q[k] >> 3)] = w;
+            }
         }
     }
 }
@@ -174,9 +200,11 @@ hipError_t launch_typed(const T* src, const float* bias, PoolShape p, T* pooled,
     const int64_t m = (int64_t)p.n * p.ho * p.wo;
     if (vector_ok) {
         p.units = (int)(m * 8 * p.cw);
-        const int64_t blocks = ((int64_t)p.units + 255) / 256;   // one unit per lane: early blocks make room for the rest
+        const int upl = p.s == 1 ? 4 : p.s == 2 ? 2 : 1;          // units per lane and round, as in the kernel
+        const int64_t blocks = ((int64_t)p.units + 256 * upl - 1) / (256 * upl);   // one round per block
         const dim3 grid((unsigned)blocks), block(256);
         switch (p.s) {
+        case 1: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 1>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
         case 2: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 2>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
         case 3: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 3>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
         case 4: hipLaunchKernelGGL((avgpool_pack4_kernel<T, 4>), grid, block, 0, stream, src, bias, p, pooled, bits); break;
@@ -201,6 +229,9 @@ hipError_t launch_avgpool_pack(const void* src, bool half, int n, int h, int w, 
     p.ho = h / s; p.wo = w / s;
     p.cw = (c + 31) / 32;
     p.units = 0;
+    p.upp_shift = -1;
+    for (int sh = 3; sh < 31; ++sh)
+        if ((8 * p.cw) == (1 << sh)) p.upp_shift = sh;
     if (half)
         return launch_typed(static_cast<const __half*>(src), bias, p, static_cast<__half*>(pooled), bits, stream);
     return launch_typed(static_cast<const float*>(src), bias, p, static_cast<float*>(pooled), bits, stream);
