@@ -364,6 +364,136 @@ __global__ __launch_bounds__(64) void conv_valu_small_split_kernel(
     }
 }
 
+// ---- few waves, long weight rows ---------------------------------------------
+// Between the tiny problems above and the launches that fill the chip several
+// times over lies a gap: some tens to a couple of thousand waves, weight rows
+// longer than the tiny kernel's 36 words.  The main kernel is latency bound
+// there (nothing hides its scalar weight loads: 3x3, 192 -> 64 channels on 1568
+// pixels took 35 us where the instructions alone need 7).  This kernel keeps the
+// tiny kernel's way of getting weights (vector loads, v_readlane to broadcast)
+// and walks the weight row in chunks of 16 words, the next chunk's weights and
+// inputs being fetched while the current one is multiplied.  Three instructions
+// per word and channel instead of two, so it only serves launches that cannot
+// fill the chip.
+constexpr int CHUNK_WORDS = 16;
+
+template <int OUT, bool FULL>
+__global__ __launch_bounds__(64) void conv_valu_chunked_kernel(
+    ConvShape s, int32_t n_ctiles, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
+    const int32_t* __restrict__ thr, void* __restrict__ out)
+{
+    constexpr int WR = CHUNK_WORDS / 2;           // weight registers per chunk: lane half h holds words 8h .. 8h+7
+    const int lane = threadIdx.x;
+    const int half = lane >> 5;
+    const int ctile = blockIdx.x % n_ctiles;
+    const int mtile = blockIdx.x / n_ctiles;
+    const Tile<FULL> t = Tile<FULL>::make(ctile, s.c_out);
+
+    const int m = mtile * 64 + lane;
+    const bool live = m < s.m;
+    const int mc = live ? m : s.m - 1;
+    const int hw = s.ho * s.wo;
+    const int pn = mc / hw;
+    const int rr = mc - pn * hw;
+    const int oh = rr / s.wo;
+    const int ph = oh * s.stride - s.pad;
+    const int pw = (rr - oh * s.wo) * s.stride - s.pad;
+
+    const int row_words = s.ks * s.ks * s.cw;
+    const int n_chunks = (row_words + CHUNK_WORDS - 1) / CHUNK_WORDS;
+    const uint32_t* wrow = w + (size_t)t.chan(lane & 31) * row_words + WR * half;
+
+    // position (channel word j, filter row u, filter column v) of the next input word to fetch
+    int fj = 0, fu = 0, fv = 0, fk = 0;
+    auto fetch = [&](uint32_t (&wr)[WR], uint32_t (&xr)[CHUNK_WORDS], int chunk) {
+#pragma unroll
+        for (int r = 0; r < WR; ++r) {
+            const int word = chunk * CHUNK_WORDS + WR * half + r;
+            wr[r] = word < row_words ? wrow[chunk * CHUNK_WORDS + r] : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < CHUNK_WORDS; ++r) {
+            const int ih = ph + fu, iw = pw + fv;
+            const bool ok = fk < row_words && ih >= 0 && ih < s.h && iw >= 0 && iw < s.w;
+            xr[r] = ok ? x[((size_t)(pn * s.h + ih) * s.w + iw) * s.cw + fj] : 0u;
+            ++fk;
+            if (++fj == s.cw) {
+                fj = 0;
+                if (++fv == s.ks) { fv = 0; ++fu; }
+            }
+        }
+    };
+
+    int32_t acc[TN];
+#pragma unroll
+    for (int o = 0; o < TN; ++o) acc[o] = 0;
+    uint32_t wc[WR], xc[CHUNK_WORDS], wn[WR], xn[CHUNK_WORDS];
+    fetch(wc, xc, 0);
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        if (chunk + 1 < n_chunks) {
+            fetch(wn, xn, chunk + 1);
+        } else {
+#pragma unroll
+            for (int r = 0; r < WR; ++r) wn[r] = 0u;
+#pragma unroll
+            for (int r = 0; r < CHUNK_WORDS; ++r) xn[r] = 0u;
+        }
+        // words past the end of the row are zero on both sides and count nothing
+#pragma unroll
+        for (int r = 0; r < CHUNK_WORDS; ++r)
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                acc[o] += __builtin_popcount(
+                    xc[r] ^ (uint32_t)__builtin_amdgcn_readlane((int)wc[r % WR], 32 * (r / WR) + o));
+#pragma unroll
+        for (int r = 0; r < WR; ++r) wc[r] = wn[r];
+#pragma unroll
+        for (int r = 0; r < CHUNK_WORDS; ++r) xc[r] = xn[r];
+    }
+
+    if constexpr (OUT == OUT_BITS) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int o = 0; o < TN; ++o) {
+            const bool on = (FULL || t.stores(o)) && (s.k - 2 * acc[o] >= thr[t.chan(o)]);
+            word |= (uint32_t)on << o;
+        }
+        if (live) static_cast<uint32_t*>(out)[(size_t)m * s.cwo + ctile] = word >> t.shift;
+    } else {
+        if (live) {
+            int32_t* row = static_cast<int32_t*>(out) + (size_t)m * s.c_out + t.o0;
+#pragma unroll
+            for (int o = 0; o < TN; ++o)
+                if (t.stores(o)) row[o] = s.k - 2 * acc[o];
+        }
+    }
+}
+
+bool chunked_applies(const ConvShape& s)
+{
+    const int64_t waves = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 63) / 64);
+    return s.ks * s.ks * s.cw >= 24 && waves <= 2048;
+}
+
+hipError_t launch_chunked(const ConvShape& s, const uint32_t* x, const uint32_t* w, const int32_t* thr,
+                          void* out, hipStream_t stream)
+{
+    const int n_ctiles = (s.c_out + TN - 1) / TN;
+    const unsigned blocks = (unsigned)(n_ctiles * ((s.m + 63) / 64));
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(64), 0, stream, s, n_ctiles, x, w, thr, out);
+    };
+    const bool full = s.c_out >= TN;
+    if (thr) {
+        if (full) go(conv_valu_chunked_kernel<OUT_BITS, true>);
+        else go(conv_valu_chunked_kernel<OUT_BITS, false>);
+    } else {
+        if (full) go(conv_valu_chunked_kernel<OUT_I32, true>);
+        else go(conv_valu_chunked_kernel<OUT_I32, false>);
+    }
+    return hipGetLastError();
+}
+
 // Whether the tiny-problem kernel applies, and its launch.
 bool small_applies(const ConvShape& s)
 {
@@ -438,6 +568,7 @@ hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_
     // pixel per lane gives twice as many waves, which small problems need to
     // cover 1024 SIMDs.
     if (!ep && small_applies(s)) return launch_small(s, x, w, thr, out, stream);
+    if (!ep && chunked_applies(s)) return launch_chunked(s, x, w, thr, out, stream);
     const int64_t waves2 = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 127) / 128);
     if (waves2 >= 2048) return launch_tm<2>(s, x, w, thr, out, ep, stream);
     return launch_tm<1>(s, x, w, thr, out, ep, stream);
