@@ -13,7 +13,6 @@ Prints ONE JSON line.  `value` is total binary ops per step / step time
 """
 import argparse
 import json
-import math
 import os
 import sys
 import time

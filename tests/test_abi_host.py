@@ -6,7 +6,6 @@ import os
 import re
 
 import numpy as np
-import pytest
 
 from paper_2010_00704_amd import binding as B
 from paper_2010_00704_amd import workloads as W
