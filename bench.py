@@ -230,6 +230,13 @@ def main():
             # profiles/bench_hbm_traffic_pmc.md (shape 5, 2x7 tile); not re-measured by this script
             "traffic": 13.2e6 if dom["cfg"].name.startswith("cfg5") else None,
         }
+    elif args.variant == "mfma_i8":
+        roofline = {
+            "kernel": "conv_mfma_i8_kernel on " + dom["cfg"].name + " (per launch)",
+            "bound": "mfma", "achieved": round(achieved, 1), "peak": 5000.0,   # dense int8 matrix rate, TOP/s
+            "unit": "TOP/s", "frac": round(achieved / 5000.0, 4),
+            "avg_launch_ms": round(dom_ms, 4), "traffic": None,
+        }
     else:
         roofline = {
             "kernel": "conv_valu_kernel on " + dom["cfg"].name + " (per launch)",
@@ -250,7 +257,10 @@ def main():
         "metric": "binary conv TBOPS (and % of VALU popcount peak) per layer shape, 1 MI355X",
         "value": round(value, 2), "unit": "TBOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "u32 bits -> int32",
+        "scaling": "weak", "vs_baseline": None,
+        # the arithmetic the convolution runs in: +-1 as 4-bit floats on the matrix cores (fp32 accumulate,
+        # every sum an exact integer), bytes on the int8 arm, packed 32-bit words on the vector ALUs
+        "dtype": "fp4" if on_mfma else ("int8" if args.variant == "mfma_i8" else "u32"),
         "data": "synthetic",
         "config": {"workload": ("all five layer shapes per step: pack + binary conv "
                                 "(cfg1-2 int32 sums, cfg3-4 fused sign-pack, cfg5 4-layer chain)")
