@@ -220,9 +220,10 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     __shared__ uint4 stage[3 * NBLK * 64];
     __shared__ int wpop_lds[WG_CH];
     __shared__ int thr_lds[FUSED ? WG_CH : 1];                  // thresholds of the tile, fetched at kernel start
-    __shared__ int tapcnt_lds[BRANCH ? 2 : 1][2][WG_CH];        // per tap: [parity][pop | pad count][channel]
+    // per tap: [parity][what the accumulator carries besides the tap's sum | the tap's sum where the tap is padding][channel]
+    __shared__ __align__(16) float tapf_lds[BRANCH ? 2 : 1][2][WG_CH];
     __shared__ uint32_t pad_lds[BRANCH ? PAD_LDS_WORDS + 8 : 1];
-    __shared__ float scale_lds[BRANCH ? MAX_BRANCHES : 1][WG_CH];   // scale[tap][channel of the tile]
+    __shared__ __align__(16) float scale_lds[BRANCH ? MAX_BRANCHES : 1][WG_CH];   // scale[tap][channel of the tile]
     const ConvShape& s = a.s;
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -788,23 +789,31 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     // lanes l and l^32 read the two K-halves of the same weight row
                     const int both = wpop[cb] + __shfl_xor(wpop[cb], 32, 64);
                     const int bothp = wpad[cb] + __shfl_xor(wpad[cb], 32, 64);
-                    if (hsel == 0) {
-                        tapcnt_lds[par][0][64 * wc + 32 * cb + row_to_channel(j)] = both;
-                        if constexpr (PADMODE == 1) tapcnt_lds[par][1][64 * wc + 32 * cb + row_to_channel(j)] = bothp;
+                    if (hsel == 0) {          // one lane per channel turns the counts into the two terms
+                        const int ch = 64 * wc + 32 * cb + row_to_channel(j);
+                        tapf_lds[par][0][ch] = (float)(2 * both - 192 * a.chunks_per_tap);
+                        if constexpr (PADMODE == 1) tapf_lds[par][1][ch] = (float)(c_in - 2 * bothp);
                     }
                     wpop[cb] = wnext[cb];
                     wpad[cb] = wpadn[cb];
                 }
                 __syncthreads();
+                // the lane's 16 channels of a block are consecutive: four 16-byte reads per table
+                typedef float f4v __attribute__((ext_vector_type(4)));
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int cl = 64 * wc + 32 * cb + 16 * hsel + r;
-                        const float corr = (float)(2 * tapcnt_lds[par][0][cl] - 192 * a.chunks_per_tap);
+                        const int cl4 = 64 * wc + 32 * cb + 16 * hsel + (r & ~3);
+                        const f4v corr4 = *reinterpret_cast<const f4v*>(&tapf_lds[par][0][cl4]);
+                        const f4v g4 = *reinterpret_cast<const f4v*>(&scale_lds[tap][cl4]);
+                        const float corr = corr4[r & 3];
+                        const float g = g4[r & 3];
                         float ypad = 0.0f;
-                        if constexpr (PADMODE == 1) ypad = (float)(c_in - 2 * tapcnt_lds[par][1][cl]);
-                        const float g = scale_lds[tap][cl];
+                        if constexpr (PADMODE == 1) {
+                            const f4v ypad4 = *reinterpret_cast<const f4v*>(&tapf_lds[par][1][cl4]);
+                            ypad = ypad4[r & 3];
+                        }
 #pragma unroll
                         for (int pb = 0; pb < PB; ++pb) {
                             const bool inb = PADMODE == 0 || ((vmask_d[pb] >> tap) & 1u);
