@@ -276,6 +276,87 @@ def main():
     print(json.dumps(line))
 
 
+def _gpu_sensors():
+    """(power sensor path, shader clock table path) of the first amdgpu card, or None."""
+    import glob
+    power = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                   glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
+    sclk = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+    if not power or not sclk:
+        return None
+    return power[0], sclk[0]
+
+
+def sustained_load(torch, B, dev, work, seconds=2.0):
+    """Replays 20-launch HIP graphs of one kernel for `seconds` each and samples the board's
+    power and shader clock meanwhile.  Returns a list of {"what", "us_per_launch", "watts",
+    "sclk_mhz"}; the sensor fields are None where the sensors cannot be read."""
+    import threading
+    import time
+
+    wk = next((w for w in work if w["cfg"].name.startswith("cfg5")), work[-1])
+    cfg, d = wk["cfg"], wk["descs"][0]
+    x_rand = torch.randint(-2**31, 2**31 - 1, wk["xp"].shape, dtype=torch.int32, device=dev)
+    w_rand, thr, y = wk["wps"][0], wk["thr"][0], wk["outs"][0]
+    x_zero, w_zero = torch.zeros_like(x_rand), torch.zeros_like(w_rand)
+    fsink = torch.empty(256 * 256, dtype=torch.float32, device=dev)
+    cases = [
+        ("%s conv, AUTO, random bits" % cfg.name,
+         lambda: B.check(B.bcnn_conv2d_binary_variant(d, x_rand, w_rand, thr, y, B.BCNN_VARIANT_AUTO), "conv")),
+        ("%s conv, AUTO, all-zero words" % cfg.name,
+         lambda: B.check(B.bcnn_conv2d_binary_variant(d, x_zero, w_zero, thr, y, B.BCNN_VARIANT_AUTO), "conv")),
+        ("fp4 matrix-core probe, 256 blocks x 400 rounds",
+         lambda: B.check(B.bcnn_diag_mfma_fp4_peak(fsink, 256, 400), "probe")),
+    ]
+    sens = _gpu_sensors()
+    res = []
+    for what, launch in cases:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            launch()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(20):
+                launch()
+        samples, stop = [], threading.Event()
+
+        def sampler():
+            while not stop.is_set():
+                try:
+                    watts = float(open(sens[0]).read()) / 1e6
+                    cur = [l for l in open(sens[1]).read().splitlines() if l.rstrip().endswith("*")][0]
+                    samples.append((watts, float(cur.split(":")[1].lower().replace("mhz", "").replace("*", ""))))
+                except (OSError, ValueError, IndexError):
+                    pass
+                time.sleep(0.05)
+
+        th = threading.Thread(target=sampler) if sens else None
+        if th:
+            th.start()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n, t0 = 0, time.time()
+        a.record()
+        while time.time() - t0 < seconds:
+            for _ in range(20):
+                g.replay()
+            n += 400
+            torch.cuda.synchronize()
+        b.record()
+        b.synchronize()
+        stop.set()
+        if th:
+            th.join()
+        tail = samples[len(samples) // 3:]          # after the sensors' averaging has settled
+        res.append({"what": what, "us_per_launch": round(a.elapsed_time(b) * 1e3 / n, 2),
+                    "watts": round(sum(p for p, _ in tail) / len(tail), 0) if tail else None,
+                    "sclk_mhz": round(sum(c for _, c in tail) / len(tail), 0) if tail else None})
+    return res
+
+
+
 def aux_measurements(torch, B, dev, work):
     """Stand-alone figures outside the timed steps: the measured xor+popcount
     issue rate, and HBM rates of the pack and epilogue kernels on rotating
@@ -343,6 +424,13 @@ def aux_measurements(torch, B, dev, work):
         b.record()
         b.synchronize()
         out[tag] = round(mblocks * 4 * 4000 * 8 * 2.0 * 32 * 32 * 64 / (a.elapsed_time(b) * 1e-3) / 1e12, 1)
+
+    # Clock and board power while the dominant kernel is replayed back to back for about two
+    # seconds (the amdgpu driver's sysfs sensors, read by a thread every 50 ms): once on random
+    # operands, once on all-zero words (constant operands), and the matrix-core probe.  The
+    # constant-operand launch shows the kernel's time at the full clock; the difference to the
+    # random-operand launch is what the board's power limit costs.
+    out["sustained"] = sustained_load(torch, B, dev, work)
 
     # pack kernel on the largest input (shape 4, 205 MB fp32), 4 rotating copies
     wk = work[3]
