@@ -43,6 +43,8 @@ def parse():
                          "instead of one chain of launches; measured 2.5 %% faster per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-aux", action="store_true", help="skip the stand-alone kernel measurements")
+    ap.add_argument("--no-sustained", action="store_true",
+                    help="skip the two-second replays with power and clock sampling (e.g. under a profiler)")
     return ap.parse_args()
 
 
@@ -247,7 +249,7 @@ def main():
 
     aux = {}
     if not args.no_aux and shapes == [1, 2, 3, 4, 5]:
-        aux = aux_measurements(torch, B, dev, work)
+        aux = aux_measurements(torch, B, dev, work, sustained=not args.no_sustained)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -357,7 +359,7 @@ def sustained_load(torch, B, dev, work, seconds=2.0):
 
 
 
-def aux_measurements(torch, B, dev, work):
+def aux_measurements(torch, B, dev, work, sustained=True):
     """Stand-alone figures outside the timed steps: the measured xor+popcount
     issue rate, and HBM rates of the pack and epilogue kernels on rotating
     buffers larger than the last-level cache."""
@@ -430,7 +432,8 @@ def aux_measurements(torch, B, dev, work):
     # operands, once on all-zero words (constant operands), and the matrix-core probe.  The
     # constant-operand launch shows the kernel's time at the full clock; the difference to the
     # random-operand launch is what the board's power limit costs.
-    out["sustained"] = sustained_load(torch, B, dev, work)
+    if sustained:
+        out["sustained"] = sustained_load(torch, B, dev, work)
 
     # pack kernel on the largest input (shape 4, 205 MB fp32), 4 rotating copies
     wk = work[3]

@@ -564,13 +564,19 @@ hipError_t launch_tm(const ConvShape& s, const uint32_t* x, const uint32_t* w, c
 hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                             const int32_t* thr, void* out, const ModuleEp* ep, hipStream_t stream)
 {
-    // Two pixels per lane halve the scalar weight traffic per popcount; one
-    // pixel per lane gives twice as many waves, which small problems need to
-    // cover 1024 SIMDs.
+    // Two pixels per lane halve the scalar weight traffic per popcount (one
+    // pixel per lane costs about 10 % more per popcount, measured); one pixel
+    // per lane gives twice as many waves, which small problems need to cover
+    // 1024 SIMDs and which evens out a launch of a few workgroups per compute
+    // unit: all of them are resident at once, so the unit with the most
+    // workgroups sets the time (784 workgroups of two pixels per lane are 4 on
+    // some of the 256 units and 3 on the rest; 1568 of one pixel are 7 and 6).
     if (!ep && small_applies(s)) return launch_small(s, x, w, thr, out, stream);
     if (!ep && chunked_applies(s)) return launch_chunked(s, x, w, thr, out, stream);
-    const int64_t waves2 = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 127) / 128);
-    if (waves2 >= 2048) return launch_tm<2>(s, x, w, thr, out, ep, stream);
+    const int64_t n_ct = (s.c_out + TN - 1) / TN;
+    const int64_t waves2 = n_ct * ((s.m + 127) / 128), waves1 = n_ct * ((s.m + 63) / 64);
+    const int64_t rounds2 = ((waves2 + 3) / 4 + 255) / 256, rounds1 = ((waves1 + 3) / 4 + 255) / 256;
+    if (waves2 >= 2048 && 20 * rounds2 <= 11 * rounds1) return launch_tm<2>(s, x, w, thr, out, ep, stream);
     return launch_tm<1>(s, x, w, thr, out, ep, stream);
 }
 
