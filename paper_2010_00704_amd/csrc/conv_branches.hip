@@ -273,8 +273,12 @@ hipError_t launch_tm(const ConvShape& s, const BranchArgs& a, hipStream_t stream
 
 hipError_t launch_conv_branches(const ConvShape& s, const BranchArgs& a, hipStream_t stream)
 {
-    const int64_t waves2 = (int64_t)((s.c_out + TN - 1) / TN) * ((s.m + 127) / 128);
-    if (waves2 >= 2048) return launch_tm<2>(s, a, stream);
+    // two pixels per lane unless one pixel per lane spreads a launch of a few
+    // workgroups per compute unit better (same rule as the plain vector-ALU kernel)
+    const int64_t n_ct = (s.c_out + TN - 1) / TN;
+    const int64_t waves2 = n_ct * ((s.m + 127) / 128), waves1 = n_ct * ((s.m + 63) / 64);
+    const int64_t rounds2 = ((waves2 + 3) / 4 + 255) / 256, rounds1 = ((waves1 + 3) / 4 + 255) / 256;
+    if (waves2 >= 2048 && 20 * rounds2 <= 11 * rounds1) return launch_tm<2>(s, a, stream);
     return launch_tm<1>(s, a, stream);
 }
 
