@@ -98,6 +98,7 @@ __device__ __forceinline__ void static_for(F&& f)
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int WG_CH = 128;  // channels per workgroup (2 waves x 2 blocks of 32)
@@ -559,26 +560,47 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     constexpr int AHEAD = HALF ? 2 : 1;                    // pixel blocks in flight ahead of the one in work
     real4 early_ids[EARLY_IDS ? AHEAD : 1][8];
     static_assert(!PLAIN || (MODULE && !BRANCH), "PLAIN is a module-output variant");
+    // The plain case addresses the identity, the real stream and the next bits as raw buffers, one
+    // descriptor per wave and tensor: base = the row of the wave's first pixel, size = the wave's rows
+    // that exist.  A lane's byte offset is then a 32-bit constant plus the row's (wave-uniform) offset,
+    // a row past the end of the tensor reads zeros and stores nothing, and a lane that has nothing to
+    // store uses an offset past every size: no 64-bit address arithmetic and no predicates per row.
+    auto wave_rows_rsrc = [&](const void* base, int row_bytes) {
+        const int m_w = m0 + 32 * PB * wp;
+        int rows = s.m - m_w;
+        rows = rows < 0 ? 0 : (rows > 32 * PB ? 32 * PB : rows);
+        const uint64_t at = reinterpret_cast<uint64_t>(base) + (uint64_t)m_w * (uint64_t)row_bytes;
+        // wave-uniform by construction; said explicitly so that the descriptor is built in scalar registers
+        const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)at);
+        const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(at >> 32));
+        return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<char*>((hi << 32) | lo), 0,
+                                                 __builtin_amdgcn_readfirstlane(rows * row_bytes), 0x00020000);
+    };
+    auto load_real4 = [](__amdgpu_buffer_rsrc_t res, uint32_t lane_off, int row_off) -> real4 {
+        if constexpr (HALF)      // aux 2: streamed once, non-temporal
+            return __builtin_bit_cast(real4, __builtin_amdgcn_raw_buffer_load_b64(res, (int)(lane_off + (uint32_t)row_off), 0, 2));
+        else
+            return __builtin_bit_cast(real4, __builtin_amdgcn_raw_buffer_load_b128(res, (int)(lane_off + (uint32_t)row_off), 0, 2));
+    };
     bool module_fast = PLAIN;
     if constexpr (MODULE) {
         if constexpr (BRANCH) {      // branch mode decides per workgroup and carries both epilogues
             const uintptr_t both = reinterpret_cast<uintptr_t>(ep.r) | reinterpret_cast<uintptr_t>(ep.identity);
             module_fast = ep.identity && ep.r && ep.x_next && s.c_out % 4 == 0 && ep.id_channels % 4 == 0 &&
+                          s.c_out <= (1 << 20) &&
                           (both & (HALF ? 7 : 15)) == 0 && m0 + WG_PX <= s.m && o0 + WG_CH <= s.c_out;
         }
         if constexpr (EARLY_IDS) {
             if (module_fast) {
                 const int e_c0 = o0 + 64 * wc + 4 * (lane & 15);
-                const int e_id0 = e_c0 % ep.id_channels;
+                const uint32_t e_voff = (uint32_t)(((lane >> 4) * ep.id_channels + e_c0 % ep.id_channels) *
+                                                   (int)sizeof(real_t));
+                const auto e_res = wave_rows_rsrc(ep.identity, ep.id_channels * (int)sizeof(real_t));
 #pragma unroll
                 for (int k = 0; k < AHEAD && k < PB; ++k)
 #pragma unroll
-                    for (int g = 0; g < 8; ++g) {
-                        int m = m0 + 32 * (PB * wp + k) + 4 * g + (lane >> 4);
-                        m = m < s.m ? m : s.m - 1;           // a row past the end reads the last row; never stored
-                        early_ids[k][g] = __builtin_nontemporal_load(reinterpret_cast<const real4*>(
-                            static_cast<const real_t*>(ep.identity) + (size_t)m * ep.id_channels + e_id0));
-                    }
+                    for (int g = 0; g < 8; ++g)
+                        early_ids[k][g] = load_real4(e_res, e_voff, (32 * k + 4 * g) * ep.id_channels * (int)sizeof(real_t));
             }
         }
     }
@@ -939,6 +961,15 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         // loads against the stores, and issued together they overlap.
         real4 ids[AHEAD + 1][8];
         const int id0 = MODULE ? c0 % (ep.id_channels > 0 ? ep.id_channels : 1) : 0;   // channel of the identity stream
+        // plain case: descriptors and lane offsets of the three streams (see wave_rows_rsrc)
+        const int esz = (int)sizeof(real_t);
+        const auto fast_id_res = wave_rows_rsrc(MODULE ? ep.identity : nullptr, ep.id_channels * esz);
+        const auto fast_r_res = wave_rows_rsrc(MODULE ? ep.r : nullptr, s.c_out * esz);
+        const auto fast_xn_res = wave_rows_rsrc(MODULE ? ep.x_next : nullptr, s.cwo * 4);
+        const uint32_t fast_id_off = (uint32_t)((prow * ep.id_channels + id0) * esz);
+        const uint32_t fast_r_off = (uint32_t)((prow * s.c_out + c0) * esz);
+        const uint32_t fast_xn_off = (cgrp & 7) == 0
+            ? (uint32_t)((prow * s.cwo + ((o0 + 64 * wc) >> 5) + (cgrp >> 3)) * 4) : 0x7FFFFFF0u;
         auto load_ids = [&](auto fast_tag, int pb, real4 (&dst)[8]) {
             constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
@@ -946,9 +977,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 const int m = m0 + 32 * (PB * wp + pb) + 4 * g + prow;
                 real4 t4 = {(real_t)0, (real_t)0, (real_t)0, (real_t)0};
                 if constexpr (FAST) {
-                    const int mc = m < s.m ? m : s.m - 1;    // a row past the end reads the last row; never stored
-                    t4 = __builtin_nontemporal_load(reinterpret_cast<const real4*>(
-                        static_cast<const real_t*>(ep.identity) + (size_t)mc * ep.id_channels + id0));
+                    t4 = load_real4(fast_id_res, fast_id_off, (32 * pb + 4 * g) * ep.id_channels * (int)sizeof(real_t));
                 } else if (ep.identity && m < s.m) {
                     // the identity stream may have fewer channels than the output
                     // (replication by bookkeeping): channel o reads o mod id_channels
@@ -1058,7 +1087,14 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                                                       (float)ids[pb % (AHEAD + 1)][g][k], has_slope, pa[k]);
                         nib |= (uint32_t)((FAST || c0 + k < s.c_out) && v[k] + pc[k] >= 0.0f) << k;
                     }
-                    if (FAST ? row_ok : (ep.r && row_ok)) {
+                    if constexpr (FAST) {
+                        real4 t4;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) t4[k] = (real_t)v[k];
+                        const int at = (int)(fast_r_off + (uint32_t)((32 * pb + 4 * g) * s.c_out * esz));
+                        if constexpr (HALF) __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(v2i, t4), fast_r_res, at, 0, 0);
+                        else __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4i, t4), fast_r_res, at, 0, 0);
+                    } else if (ep.r && row_ok) {
                         if (whole) {
                             real4 t4;
 #pragma unroll
@@ -1076,8 +1112,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                     wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x4E, 0xF, 0xF, true);   // quad_perm [2,3,0,1]
                     wd |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)wd, 0x141, 0xF, 0xF, true);  // row_half_mirror
                     const int wi = ((o0 + 64 * wc) >> 5) + (cgrp >> 3);
-                    if ((FAST ? row_ok : (ep.x_next && row_ok && wi < s.cwo)) && (cgrp & 7) == 0)
+                    if constexpr (FAST) {
+                        __builtin_amdgcn_raw_buffer_store_b32(
+                            (int)wd, fast_xn_res, (int)(fast_xn_off + (uint32_t)((32 * pb + 4 * g) * s.cwo * 4)), 0, 0);
+                    } else if (ep.x_next && row_ok && wi < s.cwo && (cgrp & 7) == 0) {
                         ep.x_next[(size_t)m * s.cwo + wi] = wd;
+                    }
                     if constexpr (FAST && !HALF) {     // keeps the live set inside the register budget
                         if (g & 1) __builtin_amdgcn_sched_barrier(0);
                     }
@@ -1108,7 +1148,9 @@ hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int
     if constexpr (OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16) {
         // the plain case of a module call (see the kernel's PLAIN parameter)
         const uintptr_t al = OUT == OUT_MODULE_F16 ? 7 : 15;
+        // (c_out bound: a wave's rows of any of the three streams stay below 2^31 bytes)
         const bool plain = e.identity && e.r && e.x_next && a.s.c_out % WG_CH == 0 && e.id_channels % 4 == 0 &&
+                           a.s.c_out <= (1 << 20) &&
                            ((reinterpret_cast<uintptr_t>(e.r) | reinterpret_cast<uintptr_t>(e.identity)) & al) == 0;
         if (plain) {
             if (a.units_per_tap % 2 == 0)
