@@ -13,8 +13,9 @@ bool conv_mfma_fp4_supported(const ConvShape& s, const uint32_t* x, const uint32
     // and both packed tensors must be addressable by 31-bit byte offsets
     const int64_t x_bytes = (int64_t)s.n * s.h * s.w * s.cw * 4;
     const int64_t w_bytes = (int64_t)s.c_out * n_units * 16;
+    // and a wave's rows of an output tensor (up to 224 rows of c_out 4-byte elements) by 31-bit offsets too
     return s.cw % 4 == 0 && (bits & 15) == 0 && 256 * n_chunks + s.k + 2 < (1 << 22) &&
-           x_bytes < (1ll << 31) && w_bytes < (1ll << 31);
+           x_bytes < (1ll << 31) && w_bytes < (1ll << 31) && s.c_out <= (1 << 20);
 }
 
 // Rounds of workgroups over the 256 CUs times the work of one workgroup:

@@ -931,7 +931,6 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         // (the stages are free now); afterwards a lane holds 4 consecutive
         // channels of a pixel, 16 lanes one pixel's 64 channels, and a store
         // instruction writes 256 contiguous bytes per pixel, four pixels at a time.
-        int32_t* y = static_cast<int32_t*>(out);
         constexpr int ROW_WORDS = 64 + 4;                      // padded row: 64 channels
         static_assert(4 * 32 * ROW_WORDS * 4 <= 3 * STAGE_BYTES, "transpose tiles must fit the stages");
         __syncthreads();                                       // every wave is done with the stages
@@ -970,6 +969,11 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         const uint32_t fast_r_off = (uint32_t)((prow * s.c_out + c0) * esz);
         const uint32_t fast_xn_off = (cgrp & 7) == 0
             ? (uint32_t)((prow * s.cwo + ((o0 + 64 * wc) >> 5) + (cgrp >> 3)) * 4) : 0x7FFFFFF0u;
+        // int32 sums: the same for the output tensor, one offset per channel of the lane
+        const auto y_res = wave_rows_rsrc(MODULE ? nullptr : out, s.c_out * 4);
+        uint32_t y_off[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) y_off[k] = c0 + k < s.c_out ? (uint32_t)((prow * s.c_out + c0 + k) * 4) : 0x7FFFFFF0u;
         auto load_ids = [&](auto fast_tag, int pb, real4 (&dst)[8]) {
             constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
@@ -1057,16 +1061,16 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 const int m = m0 + 32 * (PB * wp + pb) + px;
                 const bool row_ok = m < s.m;
                 if constexpr (!MODULE) {
-                    if (row_ok) {
-                        int32_t* dstp = y + (size_t)m * s.c_out + c0;
-                        if (vec_ok && c0 + 4 <= s.c_out) {
-                            __builtin_nontemporal_store(v4i{q.x, q.y, q.z, q.w}, reinterpret_cast<v4i*>(dstp));
-                        } else {
-                            if (c0 + 0 < s.c_out) dstp[0] = q.x;
-                            if (c0 + 1 < s.c_out) dstp[1] = q.y;
-                            if (c0 + 2 < s.c_out) dstp[2] = q.z;
-                            if (c0 + 3 < s.c_out) dstp[3] = q.w;
-                        }
+                    // the sums as a raw buffer per wave (see wave_rows_rsrc): rows past the end and
+                    // channels past c_out (offsets set past every size) are dropped by the bounds check
+                    const uint32_t row_off = (uint32_t)((32 * pb + 4 * g) * s.c_out * 4);
+                    if (vec_ok) {
+                        __builtin_amdgcn_raw_buffer_store_b128(v4i{q.x, q.y, q.z, q.w}, y_res, (int)(y_off[0] + row_off), 0, 2);
+                    } else {
+                        __builtin_amdgcn_raw_buffer_store_b32(q.x, y_res, (int)(y_off[0] + row_off), 0, 2);
+                        __builtin_amdgcn_raw_buffer_store_b32(q.y, y_res, (int)(y_off[1] + row_off), 0, 2);
+                        __builtin_amdgcn_raw_buffer_store_b32(q.z, y_res, (int)(y_off[2] + row_off), 0, 2);
+                        __builtin_amdgcn_raw_buffer_store_b32(q.w, y_res, (int)(y_off[3] + row_off), 0, 2);
                     }
                 } else {
                     real_t* rp = static_cast<real_t*>(ep.r) + (size_t)m * s.c_out + c0;
