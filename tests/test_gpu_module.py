@@ -250,3 +250,45 @@ def test_module_full_size_1x1(dev, half):
     want_r, want_bits = oracle_module(x_all[picks], wt, cfg.stride, cfg.pad, g, b, id_pick, alpha, c, half)
     assert np.array_equal(got_r.reshape(-1, cfg.c_out), want_r)
     assert np.array_equal(got_bits, want_bits)
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+def test_module_special_values(dev, variant, half):
+    """Signed zeros, denormals, the largest finite values and infinities in the
+    identity stream, a next bias that holds -0 and cancels stored values exactly:
+    the float chain keeps them as the oracle does (denormals are not flushed, a
+    value too large for half becomes an infinity, the tie r + c = 0 gives bit 1).
+    Slopes stay positive and no term is infinite on both sides, so no NaN arises:
+    a NaN's payload is the one thing the two sides need not agree on."""
+    shape = (2, 128, 24, 24, 128, 1, 1, 0) if variant != B.BCNN_VARIANT_VALU else (2, 64, 12, 12, 64, 1, 1, 0)
+    n, cin, h, w, o, k, stride, pad = shape
+    x = W.pm1(9970, (n, cin, h, w))
+    wt = W.pm1(9971, (o, cin, k, k))
+    m = n * h * w
+    g, b, _, alpha, c = make_params(9972, m, o, half, True)
+    alpha = np.maximum(alpha, np.float32(0.25))
+    if half:
+        special = np.array([0.0, -0.0, 6e-8, -6e-8, 6.1e-5, -6.1e-5, np.inf, -np.inf, 65504.0, -65504.0, 1.0, -2.5],
+                           dtype=np.float16)
+    else:
+        special = np.array([0.0, -0.0, 1e-45, -1e-45, 1.1754942e-38, -1.1754942e-38, 1.17549435e-38, np.inf,
+                            -np.inf, 3.4e38, -3.4e38, 65504.0, 1e-8, -2.5], dtype=np.float32)
+    pick = (W.raw_u64(9973, 0, m * o) % np.uint64(len(special))).astype(np.int64)
+    ident = special[pick].reshape(m, o)
+    c = c.copy()
+    c[0::7] = np.float32(-0.0)
+    with np.errstate(over="ignore"):          # values too large for half become infinities, on purpose
+        want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident, alpha, c, half)
+    assert not np.any(np.isnan(want_r.astype(np.float32)))      # no NaN in play
+    # a bias that cancels what the first row stores, so that r + c is exactly zero there
+    c2 = c.copy()
+    fin = np.isfinite(want_r[0].astype(np.float32))
+    c2[fin] = -want_r[0].astype(np.float32)[fin]
+    for cc in (c, c2):
+        with np.errstate(over="ignore"):
+            want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident, alpha, cc, half)
+        r, bits = gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, cc, half, variant)
+        view = np.uint16 if half else np.uint32
+        assert np.array_equal(r.view(view), want_r.view(view))            # bit patterns: -0 is not +0
+        assert np.array_equal(bits, want_bits)
