@@ -4,6 +4,8 @@ oracle.  The fixed shape lists of the other GPU tests aim at known tile edges;
 this one looks for the edges nobody thought of.  Shapes stay inside what the
 header documents as supported; a variant that does not cover a shape skips.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -37,7 +39,9 @@ def draw_shape(rng, mfma_friendly):
     return n, c_in, h, w, c_out, k, stride, pad
 
 
-CASES = [(seed, seed % 2 == 0) for seed in range(40)]
+# BCNN_TEST_EXTRA_SEEDS=N adds N more seeds to every test below (a longer run for a changed kernel)
+EXTRA = int(os.environ.get("BCNN_TEST_EXTRA_SEEDS", "0"))
+CASES = [(seed, seed % 2 == 0) for seed in range(40 + EXTRA)]
 
 
 @pytest.mark.parametrize("seed,mfma_friendly", CASES)
@@ -73,7 +77,7 @@ def test_random_plain_and_fused(dev, seed, mfma_friendly):
     assert ran >= 4
 
 
-@pytest.mark.parametrize("seed,mfma_friendly", CASES[:24])
+@pytest.mark.parametrize("seed,mfma_friendly", CASES[:24 + EXTRA])
 @pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
 def test_random_module(dev, seed, mfma_friendly, half):
     rng = np.random.default_rng(13000 + seed)
@@ -112,7 +116,7 @@ def test_random_module(dev, seed, mfma_friendly, half):
         assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(24 + EXTRA))
 def test_random_branches(dev, seed):
     rng = np.random.default_rng(14000 + seed)
     mfma_friendly = seed % 2 == 0
