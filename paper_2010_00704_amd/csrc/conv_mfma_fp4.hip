@@ -46,6 +46,8 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     a.tap_step = 0;
     a.taps = s.ks * s.ks;
     a.chunks_per_tap = 0;
+    a.div_hw = DivBy::make(s.ho * s.wo);
+    a.div_wo = DivBy::make(s.wo);
     // Feature maps of 7, 14, 28, 56 pixels a side make the pixel count a
     // multiple of 49: 7 pixel blocks per wave then tile it without remainder
     // where 4 would leave a quarter of the last round idle.  The 2 x 7 tile
@@ -99,6 +101,8 @@ hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& b, hi
     // its end; 1x1 with parallel branches: every branch starts at the same pixel
     a.row_jump = s.ks == 1 ? 0 : (s.w - s.ks) * s.cw;
     a.tap_step = (int32_t)b.x_branch_stride + (s.ks == 1 ? -s.cw : 0);
+    a.div_hw = DivBy::make(s.ho * s.wo);
+    a.div_wo = DivBy::make(s.wo);
     BranchEp bp;
     bp.scale = b.scale;
     bp.bias = b.bias;

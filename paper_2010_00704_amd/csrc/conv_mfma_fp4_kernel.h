@@ -59,6 +59,31 @@
 
 namespace bcnn {
 
+// Division of 0 <= n < 2^31 by a divisor d fixed at launch: with s = ceil(log2 d) and
+// mul = floor(2^(31+s) / d) + 1 (which fits 32 bits), floor(n / d) = (n * mul) >> (31 + s) exactly,
+// because the error n * (mul * d - 2^(31+s)) / (d * 2^(31+s)) stays below 1 / d.  Three instructions
+// instead of the thirty of a division by an unknown; d = 1 has no 32-bit multiplier and is selected.
+struct DivBy {
+    uint32_t mul;
+    int32_t shift;   // s - 1
+    int32_t d;
+    static DivBy make(int32_t d)
+    {
+        DivBy r{0u, 0, d};
+        if (d > 1) {
+            int s = 0;
+            while ((int64_t(1) << s) < d) ++s;
+            r.mul = (uint32_t)((uint64_t(1) << (31 + s)) / (uint64_t)d + 1u);
+            r.shift = s - 1;
+        }
+        return r;
+    }
+    __device__ __forceinline__ int operator()(int n) const
+    {
+        return d == 1 ? n : (int)(__umulhi((uint32_t)n, mul) >> shift);
+    }
+};
+
 struct MfmaArgs {
     ConvShape s;
     int32_t n_ptiles, n_ctiles;
@@ -71,6 +96,7 @@ struct MfmaArgs {
     int32_t tap_step;       // words added when a tap (branch) is complete: 0 for the plain convolution
     int32_t taps;           // filter taps = branches
     int32_t chunks_per_tap; // branch mode: cw / 8
+    DivBy div_hw, div_wo;   // division of a pixel index by ho*wo and by wo
 };
 
 // Branch mode (see the section in front of the fold below): per-branch scales,
@@ -300,9 +326,9 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             vmask[i] = 0xFFFFFFFFu;
         } else {
             const int hw = s.ho * s.wo;
-            const int n = m / hw;
+            const int n = a.div_hw(m);
             const int r = m - n * hw;
-            const int oh = r / s.wo;
+            const int oh = a.div_wo(r);
             const int ph = oh * s.stride - s.pad;
             const int pw = (r - oh * s.wo) * s.stride - s.pad;
             rbase[i] = ((n * s.h + ph) * s.w + pw) * s.cw;
@@ -523,12 +549,10 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             int m = m0 + 32 * (PB * wp + pb) + j;
             m = m < s.m ? m : s.m - 1;
             const int hw = s.ho * s.wo;
-            const int n = m / hw;
-            const int r = m - n * hw;
-            const int oh = r / s.wo;
+            const int r = m - a.div_hw(m) * hw;
+            const int oh = a.div_wo(r);
             const int ph = oh * s.stride - s.pad;
             const int pw_ = (r - oh * s.wo) * s.stride - s.pad;
-            (void)n;
             vmask_d[pb] = tap_mask(ph, pw_);
         }
     }
