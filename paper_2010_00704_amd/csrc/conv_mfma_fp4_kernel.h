@@ -560,13 +560,9 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // ---- accumulators: lane (pixel j = lane%32, half h = lane/32), register r
     //      <-> channel 32*block + 16h + r.  They start at zero; every constant
     //      and per-channel term is applied in the epilogue.
+    //      (They are cleared further down, between the issue of the first loads
+    //      and the wait for them.)
     v16f acc[CB][PB];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
 
     // ---- module output: is this workgroup's tile the plain case (whole tile
     // inside the output, vector-aligned rows, identity / real stream / next bits
@@ -791,6 +787,20 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         advance();
     }
     fetch_begin();                                       // chunk 2: the loop expects its position ready
+    // The accumulators are cleared here, while the first chunks are on their way from memory.  Left to
+    // itself the compiler re-creates the zeros right in front of the loop, after the wait; the empty
+    // statements below take every accumulator as input and output, so the zeros must exist here.
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
+            if constexpr (PB >= 7) asm volatile("" : "+a"(acc[cb][pb]));     // the wide tile keeps them in acc registers
+            else asm volatile("" : "+v"(acc[cb][pb]));
+        }
+    __builtin_amdgcn_sched_barrier(0);
     if constexpr (FUSED) {
         // |y| <= K, so thresholds beyond +-(K+1) decide nothing new and are clamped
         if (t < WG_CH)
