@@ -378,10 +378,13 @@ int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_pack
     const bool mfma_ok = bcnn::conv_mfma_fp4_supported(s, x_packed, w_packed);
     switch (variant) {
         case BCNN_VARIANT_AUTO:
-            // The module epilogue makes the matrix-core kernel's fixed cost about 12 us
-            // against 7 us on the vector ALUs, so it needs enough work to win: measured
-            // break-even at about 4e7 output elements x input words.
-            if (mfma_ok && (double)s.m * s.c_out * s.cw >= 4.0e7)
+            // The module epilogue makes the matrix-core kernel's fixed cost about 10 us
+            // against 7 us on the vector ALUs, whose time grows with the words per output
+            // (taps x C_in / 32): measured on 1x1 and 3x3 modules, the matrix cores win at
+            // every size from 16 words on, and below that from about 3e7 output elements x
+            // words on.
+            const int kwords = s.ks * s.ks * s.cw;
+            if (mfma_ok && (kwords >= 16 || (double)s.m * s.c_out * kwords >= 3.0e7))
                 e = bcnn::launch_conv_mfma_fp4(s, x_packed, w_packed, nullptr, nullptr, &m, 0, st);
             else
                 e = bcnn::launch_conv_valu(s, x_packed, w_packed, nullptr, nullptr, &m, st);
