@@ -376,6 +376,7 @@ int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_pack
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e;
     const bool mfma_ok = bcnn::conv_mfma_fp4_supported(s, x_packed, w_packed);
+    const int kwords = s.ks * s.ks * s.cw;      // packed words per output element
     switch (variant) {
         case BCNN_VARIANT_AUTO:
             // The module epilogue makes the matrix-core kernel's fixed cost about 10 us
@@ -383,7 +384,6 @@ int bcnn_conv2d_binary_module(const bcnn_conv_desc* desc, const uint32_t* x_pack
             // (taps x C_in / 32): measured on 1x1 and 3x3 modules, the matrix cores win at
             // every size from 16 words on, and below that from about 3e7 output elements x
             // words on.
-            const int kwords = s.ks * s.ks * s.cw;
             if (mfma_ok && (kwords >= 16 || (double)s.m * s.c_out * kwords >= 3.0e7))
                 e = bcnn::launch_conv_mfma_fp4(s, x_packed, w_packed, nullptr, nullptr, &m, 0, st);
             else
