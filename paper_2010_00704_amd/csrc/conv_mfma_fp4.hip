@@ -53,15 +53,20 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     // where 4 would leave a quarter of the last round idle.  The 2 x 7 tile
     // runs one workgroup per CU, so nothing hides its prologue and epilogue,
     // where two co-resident 2 x 4 workgroups per CU overlap each other's ends.
-    // Measured where the wide tile saves a round: 7-9 % ahead at 14 to 36
-    // chunks, 2-3 % at 9, level at 4, behind at 3; where it saves none the
-    // narrow tile wins at every length.  Only the fused kernel has the
+    // Measured where the wide tile saves a round, on launches whose 2 x 4
+    // workgroups are all resident at once (392 of them): 7-9 % ahead at 14 to
+    // 36 chunks, 2-3 % at 9, level at 4, behind at 3; with 784 workgroups and 9
+    // chunks the two tiles are level, so there the narrow one stays up to 16
+    // chunks; where the wide tile saves no round the narrow one wins at every
+    // length.  Only the fused kernel has the
     // registers for it: the int32 epilogue of a 2 x 7 tile would spill.
     // `tile` = 4 or 7 forces a tile (for tests and measurements), 0 chooses.
     if (ep && ep->half) return launch_pb<4, OUT_MODULE_F16>(a, x, w, nullptr, nullptr, ep, stream);
     if (ep) return launch_pb<4, OUT_MODULE_F32>(a, x, w, nullptr, nullptr, ep, stream);
     if (!thr) return launch_pb<4, OUT_I32>(a, x, w, thr, out, nullptr, stream);
-    if (tile == 7 || (tile == 0 && a.n_chunks >= 9 && tile_cost(s, 7) < tile_cost(s, 4)))
+    const int64_t wgs4 = ((s.m + 255) / 256) * a.n_ctiles;     // workgroups of the 2 x 4 tile; 512 are resident at once
+    const bool long_enough = a.n_chunks >= 16 || (a.n_chunks >= 9 && wgs4 <= 512);
+    if (tile == 7 || (tile == 0 && long_enough && tile_cost(s, 7) < tile_cost(s, 4)))
         return launch_pb<7, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
     return launch_pb<4, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
 }
