@@ -52,37 +52,13 @@
 // sign bits of a block, one cross-half exchange completes the 32-bit word.
 #pragma once
 #include "bcnn_common.h"
+#include "div_by.h"
 
 #include <type_traits>
 
 #include <utility>
 
 namespace bcnn {
-
-// Division of 0 <= n < 2^31 by a divisor d fixed at launch: with s = ceil(log2 d) and
-// mul = floor(2^(31+s) / d) + 1 (which fits 32 bits), floor(n / d) = (n * mul) >> (31 + s) exactly,
-// because the error n * (mul * d - 2^(31+s)) / (d * 2^(31+s)) stays below 1 / d.  Three instructions
-// instead of the thirty of a division by an unknown; d = 1 has no 32-bit multiplier and is selected.
-struct DivBy {
-    uint32_t mul;
-    int32_t shift;   // s - 1
-    int32_t d;
-    static DivBy make(int32_t d)
-    {
-        DivBy r{0u, 0, d};
-        if (d > 1) {
-            int s = 0;
-            while ((int64_t(1) << s) < d) ++s;
-            r.mul = (uint32_t)((uint64_t(1) << (31 + s)) / (uint64_t)d + 1u);
-            r.shift = s - 1;
-        }
-        return r;
-    }
-    __device__ __forceinline__ int operator()(int n) const
-    {
-        return d == 1 ? n : (int)(__umulhi((uint32_t)n, mul) >> shift);
-    }
-};
 
 struct MfmaArgs {
     ConvShape s;
