@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     build,
     conv2d_pm1,
     conv2d_pm1_at,
+    load_bf16,
     module_epilogue,
     module_tail,
     num_threads,
@@ -20,6 +21,8 @@ from .binding import (  # noqa: F401
     replicate_channels,
     sign_bias_f32,
     sign_f32,
+    store_bf16,
+    store_f16,
     threshold_sign,
     unpack_channels,
 )

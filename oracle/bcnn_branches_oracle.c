@@ -238,3 +238,105 @@ void oracle_module_tail(const double *z64, const float *z32, const float *identi
             }
         }
 }
+
+/*
+ * Storage rounding of the real stream.  A module writes its real output in
+ * the stream's type and everything behind it (the next module's bias + sign,
+ * the identity addition of the module after) reads the value as stored
+ * (Section 4.2.1, first paragraph: the bias is added to the module's real
+ * input; the paper fixes no storage type, so the reading is: the input is
+ * what memory holds).  Two 16-bit types:
+ *   binary16 : 1 sign, 5 exponent bits (bias 15), 10 fraction bits
+ *   bfloat16 : 1 sign, 8 exponent bits (bias 127), 7 fraction bits
+ * The conversion is the IEEE 754 one: round to nearest, ties to the even
+ * fraction; results at or beyond largest finite + half a step are infinity;
+ * below the smallest normal number the step stays that of the smallest
+ * normal exponent (gradual underflow, no flush); a NaN stays a NaN (quiet,
+ * sign kept, payload dropped).  It is written out from that definition: take
+ * the exponent e of |x| (not below the smallest normal one), express |x| in
+ * units of 2^(e - fraction bits), round that count to an integer.
+ * nearbyint() rounds ties to even in the default rounding mode, which is the
+ * only one this library runs in; the division by a power of two is exact.
+ */
+static uint16_t store_16bit(float x, int ebits, int fbits, float *back)
+{
+    const int bias = (1 << (ebits - 1)) - 1;
+    const int emin = 1 - bias, emax = bias;
+    const uint16_t sign = signbit(x) ? (uint16_t)(1u << (ebits + fbits)) : 0;
+    const uint16_t all_ones_exp = (uint16_t)(((1u << ebits) - 1u) << fbits);
+    if (isnan(x)) {
+        *back = signbit(x) ? -NAN : NAN;
+        return (uint16_t)(sign | all_ones_exp | (1u << (fbits - 1)));
+    }
+    const double a = fabs((double)x);
+    if (a == 0.0) {
+        *back = signbit(x) ? -0.0f : 0.0f;
+        return sign;
+    }
+    if (isinf(x)) {
+        *back = x;
+        return (uint16_t)(sign | all_ones_exp);
+    }
+    int ex;
+    (void)frexp(a, &ex);            /* a = m * 2^ex with 0.5 <= m < 1, so 2^(ex-1) <= a < 2^ex */
+    int e = ex - 1;
+    if (e < emin)
+        e = emin;
+    double unit = ldexp(1.0, e - fbits);
+    double count = nearbyint(a / unit);             /* 0 .. 2^(fbits+1) */
+    if (count == ldexp(1.0, fbits + 1)) {           /* rounded up into the next exponent */
+        e += 1;
+        unit = ldexp(1.0, e - fbits);
+        count = ldexp(1.0, fbits);
+    }
+    if (e > emax) {
+        *back = signbit(x) ? -INFINITY : INFINITY;
+        return (uint16_t)(sign | all_ones_exp);
+    }
+    const double v = count * unit;                  /* exact */
+    *back = (float)(signbit(x) ? -v : v);           /* exact: every such value is a float */
+    const unsigned n = (unsigned)count;
+    if (n < (1u << fbits))                          /* subnormal (or zero): exponent field 0 */
+        return (uint16_t)(sign | n);
+    return (uint16_t)(sign | ((unsigned)(e + bias) << fbits) | (n - (1u << fbits)));
+}
+
+/* x: [count] float -> code: [count] the 16-bit patterns, back: [count] the
+ * stored values read back as float (either output may be NULL). */
+void oracle_store_f16(const float *x, int64_t count, uint16_t *code, float *back)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        float b;
+        const uint16_t c = store_16bit(x[i], 5, 10, &b);
+        if (code) code[i] = c;
+        if (back) back[i] = b;
+    }
+}
+
+void oracle_store_bf16(const float *x, int64_t count, uint16_t *code, float *back)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        float b;
+        const uint16_t c = store_16bit(x[i], 8, 7, &b);
+        if (code) code[i] = c;
+        if (back) back[i] = b;
+    }
+}
+
+/* The value of a bfloat16 pattern: sign, exponent field E, fraction F give
+ * (-1)^s * 2^(E-127) * (1 + F/128), E = 0: (-1)^s * 2^-126 * F/128,
+ * E = 255: infinity (F = 0) or NaN. */
+void oracle_load_bf16(const uint16_t *code, int64_t count, float *value)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        const int s = code[i] >> 15, E = (code[i] >> 7) & 0xFF, F = code[i] & 0x7F;
+        double v;
+        if (E == 255)
+            v = F ? (double)NAN : (double)INFINITY;
+        else if (E == 0)
+            v = ldexp((double)F / 128.0, -126);
+        else
+            v = ldexp(1.0 + (double)F / 128.0, E - 127);
+        value[i] = (float)(s ? -v : v);
+    }
+}

@@ -62,6 +62,12 @@ def _load():
     lib.oracle_module_epilogue.restype = None
     lib.oracle_module_tail.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp]
     lib.oracle_module_tail.restype = None
+    lib.oracle_store_f16.argtypes = [vp, i64, vp, vp]
+    lib.oracle_store_f16.restype = None
+    lib.oracle_store_bf16.argtypes = [vp, i64, vp, vp]
+    lib.oracle_store_bf16.restype = None
+    lib.oracle_load_bf16.argtypes = [vp, i64, vp]
+    lib.oracle_load_bf16.restype = None
     lib.oracle_avgpool_nhwc.argtypes = [vp] + [i32] * 5 + [vp, vp]
     lib.oracle_avgpool_nhwc.restype = i32
     _lib = lib
@@ -321,3 +327,29 @@ def avgpool_nhwc(a, s):
     if rc != 0:
         raise ValueError("oracle_avgpool_nhwc failed: %d" % rc)
     return p64, p32
+
+
+def store_f16(x):
+    """float32 array -> the values as a binary16 stream stores them (numpy
+    float16 array of the same shape; the oracle produces the bit patterns)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    code = np.empty(x.shape, dtype=np.uint16)
+    _load().oracle_store_f16(_ptr(x), x.size, _ptr(code), None)
+    return code.view(np.float16)
+
+
+def store_bf16(x):
+    """float32 array -> (uint16 bfloat16 patterns, the stored values as float32)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    code = np.empty(x.shape, dtype=np.uint16)
+    back = np.empty(x.shape, dtype=np.float32)
+    _load().oracle_store_bf16(_ptr(x), x.size, _ptr(code), _ptr(back))
+    return code, back
+
+
+def load_bf16(code):
+    """uint16 bfloat16 patterns -> float32 values."""
+    code = np.ascontiguousarray(code, dtype=np.uint16)
+    out = np.empty(code.shape, dtype=np.float32)
+    _load().oracle_load_bf16(_ptr(code), code.size, _ptr(out))
+    return out

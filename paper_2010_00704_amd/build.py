@@ -65,5 +65,47 @@ def build_library(verbose=False):
     return LIB_PATH
 
 
+def resource_usage(jobs=None):
+    """Device-only compile of every source with the compiler's per-kernel
+    resource remarks switched on.  Returns {kernel symbol: {"scratch": bytes
+    per lane, "vgpr_spills": n, "sgpr_spills": n, "vgprs": n, "agprs": n,
+    "occupancy": waves per SIMD}}; nothing is linked or written."""
+    import re
+    import shutil
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
+    srcs = sources()
+    tmpdir = tempfile.mkdtemp(prefix="bcnn_usage_")
+    common = [f for f in FLAGS if f not in ("-shared", "-fPIC")] + [
+        "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+        "-I", os.path.join(_ROOT, "include"), "-I", os.path.join(_HERE, "csrc")]
+    fields = {"ScratchSize [bytes/lane]": "scratch", "VGPRs Spill": "vgpr_spills", "SGPRs Spill": "sgpr_spills",
+              "VGPRs": "vgprs", "AGPRs": "agprs", "Occupancy [waves/SIMD]": "occupancy"}
+    out = {}
+    try:
+        jobs = jobs or min(len(srcs), max(1, min(8, os.cpu_count() or 1)))
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            results = list(pool.map(
+                lambda src: _run([HIPCC] + common + ["-c", src, "-o", os.path.join(tmpdir, os.path.basename(src) + ".o")]),
+                srcs))
+        for src, (rc, log) in zip(srcs, results):
+            if rc != 0:
+                raise RuntimeError("hipcc failed on %s:\n%s" % (os.path.basename(src), log))
+            cur = None
+            for line in log.splitlines():
+                m = re.search(r"remark:\s+(.*?):\s+(\S+) \[-Rpass-analysis", line)
+                if not m:
+                    continue
+                key, val = m.group(1).strip(), m.group(2)
+                if key == "Function Name":
+                    cur = out.setdefault(val, {"source": os.path.basename(src)})
+                elif cur is not None and key in fields:
+                    cur[fields[key]] = int(val)
+    finally:
+        shutil.rmtree(tmpdir, ignore_errors=True)
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))

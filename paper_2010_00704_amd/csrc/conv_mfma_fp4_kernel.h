@@ -773,7 +773,10 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         for (int pb = 0; pb < PB; ++pb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[cb][pb][r] = 0.0f;
-            if constexpr (PB >= 7) asm volatile("" : "+a"(acc[cb][pb]));     // the wide tile keeps them in acc registers
+            // (branch mode holds a second accumulator set; pinning this one to a register class there
+            // leaves the allocator no room and it spills, so the compiler places those zeros itself)
+            if constexpr (BRANCH) continue;
+            else if constexpr (PB >= 7) asm volatile("" : "+a"(acc[cb][pb]));     // the wide tile keeps them in acc registers
             else asm volatile("" : "+v"(acc[cb][pb]));
         }
     __builtin_amdgcn_sched_barrier(0);

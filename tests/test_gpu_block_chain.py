@@ -44,7 +44,7 @@ def oracle_module_rows(sign_rows, n, h, w, wt, g, b, identity_rows, alpha, next_
     y = oracle.conv2d_pm1(x, wt, 1, 0)                                   # [n, h, w, o]
     o = wt.shape[0]
     _, r32 = oracle.module_epilogue(y, g, b, identity_rows.astype(np.float32).reshape(n, h, w, o), alpha)
-    stored = r32.astype(np.float16).reshape(m, o)
+    stored = oracle.store_f16(r32).reshape(m, o)
     bits, signs = bits_of_rows(stored, next_bias)
     return stored, bits, signs
 
@@ -65,7 +65,7 @@ def test_block_chain(dev, shape):
     seed = 30000 + 17 * c + h
     m = n * h * w
     par = lambda k, shp, lo, hi: W.uniform_f32(seed + k, shp, lo, hi)      # noqa: E731
-    a0 = par(0, (m, c), -30.0, 30.0).astype(np.float16)
+    a0 = oracle.store_f16(par(0, (m, c), -30.0, 30.0))
     b0, b1, b2 = par(1, (c,), -5.0, 5.0), par(2, (c,), -5.0, 5.0), par(3, (c,), -5.0, 5.0)
     w1, w2 = W.pm1(seed + 4, (c, c, 1, 1)), W.pm1(seed + 5, (c, c, 1, 1))
     g1, g2 = par(6, (c,), -0.2, 0.2), par(7, (c,), -0.2, 0.2)
@@ -83,7 +83,7 @@ def test_block_chain(dev, shape):
     _, p32 = oracle.avgpool_nhwc(want_a2.astype(np.float32).reshape(n, h, w, c), 2)
     ho, wo = h // 2, w // 2
     mp = n * ho * wo
-    want_p = p32.astype(np.float16).reshape(mp, c)
+    want_p = oracle.store_f16(p32).reshape(mp, c)
     want_xp, _ = bits_of_rows(want_p, bp)
     p_rep = oracle.replicate_channels(want_p, rep, axis=1)
     want_xr, sr = bits_of_rows(p_rep, br)

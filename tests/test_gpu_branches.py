@@ -8,6 +8,8 @@ compared for equality (and, as a sanity check, against the oracle's double
 result within the chain's rounding bound); the fused bits and the packed words
 are compared bit for bit.
 """
+import functools
+
 import numpy as np
 import pytest
 import torch
@@ -56,7 +58,7 @@ def test_pack_bias(dev, outer, channels, inner, dtype):
         x = W.real_with_sign(seed, signs)
         bias = W.uniform_f32(seed + 2, (channels,), -1.5, 1.5)
         if dtype == "f16":
-            x = x.astype(np.float16)
+            x = oracle.store_f16(x)
             xt, code = torch.from_numpy(x), B.BCNN_F16
         else:
             xt, code = torch.from_numpy(x), B.BCNN_F32
@@ -89,7 +91,7 @@ def test_pack_bias_replicated(dev, outer, src_channels, inner, rep, dtype):
     seed = 7500 + outer * 131 + src_channels * 7 + inner + rep
     x = W.real_with_sign(seed, W.pm1(seed, (outer, src_channels, inner)))
     if dtype == "f16":
-        x = x.astype(np.float16)
+        x = oracle.store_f16(x)
     channels = src_channels * rep
     bias = W.uniform_f32(seed + 2, (channels,), -1.5, 1.5)
     x32 = x.astype(np.float32)
@@ -144,11 +146,11 @@ def gpu_branches(dev, xb, wt, padv_words, mode, g, hb, stride, pad, fused, varia
         cwo = (o + 31) // 32
         out = Guarded(n * ho * wo * cwo, dev)
         run_variant(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr,
-                                                            variant), "branches_sign_pack")
+                                                            variant), "branches_sign_pack", variant)
         return out.get(np.uint32).reshape(n, ho * wo, cwo)
     out = Guarded(n * ho * wo * o, dev)
     run_variant(B.bcnn_conv2d_binary_branches(desc, p, xp, stride_words, wp, pw, mode, gt, ht, out.ptr, variant),
-                "branches")
+                "branches", variant)
     return out.get(np.float32).reshape(n, ho, wo, o)
 
 
@@ -267,20 +269,35 @@ def test_branch_argument_checks(dev):
 
 
 # ------------------------------------------------------------ full-size shapes
-@pytest.mark.parametrize("index", [3, 4])
-@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
-def test_branches_full_size(dev, index, variant):
-    """The launch is the full benchmark shape (3x3, 256 channels, whole batch,
-    one tensor shared by the branches, per-branch pad words); the oracle
-    evaluates the first, middle and last image."""
+def _branch_params(index):
     cfg = W.CONFIGS[index - 1]
-    picks = [0, cfg.n // 2, cfg.n - 1]
-    _, x_all, ws, _ = W.make_inputs(index)
-    wt = ws[0]
     p = cfg.k * cfg.k
     padv = W.pm1(9200 + index, (p, cfg.c_in))
     g = W.uniform_f32(9300 + index, (p, cfg.c_out), -1.5, 1.5)
     hb = W.uniform_f32(9400 + index, (cfg.c_out,), -40.0, 40.0)
+    return padv, g, hb
+
+
+@functools.lru_cache(maxsize=None)
+def _full_size_branch_oracle(index):
+    """The oracle's float chain on the whole batch, once per session for all variants."""
+    cfg, x_all, ws, _ = W.make_inputs(index)
+    padv, g, hb = _branch_params(index)
+    _, z32 = oracle.branches_pm1(x_all[None], padv, ws[0], g, hb, cfg.stride, cfg.pad)
+    return z32, oracle_bits(z32)
+
+
+@pytest.mark.parametrize("index", [3, 4, 5])
+@pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
+def test_branches_full_size(dev, index, variant):
+    """The launch is the full benchmark shape (3x3, whole batch, one tensor
+    shared by the branches, per-branch pad words); the oracle evaluates every
+    image and the whole output is compared (shape 5: its first layer)."""
+    cfg, x_all, ws, _ = W.make_inputs(index)
+    wt = ws[0]
+    p = cfg.k * cfg.k
+    padv, g, hb = _branch_params(index)
+    z32, want_bits = _full_size_branch_oracle(index)
     desc = B.conv_desc(cfg.n, cfg.c_in, cfg.h, cfg.w, cfg.c_out, cfg.k, cfg.stride, cfg.pad)
     ho, wo = B.out_shape(desc)
     xp = B.pack_nchw(up(x_all, dev))
@@ -290,15 +307,12 @@ def test_branches_full_size(dev, index, variant):
     z = torch.empty((cfg.n, ho, wo, cfg.c_out), dtype=torch.float32, device=dev)
     zp = torch.empty((cfg.n, ho * wo, cfg.c_out // 32), dtype=torch.int32, device=dev)
     run_variant(B.bcnn_conv2d_binary_branches(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, z, variant),
-                "branches")
+                "branches", variant)
     run_variant(B.bcnn_conv2d_binary_branches_sign_pack(desc, p, xp, 0, wp, pw, B.BCNN_PAD_WORDS, gt, ht, zp,
-                                                        variant), "fused")
+                                                        variant), "fused", variant)
     torch.cuda.synchronize()
-    _, z32 = oracle.branches_pm1(x_all[picks][None], padv, wt, g, hb, cfg.stride, cfg.pad)
-    got = z[picks].cpu().numpy()
-    assert np.array_equal(got, z32)
-    bits = zp[picks].cpu().numpy().view(np.uint32)
-    assert np.array_equal(bits, oracle_bits(z32))
+    assert np.array_equal(z.cpu().numpy(), z32)
+    assert np.array_equal(zp.cpu().numpy().view(np.uint32), want_bits)
 
 
 # ------------------------------------------------------------ branches inside a module
@@ -345,7 +359,7 @@ def test_branches_module_matches_oracle(dev, shape, variant, half, mode):
             alpha = W.uniform_f32(seed + 6, (o,), 0.05, 0.5)
             cn = W.uniform_f32(seed + 7, (o,), -10.0, 10.0)
         if half:
-            ident = ident.astype(np.float16)
+            ident = oracle.store_f16(ident)
         if mode == "minus":
             padv_o, words, code = -np.ones((p, c), dtype=np.int8), None, B.BCNN_PAD_WORDS
         elif mode == "words":
@@ -354,7 +368,7 @@ def test_branches_module_matches_oracle(dev, shape, variant, half, mode):
             padv_o, words, code = np.zeros((p, c), dtype=np.int8), None, B.BCNN_PAD_ZERO
         z64, z32 = oracle.branches_pm1(xb, padv_o, wt, g, hb, stride, pad)
         _, r32 = oracle.module_tail(z64, z32, ident.astype(np.float32).reshape(z32.shape), alpha)
-        stored = r32.astype(np.float16) if half else r32
+        stored = oracle.store_f16(r32) if half else r32
         sgn = oracle.sign_bias_f32(stored.astype(np.float32).reshape(m, o, 1), cn)
         want_bits = oracle.pack_channels(sgn.reshape(n, ho * wo, o).transpose(0, 2, 1))
 
@@ -372,7 +386,7 @@ def test_branches_module_matches_oracle(dev, shape, variant, half, mode):
             desc, p, xp, n * h * w * cw, wp, up(i32(words), dev) if words is not None else None, code, up(g, dev),
             up(hb, dev), rbuf.ptr, up(alpha, dev), up(cn, dev), B.BCNN_F16 if half else B.BCNN_F32, rbuf.ptr,
             bits.ptr, variant)
-        run_variant(rc, "branches_module")
+        run_variant(rc, "branches_module", variant)
         got_r = rbuf.get(np.uint8)[:m * o * esz].view(np.float16 if half else np.float32).reshape(m, o)
         assert np.array_equal(got_r, stored.reshape(m, o))
         assert np.array_equal(bits.get(np.uint32).reshape(n, ho * wo, cwo), want_bits)

@@ -22,7 +22,7 @@ def dev():
 def expected(src, s, bias, half):
     """Oracle side: the float chain, the value as stored, bias + sign, packed."""
     _, p32 = oracle.avgpool_nhwc(src.astype(np.float32), s)
-    stored = p32.astype(np.float16) if half else p32
+    stored = oracle.store_f16(p32) if half else p32
     n, ho, wo, c = stored.shape
     b = np.zeros(c, dtype=np.float32) if bias is None else bias
     sgn = oracle.sign_bias_f32(stored.astype(np.float32).reshape(n * ho * wo, c, 1), b)
@@ -33,7 +33,7 @@ def source(seed, shape, half):
     # a few magnitudes so that additions round, and exact zeros so that the tie of the sign shows up
     a = W.uniform_f32(seed, shape, -40.0, 40.0, steps=320)
     a = a * np.where(W.uniform_f32(seed + 1, shape, 0.0, 1.0) < 0.2, np.float32(1e-3), np.float32(1.0))
-    return a.astype(np.float16) if half else a.astype(np.float32)
+    return oracle.store_f16(a) if half else a.astype(np.float32)
 
 
 def run(dev, src, s, bias, half, want_pooled=True, want_bits=True, misalign=0):

@@ -12,7 +12,8 @@ import pytest
 import oracle
 from paper_2010_00704_amd import binding as B
 from paper_2010_00704_amd import workloads as W
-from gpu_helpers import Guarded, gpu_device, i32, oracle_bits_of_sign, oracle_pack_nchw, oracle_pack_vectors, up
+from gpu_helpers import (COVER_ALL, Guarded, gpu_device, i32, oracle_bits_of_sign, oracle_pack_nchw,
+                         oracle_pack_vectors, up)
 
 pytestmark = pytest.mark.gpu
 
@@ -64,13 +65,13 @@ def test_random_plain_and_fused(dev, seed, mfma_friendly):
     for v in variants:
         out = Guarded(y.size, dev)
         rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, None, out.ptr, v)
-        if rc != B.BCNN_ERR_UNSUPPORTED:
+        if rc != B.BCNN_ERR_UNSUPPORTED or v in COVER_ALL:
             B.check(rc, "conv")
             assert np.array_equal(out.get(np.int32).reshape(y.shape), y), "variant %d sums" % v
             ran += 1
         bits = Guarded(want_bits.size, dev)
         rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, up(thr, dev), bits.ptr, v)
-        if rc != B.BCNN_ERR_UNSUPPORTED:
+        if rc != B.BCNN_ERR_UNSUPPORTED or v in COVER_ALL:
             B.check(rc, "fused")
             assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits), "variant %d bits" % v
             ran += 1
@@ -94,10 +95,10 @@ def test_random_module(dev, seed, mfma_friendly, half):
     alpha = W.uniform_f32(13600 + seed, (o,), 0.0, 0.5)
     cn = W.uniform_f32(13700 + seed, (o,), -5.0, 5.0)
     if half:
-        ident = ident.astype(np.float16)
+        ident = oracle.store_f16(ident)
     ident_full = oracle.replicate_channels(ident.astype(np.float32), -(-o // idc), axis=1)[:, :o]
     _, r32 = oracle.module_epilogue(y, g, b, ident_full.reshape(y.shape), alpha)
-    stored = (r32.astype(np.float16) if half else r32).reshape(m, o)
+    stored = (oracle.store_f16(r32) if half else r32).reshape(m, o)
     sgn = oracle.sign_bias_f32(stored.astype(np.float32).reshape(m, o, 1), cn)
     want_bits = oracle_bits_of_sign(sgn.reshape(n, ho, wo, o))
     desc = B.conv_desc(n, c, h, w, o, k, stride, pad)
@@ -109,7 +110,7 @@ def test_random_module(dev, seed, mfma_friendly, half):
         rc = B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), up(ident, dev), up(alpha, dev),
                                          up(cn, dev), B.BCNN_F16 if half else B.BCNN_F32, rbuf.ptr, bits.ptr, v,
                                          identity_channels=idc)
-        if rc == B.BCNN_ERR_UNSUPPORTED:
+        if rc == B.BCNN_ERR_UNSUPPORTED and v not in COVER_ALL:
             continue
         B.check(rc, "module")
         assert np.array_equal(rbuf.get(np.float16 if half else np.float32, m * o).reshape(m, o), stored)
@@ -161,7 +162,7 @@ def test_random_branches(dev, seed):
     for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4):
         out = Guarded(z32.size, dev)
         rc = B.bcnn_conv2d_binary_branches(desc, p, xp, xs, wp, pw, code, up(g, dev), up(hb, dev), out.ptr, v)
-        if rc == B.BCNN_ERR_UNSUPPORTED:
+        if rc == B.BCNN_ERR_UNSUPPORTED and v not in COVER_ALL:
             continue
         B.check(rc, "branches")
         assert np.array_equal(out.get(np.float32).reshape(z32.shape), z32)
@@ -210,12 +211,12 @@ def test_tiny_problems_on_every_path(dev, shape):
               B.BCNN_VARIANT_MFMA_I8):
         out = Guarded(y.size, dev)
         rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, None, out.ptr, v)
-        if rc != B.BCNN_ERR_UNSUPPORTED:
+        if rc != B.BCNN_ERR_UNSUPPORTED or v in COVER_ALL:
             B.check(rc, "conv")
             assert np.array_equal(out.get(np.int32).reshape(y.shape), y), "variant %d sums" % v
         bits = Guarded(want_bits.size, dev)
         rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, up(thr, dev), bits.ptr, v)
-        if rc != B.BCNN_ERR_UNSUPPORTED:
+        if rc != B.BCNN_ERR_UNSUPPORTED or v in COVER_ALL:
             B.check(rc, "fused")
             assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits), "variant %d bits" % v
     # the module call on the same tiny problem (AUTO stays on the vector ALUs here, the matrix cores are forced)
@@ -233,7 +234,7 @@ def test_tiny_problems_on_every_path(dev, shape):
         nb = Guarded(mod_bits.size, dev)
         rc = B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), up(ident, dev), up(alpha, dev),
                                          up(cn, dev), B.BCNN_F32, rbuf.ptr, nb.ptr, v)
-        if rc == B.BCNN_ERR_UNSUPPORTED:
+        if rc == B.BCNN_ERR_UNSUPPORTED and v not in COVER_ALL:
             continue
         B.check(rc, "module")
         assert np.array_equal(rbuf.get(np.float32, m * o).reshape(m, o), r32.reshape(m, o)), "variant %d stream" % v
@@ -270,7 +271,7 @@ def test_tiny_branch_problems_on_every_path(dev, shape, mode):
     for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4):
         out = Guarded(z32.size, dev)
         rc = B.bcnn_conv2d_binary_branches(desc, p, xp, n * h * w * cw, wp, pw, code, up(g, dev), up(hb, dev), out.ptr, v)
-        if rc == B.BCNN_ERR_UNSUPPORTED:
+        if rc == B.BCNN_ERR_UNSUPPORTED and v not in COVER_ALL:
             continue
         B.check(rc, "branches")
         assert np.array_equal(out.get(np.float32).reshape(z32.shape), z32), "variant %d" % v
