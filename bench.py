@@ -228,10 +228,11 @@ def main():
             "bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_FP4_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
             "avg_launch_ms": round(dom_ms, 4),
-            # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised in
-            # profiles/bench_hbm_traffic_pmc.md (shape 5, 2x7 tile); not re-measured by this script
-            "traffic": 13.2e6 if dom["cfg"].name.startswith("cfg5") else None,
         }
+        # HBM bytes per launch: not measurable from inside this script; taken from the table that
+        # `python -m paper_2010_00704_amd.rocprof_summary pmc ...` wrote from the FETCH_SIZE / WRITE_SIZE
+        # counter runs of this same command (null if that summary is not there)
+        roofline.update(traffic_from_profile(dom["cfg"]))
     elif args.variant == "mfma_i8":
         roofline = {
             "kernel": "conv_mfma_i8_kernel on " + dom["cfg"].name + " (per launch)",
@@ -276,6 +277,30 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def traffic_from_profile(cfg):
+    """{"traffic": HBM bytes per launch of the convolution of `cfg`, "traffic_source": file and run,
+    "traffic_over_algorithmic": ratio to the compulsory bytes (packed input + packed weights + thresholds
+    + packed output)} from profiles/bench_hbm_traffic_pmc.md, or traffic = None."""
+    path = os.path.join(ROOT, "profiles", "bench_hbm_traffic_pmc.md")
+    out = {"traffic": None}
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == cfg.name:
+                    cw, cwo = (cfg.c_in + 31) // 32, (cfg.c_out + 31) // 32
+                    ho = (cfg.h + 2 * cfg.pad - cfg.k) // cfg.stride + 1
+                    wo = (cfg.w + 2 * cfg.pad - cfg.k) // cfg.stride + 1
+                    # a layer of the chain reads the previous layer's output: same size as the input here
+                    algorithmic = 4 * (cfg.n * cfg.h * cfg.w * cw + cfg.c_out * cfg.k * cfg.k * cw + cfg.c_out +
+                                       cfg.n * ho * wo * (cwo if cfg.fused else cfg.c_out))
+                    out = {"traffic": float(parts[2]), "traffic_source": "profiles/bench_hbm_traffic_pmc.md",
+                           "traffic_over_algorithmic": round(float(parts[2]) / algorithmic, 2)}
+    except OSError:
+        pass
+    return out
 
 
 def _gpu_sensors():
@@ -432,8 +457,8 @@ def aux_measurements(torch, B, dev, work, sustained=True):
     # operands, once on all-zero words (constant operands), and the matrix-core probe.  The
     # constant-operand launch shows the kernel's time at the full clock; the difference to the
     # random-operand launch is what the board's power limit costs.
-    if sustained:
-        out["sustained"] = sustained_load(torch, B, dev, work)
+    # (measured last, below: it holds the chip at its power limit for seconds, which would bias
+    # whatever is timed right after it)
 
     # pack kernel on the largest input (shape 4, 205 MB fp32), 4 rotating copies
     wk = work[3]
@@ -466,7 +491,19 @@ def aux_measurements(torch, B, dev, work, sustained=True):
     B.check(B.bcnn_diag_copy_u32(ys[0], dst, ys[0].numel()), "copy")
     ms = eager_ms(lambda r: B.check(B.bcnn_diag_copy_u32(ys[r % 4], dst, ys[0].numel()), "copy"), reps)
     out["copy_gbs_read_plus_write"] = round(2 * ys[0].numel() * 4 / (ms * 1e-3) / 1e9, 1)
-    del ys, dst
+    # one-sided ceilings on the same 102.8 MB: a pure store (what bounds the int32 convolution of shape 2)
+    # and a pure read (what bounds pack and the stand-alone epilogue), 16-byte non-temporal accesses
+    dsts = [dst] + [torch.empty_like(dst) for _ in range(3)]
+    words = dst.numel()
+    for d4 in dsts:
+        B.check(B.bcnn_diag_store_u32(d4, words), "store")
+    ms = eager_ms(lambda r: B.check(B.bcnn_diag_store_u32(dsts[r % 4], words), "store"), reps)
+    out["store_only_gbs"] = round(words * 4 / (ms * 1e-3) / 1e9, 1)
+    rsink = torch.empty(((words // 4 + 2047) // 2048) * 256, dtype=torch.int32, device=dev)
+    B.check(B.bcnn_diag_read_u32(ys[0], words, rsink), "read")
+    ms = eager_ms(lambda r: B.check(B.bcnn_diag_read_u32(ys[r % 4], words, rsink), "read"), reps)
+    out["read_only_gbs"] = round(words * 4 / (ms * 1e-3) / 1e9, 1)
+    del ys, dst, dsts, rsink
 
     # pack with a per-channel bias before the sign, same input as the pack figure above
     from paper_2010_00704_amd import workloads as W
@@ -480,7 +517,8 @@ def aux_measurements(torch, B, dev, work, sustained=True):
     del srcs
 
     # branch convolution (F*F shifted 1x1 branches, per-branch real scales, per-branch pad words,
-    # fused sign-pack) on the 3x3 shapes; runs on the vector ALUs, so the bound is the xor+popcount peak
+    # fused sign-pack) on the 3x3 shapes.  These shapes run on the matrix cores (C_in a multiple of 256);
+    # the fraction quoted is against the xor+popcount peak of the vector ALUs, the arm every shape can use
     out["branches"] = []
     for wk in work[2:5]:
         cfg = wk["cfg"]
@@ -571,6 +609,8 @@ def aux_measurements(torch, B, dev, work, sustained=True):
             "real": name, "shape": list(shape), "ms": round(ms, 4), "gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
             "frac_hbm": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
         del maps
+    if sustained:
+        out["sustained"] = sustained_load(torch, B, dev, work)
     return out
 
 

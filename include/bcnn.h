@@ -84,7 +84,7 @@ typedef struct {
  * unknown dtype or more than 2^31-1 output words, ALIGNMENT if dst is not
  * 4-byte aligned or src not aligned to its element size.
  */
-int bcnn_pack(const void *src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+int bcnn_pack(const void *src, bcnn_dtype dtype, int64_t outer, int64_t channels, int64_t inner,
               uint32_t *dst, void *hip_stream);
 
 /*
@@ -95,7 +95,7 @@ int bcnn_pack(const void *src, int dtype, int64_t outer, int64_t channels, int64
  *   bias : device, float32 [channels].  NULL is INVALID_ARG.
  * Everything else as bcnn_pack.
  */
-int bcnn_pack_bias(const void *src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+int bcnn_pack_bias(const void *src, bcnn_dtype dtype, int64_t outer, int64_t channels, int64_t inner,
                    const float *bias, uint32_t *dst, void *hip_stream);
 
 /*
@@ -109,7 +109,7 @@ int bcnn_pack_bias(const void *src, int dtype, int64_t outer, int64_t channels, 
  *   dst  : device, [outer][inner][ceil(replication * src_channels / 32)]
  * replication = 1 is bcnn_pack_bias.
  */
-int bcnn_pack_bias_replicated(const void *src, int dtype, int64_t outer, int64_t src_channels,
+int bcnn_pack_bias_replicated(const void *src, bcnn_dtype dtype, int64_t outer, int64_t src_channels,
                               int64_t inner, int32_t replication, const float *bias, uint32_t *dst,
                               void *hip_stream);
 
@@ -135,7 +135,7 @@ int bcnn_pack_bias_replicated(const void *src, int dtype, int64_t outer, int64_t
  * not aligned to their element size.  Rows of 4-element-aligned tensors with
  * channels a multiple of 4 take the fast path.
  */
-int bcnn_avgpool_bias_sign_pack(const void *src, int real_dtype, int32_t n, int32_t h, int32_t w,
+int bcnn_avgpool_bias_sign_pack(const void *src, bcnn_dtype real_dtype, int32_t n, int32_t h, int32_t w,
                                 int32_t channels, int32_t s, const float *bias, void *pooled,
                                 uint32_t *x_packed, void *hip_stream);
 
@@ -301,23 +301,6 @@ int bcnn_out_dim(int32_t in, int32_t k, int32_t stride, int32_t pad);
 
 /* Static, NUL-terminated description of a bcnn_status value. Host only. */
 const char *bcnn_status_string(int status);
-
-/*
- * Measurement helpers (not part of the method).
- * bcnn_diag_copy_u32: dst[i] = src[i] for `words` 32-bit words; the known-size
- *   kernel that memory-traffic counters are calibrated against.
- * bcnn_diag_valu_peak: every lane runs `iters` rounds of 64 independent
- *   xor + popcount-accumulate pairs on registers and writes one word to
- *   sink[global thread id]; sink holds blocks*256 words.  Times the vector
- *   ALUs' xor/popcount issue rate with no memory traffic.
- * bcnn_diag_mfma_fp4_peak: every wave issues `iters` rounds of 8 independent
- *   32x32x64 fp4 matrix instructions on random +-1 operands held in registers
- *   and writes one float to sink[global thread id] (blocks*256 floats).  Times
- *   the rate the matrix cores sustain on this kind of data.
- */
-int bcnn_diag_copy_u32(const uint32_t *src, uint32_t *dst, int64_t words, void *hip_stream);
-int bcnn_diag_valu_peak(uint32_t *sink, int32_t blocks, int32_t iters, void *hip_stream);
-int bcnn_diag_mfma_fp4_peak(float *sink, int32_t blocks, int32_t iters, void *hip_stream);
 
 #ifdef __cplusplus
 }

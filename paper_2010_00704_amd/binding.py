@@ -30,6 +30,7 @@ EXPORTS = (
     "bcnn_pack_bias", "bcnn_conv2d_binary_branches", "bcnn_conv2d_binary_branches_sign_pack",
     "bcnn_conv2d_binary_module", "bcnn_pack_bias_replicated", "bcnn_diag_mfma_fp4_peak",
     "bcnn_conv2d_binary_branches_module", "bcnn_avgpool_bias_sign_pack",
+    "bcnn_diag_store_u32", "bcnn_diag_read_u32",
 )
 
 
@@ -73,6 +74,8 @@ def lib():
         L.bcnn_status_string.argtypes = [ctypes.c_int]
         L.bcnn_status_string.restype = ctypes.c_char_p
         L.bcnn_diag_copy_u32.argtypes = [vp, vp, i64, vp]
+        L.bcnn_diag_store_u32.argtypes = [vp, i64, i32, vp]
+        L.bcnn_diag_read_u32.argtypes = [vp, i64, vp, i32, vp]
         L.bcnn_diag_valu_peak.argtypes = [vp, i32, i32, vp]
         L.bcnn_diag_mfma_fp4_peak.argtypes = [vp, i32, i32, vp]
         L.bcnn_pack_bias.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp]
@@ -204,6 +207,14 @@ def bcnn_threshold_sign_pack(y, thr, rows, c_out, y_packed, stream=None):
 
 def bcnn_diag_copy_u32(src, dst, words, stream=None):
     return lib().bcnn_diag_copy_u32(_ptr(src), _ptr(dst), words, _stream(stream))
+
+
+def bcnn_diag_store_u32(dst, words, blocks=0, stream=None):
+    return lib().bcnn_diag_store_u32(_ptr(dst), words, blocks, _stream(stream))
+
+
+def bcnn_diag_read_u32(src, words, sink, blocks=0, stream=None):
+    return lib().bcnn_diag_read_u32(_ptr(src), words, _ptr(sink), blocks, _stream(stream))
 
 
 def bcnn_diag_valu_peak(sink, blocks, iters, stream=None):

@@ -9,65 +9,6 @@
 namespace bcnn {
 namespace {
 
-// Issue-rate probe: 64 independent accumulators per lane, each fed by one
-// v_xor_b32 (scalar operand x vector operand, as in the convolution) and one
-// v_bcnt_u32_b32 per round; operands live in registers only.  8 vector words
-// times 8 scalar words give the 64 distinct pairs; the scalar words change
-// every round so no xor can be hoisted out of the loop.
-__global__ __launch_bounds__(256) void diag_valu_peak_kernel(uint32_t* __restrict__ sink, int iters)
-{
-    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
-    uint32_t acc[64];
-#pragma unroll
-    for (int a = 0; a < 64; ++a) acc[a] = 0;
-    uint32_t xv[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) xv[j] = (gid + j) * 2654435761u + 12345u;
-    uint32_t sv[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) sv[j] = __builtin_amdgcn_readfirstlane(0x9E3779B9u * (j + 1));
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) sv[j] = sv[j] * 5u + 1u;
-#pragma unroll
-        for (int a = 0; a < 64; ++a)
-            acc[a] += __builtin_popcount(xv[a & 7] ^ sv[a >> 3]);
-    }
-    uint32_t r = 0;
-#pragma unroll
-    for (int a = 0; a < 64; ++a) r ^= acc[a];
-    sink[gid] = r;
-}
-
-// Matrix-core issue-rate probe: every wave keeps 8 independent accumulators of
-// v_mfma_f32_32x32x64_f8f6f4 busy with fp4 operands that are random +-1 (the
-// codes 0x2 / 0xA, as in the convolution), held in registers; no memory traffic.
-typedef int diag_v8i __attribute__((ext_vector_type(8)));
-typedef float diag_v16f __attribute__((ext_vector_type(16)));
-__global__ __launch_bounds__(256) void diag_mfma_fp4_peak_kernel(float* __restrict__ sink, int iters)
-{
-    uint32_t seed = (blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
-    diag_v8i a[2], b[4];
-    for (int q = 0; q < 6; ++q)
-        for (int j = 0; j < 8; ++j) {
-            seed = seed * 1664525u + 1013904223u;
-            const int v = j < 4 ? (int)((seed & 0x88888888u) | 0x22222222u) : 0;
-            if (q < 2) a[q][j] = v; else b[q - 2][j] = v;
-        }
-    diag_v16f c[8];
-    for (int n = 0; n < 8; ++n)
-        for (int r = 0; r < 16; ++r) c[n][r] = 0.0f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int n = 0; n < 8; ++n)
-            c[n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[n & 1], b[n >> 1], c[n], 4, 4, 0, 0, 0, 0);
-    }
-    float s = 0.0f;
-    for (int n = 0; n < 8; ++n)
-        for (int r = 0; r < 16; ++r) s += c[n][r];
-    sink[blockIdx.x * 256 + threadIdx.x] = s;
-}
-
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 int out_dim(int in, int k, int stride, int pad)
@@ -186,20 +127,20 @@ static int pack_entry(const void* src, int dtype, int64_t outer, int64_t channel
     return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
 
-int bcnn_pack(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+int bcnn_pack(const void* src, bcnn_dtype dtype, int64_t outer, int64_t channels, int64_t inner,
               uint32_t* dst, void* hip_stream)
 {
     return pack_entry(src, dtype, outer, channels, channels, inner, nullptr, dst, hip_stream);
 }
 
-int bcnn_pack_bias(const void* src, int dtype, int64_t outer, int64_t channels, int64_t inner,
+int bcnn_pack_bias(const void* src, bcnn_dtype dtype, int64_t outer, int64_t channels, int64_t inner,
                    const float* bias, uint32_t* dst, void* hip_stream)
 {
     if (!bias) return BCNN_ERR_INVALID_ARG;
     return pack_entry(src, dtype, outer, channels, channels, inner, bias, dst, hip_stream);
 }
 
-int bcnn_pack_bias_replicated(const void* src, int dtype, int64_t outer, int64_t src_channels,
+int bcnn_pack_bias_replicated(const void* src, bcnn_dtype dtype, int64_t outer, int64_t src_channels,
                               int64_t inner, int32_t replication, const float* bias, uint32_t* dst,
                               void* hip_stream)
 {
@@ -209,7 +150,7 @@ int bcnn_pack_bias_replicated(const void* src, int dtype, int64_t outer, int64_t
                       hip_stream);
 }
 
-int bcnn_avgpool_bias_sign_pack(const void* src, int real_dtype, int32_t n, int32_t h, int32_t w,
+int bcnn_avgpool_bias_sign_pack(const void* src, bcnn_dtype real_dtype, int32_t n, int32_t h, int32_t w,
                                 int32_t channels, int32_t s, const float* bias, void* pooled,
                                 uint32_t* x_packed, void* hip_stream)
 {
@@ -415,32 +356,6 @@ int bcnn_threshold_sign_pack(const int32_t* y, const int32_t* thr, int64_t rows,
     const hipError_t e = bcnn::launch_threshold_sign_pack(y, thr, rows, c_out, y_packed,
                                                           static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
-}
-
-int bcnn_diag_copy_u32(const uint32_t* src, uint32_t* dst, int64_t words, void* hip_stream)
-{
-    if (!src || !dst || words < 1) return BCNN_ERR_INVALID_ARG;
-    if (!bcnn::aligned(src, 4) || !bcnn::aligned(dst, 4)) return BCNN_ERR_ALIGNMENT;
-    const hipError_t e = bcnn::launch_diag_copy(src, dst, words, static_cast<hipStream_t>(hip_stream));
-    return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
-}
-
-int bcnn_diag_valu_peak(uint32_t* sink, int32_t blocks, int32_t iters, void* hip_stream)
-{
-    if (!sink || blocks < 1 || iters < 1) return BCNN_ERR_INVALID_ARG;
-    if (!bcnn::aligned(sink, 4)) return BCNN_ERR_ALIGNMENT;
-    hipLaunchKernelGGL(bcnn::diag_valu_peak_kernel, dim3((unsigned)blocks), dim3(256), 0,
-                       static_cast<hipStream_t>(hip_stream), sink, iters);
-    return hipGetLastError() == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
-}
-
-int bcnn_diag_mfma_fp4_peak(float* sink, int32_t blocks, int32_t iters, void* hip_stream)
-{
-    if (!sink || blocks < 1 || iters < 1) return BCNN_ERR_INVALID_ARG;
-    if (!bcnn::aligned(sink, 4)) return BCNN_ERR_ALIGNMENT;
-    hipLaunchKernelGGL(bcnn::diag_mfma_fp4_peak_kernel, dim3((unsigned)blocks), dim3(256), 0,
-                       static_cast<hipStream_t>(hip_stream), sink, iters);
-    return hipGetLastError() == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
 
 }  // extern "C"

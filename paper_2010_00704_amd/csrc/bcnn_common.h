@@ -97,6 +97,5 @@ hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& a, hi
 // with bias + sign + pack of the pooled map; pooled or bits may be nullptr, bias too (zero)
 hipError_t launch_avgpool_pack(const void* src, bool half, int n, int h, int w, int c, int s, const float* bias,
                                void* pooled, uint32_t* bits, hipStream_t stream);
-hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream);
 
 }  // namespace bcnn

@@ -390,14 +390,6 @@ __global__ __launch_bounds__(256) void threshold_sign_pack4_kernel(
     }
 }
 
-__global__ __launch_bounds__(256) void diag_copy_kernel(const uint32_t* __restrict__ src,
-                                                       uint32_t* __restrict__ dst, int64_t words)
-{
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride)
-        dst[i] = src[i];
-}
-
 }  // namespace
 
 template <typename T>
@@ -449,15 +441,6 @@ hipError_t launch_threshold_sign_pack(const int32_t* y, const int32_t* thr, int6
     const int64_t blocks = (waves + 3) / 4;
     hipLaunchKernelGGL((threshold_sign_pack_kernel<ROWS>), dim3((unsigned)blocks), dim3(256), 0,
                        stream, y, thr, rows, c_out, (c_out + 31) / 32, y_packed);
-    return hipGetLastError();
-}
-
-hipError_t launch_diag_copy(const uint32_t* src, uint32_t* dst, int64_t words, hipStream_t stream)
-{
-    int64_t blocks = (words + 255) / 256;
-    if (blocks > 8192) blocks = 8192;
-    if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(diag_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, dst, words);
     return hipGetLastError();
 }
 

@@ -15,9 +15,12 @@ FAKE = 0x10000  # aligned, non-null, never dereferenced by the host checks
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "bcnn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(bcnn_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("bcnn.h", "bcnn_diag.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(bcnn_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_function():
@@ -88,6 +91,9 @@ def test_pack_and_threshold_reject_bad_arguments():
     assert L.bcnn_threshold_sign_pack(FAKE, FAKE + 64, 4, 32, FAKE + 1, None) == B.BCNN_ERR_ALIGNMENT
     assert L.bcnn_diag_copy_u32(None, FAKE, 4, None) == B.BCNN_ERR_INVALID_ARG
     assert L.bcnn_diag_valu_peak(None, 1, 1, None) == B.BCNN_ERR_INVALID_ARG
+    assert L.bcnn_diag_store_u32(FAKE, 6, 0, None) == B.BCNN_ERR_INVALID_ARG
+    assert L.bcnn_diag_store_u32(FAKE + 4, 8, 0, None) == B.BCNN_ERR_ALIGNMENT
+    assert L.bcnn_diag_read_u32(FAKE, 8, None, 0, None) == B.BCNN_ERR_INVALID_ARG
 
 
 # ---- the seeded input generator (shared by the oracle side and the GPU side) ----
