@@ -52,7 +52,8 @@ typedef enum {
     BCNN_ERR_DEVICE = -4       /* the HIP runtime refused the launch */
 } bcnn_status;
 
-typedef enum { BCNN_F32 = 0, BCNN_F16 = 1, BCNN_I8 = 2 } bcnn_dtype;
+/* BCNN_BF16: bfloat16 (1 sign, 8 exponent, 7 fraction bits), rounded to nearest even when stored */
+typedef enum { BCNN_F32 = 0, BCNN_F16 = 1, BCNN_I8 = 2, BCNN_BF16 = 3 } bcnn_dtype;
 
 /* Which arithmetic the convolution runs on.  All variants give identical
  * results; AUTO picks the fastest one measured for the shape. */
@@ -125,7 +126,7 @@ int bcnn_pack_bias_replicated(const void *src, bcnn_dtype dtype, int64_t outer, 
  *   x_packed[n][oh][ow][.] : bit c = (float(pooled as stored) + bias[c] >= 0)
  * Windows are not padded; rows and columns that do not fill a window are
  * dropped (h_out = h / S, w_out = w / S, rounded down).
- *   src        : device, [n][h][w][channels] of real_dtype (BCNN_F32 or BCNN_F16)
+ *   src        : device, [n][h][w][channels] of real_dtype (BCNN_F32, BCNN_F16 or BCNN_BF16)
  *   bias       : device, float32 [channels], or NULL for no bias
  *   pooled     : device, [n][h_out][w_out][channels] of real_dtype, or NULL
  *   x_packed   : device, [n][h_out][w_out][ceil(channels/32)], tail bits 0, or NULL
@@ -190,7 +191,7 @@ int bcnn_conv2d_binary_variant(const bcnn_conv_desc *desc, const uint32_t *x_pac
  *   r is rounded to real_dtype and stored;  bit = (r_stored + next_bias[o] >= 0)
  * All arrays are device memory.  identity == NULL: no identity path;
  * prelu_slope == NULL: no activation; next_bias == NULL: 0.  identity and r
- * are [n*h_out*w_out][c_out] of real_dtype (BCNN_F32 or BCNN_F16), i.e. the
+ * are [n*h_out*w_out][c_out] of real_dtype (BCNN_F32, BCNN_F16 or BCNN_BF16), i.e. the
  * real stream in channel-last order; r may be the same buffer as identity
  * (the stream is updated in place).  identity_channels (0 = c_out): when the
  * block widens the network by replicating channels (Section 4.2.2), the
@@ -208,7 +209,7 @@ typedef struct {
     const void *identity;     /* [m][c_out] of real_dtype, or NULL */
     const float *prelu_slope; /* [c_out], or NULL */
     const float *next_bias;   /* [c_out], or NULL */
-    int32_t real_dtype;       /* BCNN_F32 or BCNN_F16 */
+    int32_t real_dtype;       /* BCNN_F32, BCNN_F16 or BCNN_BF16 (the branch call's tail: F32 or F16) */
     int32_t identity_channels; /* channels of the identity stream; 0 means c_out */
 } bcnn_module_epilogue;
 

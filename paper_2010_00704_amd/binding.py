@@ -18,7 +18,7 @@ BCNN_ERR_UNSUPPORTED = -2
 BCNN_ERR_ALIGNMENT = -3
 BCNN_ERR_DEVICE = -4
 
-BCNN_F32, BCNN_F16, BCNN_I8 = 0, 1, 2
+BCNN_F32, BCNN_F16, BCNN_I8, BCNN_BF16 = 0, 1, 2, 3
 BCNN_VARIANT_AUTO, BCNN_VARIANT_VALU, BCNN_VARIANT_MFMA_I8, BCNN_VARIANT_MFMA_FP4 = 0, 1, 2, 3
 BCNN_VARIANT_MFMA_FP4_T4, BCNN_VARIANT_MFMA_FP4_T7 = 4, 5
 BCNN_PAD_WORDS, BCNN_PAD_ZERO = 0, 1
@@ -232,7 +232,7 @@ def check(status, where="bcnn"):
 
 # ---- conveniences that only allocate outputs with torch and call the above ----
 
-_DTYPES = {torch.float32: BCNN_F32, torch.float16: BCNN_F16, torch.int8: BCNN_I8}
+_DTYPES = {torch.float32: BCNN_F32, torch.float16: BCNN_F16, torch.int8: BCNN_I8, torch.bfloat16: BCNN_BF16}
 
 
 def pack_nchw(x, stream=None):

@@ -109,16 +109,22 @@ const char* bcnn_status_string(int status)
     }
 }
 
+// bcnn_dtype of a real stream -> the kernels' REAL_* code
+static int real_kind(int dtype)
+{
+    return dtype == BCNN_F16 ? bcnn::REAL_F16 : dtype == BCNN_BF16 ? bcnn::REAL_BF16 : bcnn::REAL_F32;
+}
+
 static int pack_entry(const void* src, int dtype, int64_t outer, int64_t channels, int64_t src_channels,
                       int64_t inner, const float* bias, uint32_t* dst, void* hip_stream)
 {
     if (!src || !dst || outer < 1 || channels < 1 || inner < 1) return BCNN_ERR_INVALID_ARG;
     if (src_channels < 1 || src_channels > channels) return BCNN_ERR_INVALID_ARG;
-    if (dtype != BCNN_F32 && dtype != BCNN_F16 && dtype != BCNN_I8) return BCNN_ERR_UNSUPPORTED;
+    if (dtype != BCNN_F32 && dtype != BCNN_F16 && dtype != BCNN_I8 && dtype != BCNN_BF16) return BCNN_ERR_UNSUPPORTED;
     const int64_t cw = (channels + 31) / 32;
     if (outer > INT_MAX || inner > INT_MAX || outer * inner > INT_MAX / cw) return BCNN_ERR_UNSUPPORTED;
     if ((double)outer * (double)channels * (double)inner > 9.0e18) return BCNN_ERR_UNSUPPORTED;
-    const uintptr_t esz = dtype == BCNN_F32 ? 4 : dtype == BCNN_F16 ? 2 : 1;
+    const uintptr_t esz = dtype == BCNN_F32 ? 4 : dtype == BCNN_I8 ? 1 : 2;
     if (!bcnn::aligned(src, esz) || !bcnn::aligned(dst, 4)) return BCNN_ERR_ALIGNMENT;
     if (src == static_cast<const void*>(dst)) return BCNN_ERR_INVALID_ARG;
     if (bias && !bcnn::aligned(bias, 4)) return BCNN_ERR_ALIGNMENT;
@@ -156,7 +162,7 @@ int bcnn_avgpool_bias_sign_pack(const void* src, bcnn_dtype real_dtype, int32_t 
 {
     if (!src || (!pooled && !x_packed)) return BCNN_ERR_INVALID_ARG;
     if (n < 1 || h < 1 || w < 1 || channels < 1 || s < 1) return BCNN_ERR_INVALID_ARG;
-    if (real_dtype != BCNN_F32 && real_dtype != BCNN_F16) return BCNN_ERR_UNSUPPORTED;
+    if (real_dtype != BCNN_F32 && real_dtype != BCNN_F16 && real_dtype != BCNN_BF16) return BCNN_ERR_UNSUPPORTED;
     if (s > 8) return BCNN_ERR_UNSUPPORTED;
     const int64_t ho = h / s, wo = w / s;
     if (ho < 1 || wo < 1) return BCNN_ERR_INVALID_ARG;
@@ -167,7 +173,7 @@ int bcnn_avgpool_bias_sign_pack(const void* src, bcnn_dtype real_dtype, int32_t 
         !bcnn::aligned(bias, 4))
         return BCNN_ERR_ALIGNMENT;
     if (src == pooled || src == static_cast<const void*>(x_packed)) return BCNN_ERR_INVALID_ARG;
-    const hipError_t e = bcnn::launch_avgpool_pack(src, real_dtype == BCNN_F16, n, h, w, channels, s, bias, pooled,
+    const hipError_t e = bcnn::launch_avgpool_pack(src, real_kind(real_dtype), n, h, w, channels, s, bias, pooled,
                                                    x_packed, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? BCNN_OK : BCNN_ERR_DEVICE;
 }
@@ -248,7 +254,9 @@ static int make_module_ep(const bcnn_module_epilogue* ep, bool with_bn, const bc
     if (!ep || (with_bn && (!ep->bn_scale || !ep->bn_bias))) return BCNN_ERR_INVALID_ARG;
     if (!with_bn && (ep->bn_scale || ep->bn_bias)) return BCNN_ERR_INVALID_ARG;
     if (!r && !x_next_packed) return BCNN_ERR_INVALID_ARG;
-    if (ep->real_dtype != BCNN_F32 && ep->real_dtype != BCNN_F16) return BCNN_ERR_UNSUPPORTED;
+    if (ep->real_dtype != BCNN_F32 && ep->real_dtype != BCNN_F16 && ep->real_dtype != BCNN_BF16)
+        return BCNN_ERR_UNSUPPORTED;
+    if (!with_bn && ep->real_dtype == BCNN_BF16) return BCNN_ERR_UNSUPPORTED;   // branch sums end in float or half
     const int id_channels = ep->identity_channels ? ep->identity_channels : s.c_out;
     if (id_channels < 1 || id_channels > s.c_out) return BCNN_ERR_INVALID_ARG;
     if (id_channels != s.c_out && ep->identity && ep->identity == r) return BCNN_ERR_INVALID_ARG;
@@ -261,7 +269,7 @@ static int make_module_ep(const bcnn_module_epilogue* ep, bool with_bn, const bc
         return BCNN_ERR_ALIGNMENT;
     m->scale = ep->bn_scale; m->bias = ep->bn_bias; m->identity = ep->identity; m->slope = ep->prelu_slope;
     m->id_channels = id_channels;
-    m->next_bias = ep->next_bias; m->r = r; m->x_next = x_next_packed; m->half = ep->real_dtype == BCNN_F16;
+    m->next_bias = ep->next_bias; m->r = r; m->x_next = x_next_packed; m->half = real_kind(ep->real_dtype);
     return BCNN_OK;
 }
 

@@ -31,25 +31,31 @@ struct ModuleEp {
     const float* next_bias;  // [c_out] or nullptr (0)
     void* r;                 // [m][c_out] float or half, or nullptr
     uint32_t* x_next;        // [m][cwo] packed bits of sign(r + next_bias), or nullptr
-    int32_t half;            // identity and r are IEEE half instead of float
+    int32_t half;            // type of identity and r: REAL_F32, REAL_F16 or REAL_BF16
 };
+
+// Storage type of a module's real stream (the paper fixes none; Section 4.2.1, first paragraph).
+enum { REAL_F32 = 0, REAL_F16 = 1, REAL_BF16 = 2 };
+template <int REAL> struct real_type { using type = float; };
+template <> struct real_type<REAL_F16> { using type = _Float16; };
+template <> struct real_type<REAL_BF16> { using type = __bf16; };
 
 // One element of that epilogue: the order of operations is part of the
 // interface (one rounding per step: fma, add, multiply; then storage
-// rounding when the stream is half).  Returns the value as stored.
-template <bool HALF>
+// rounding, to nearest even, when the stream is a 16-bit type).  Returns the value as stored.
+template <int REAL>
 __device__ __forceinline__ float module_tail(float t, bool has_id, float idv, bool has_slope, float a)
 {
     if (has_id) t = t + idv;
     if (has_slope) t = (t >= 0.0f) ? t : a * t;
-    if constexpr (HALF) t = (float)(_Float16)t;
+    if constexpr (REAL != REAL_F32) t = (float)(typename real_type<REAL>::type)t;
     return t;
 }
-template <bool HALF>
+template <int REAL>
 __device__ __forceinline__ float module_value(float y, float g, float b, bool has_id, float idv,
                                               bool has_slope, float a)
 {
-    return module_tail<HALF>(__builtin_fmaf(g, y, b), has_id, idv, has_slope, a);
+    return module_tail<REAL>(__builtin_fmaf(g, y, b), has_id, idv, has_slope, a);
 }
 
 // Launchers, one per kernel family.  Each returns the hipError_t of its launch.
@@ -93,9 +99,9 @@ hipError_t launch_conv_branches(const ConvShape& s, const BranchArgs& a, hipStre
 // the same on the matrix cores; `supported` says whether it covers the call
 bool conv_branches_mfma_supported(const ConvShape& s, const BranchArgs& a);
 hipError_t launch_conv_branches_mfma(const ConvShape& s, const BranchArgs& a, hipStream_t stream);
-// S x S / S average pooling of a channel-last real map [n][h][w][c] (float, or half when `half`), fused
+// S x S / S average pooling of a channel-last real map [n][h][w][c] (of type REAL_* `real`), fused
 // with bias + sign + pack of the pooled map; pooled or bits may be nullptr, bias too (zero)
-hipError_t launch_avgpool_pack(const void* src, bool half, int n, int h, int w, int c, int s, const float* bias,
+hipError_t launch_avgpool_pack(const void* src, int real, int n, int h, int w, int c, int s, const float* bias,
                                void* pooled, uint32_t* bits, hipStream_t stream);
 
 }  // namespace bcnn

@@ -61,6 +61,7 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     // length.  Only the fused kernel has the
     // registers for it: the int32 epilogue of a 2 x 7 tile would spill.
     // `tile` = 4 or 7 forces a tile (for tests and measurements), 0 chooses.
+    if (ep && ep->half == REAL_BF16) return launch_pb<4, OUT_MODULE_BF16>(a, x, w, nullptr, nullptr, ep, stream);
     if (ep && ep->half) return launch_pb<4, OUT_MODULE_F16>(a, x, w, nullptr, nullptr, ep, stream);
     if (ep) return launch_pb<4, OUT_MODULE_F32>(a, x, w, nullptr, nullptr, ep, stream);
     if (!thr) return launch_pb<4, OUT_I32>(a, x, w, thr, out, nullptr, stream);

@@ -73,6 +73,7 @@ struct MfmaArgs {
     int32_t taps;           // filter taps = branches
     int32_t chunks_per_tap; // branch mode: cw / 8
     DivBy div_hw, div_wo;   // division of a pixel index by ho*wo and by wo
+    DivBy div_ct;           // division of a tile index by n_ctiles
 };
 
 // Branch mode (see the section in front of the fold below): per-branch scales,
@@ -191,7 +192,7 @@ constexpr int MAX_BRANCHES = 16;        // scales kept in LDS: taps <= this
 // outside the image stands for (0: -1 everywhere, nothing to do; 1: the
 // branch's pad words; 2: nothing at all).  Kind: what happens to the branch sum
 // (float out, sign bits, or the module tail with a float / half real stream).
-enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3, OUT_BRANCH = 4 };
+enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3, OUT_MODULE_BF16 = 4, OUT_BRANCH = 8 };
 enum { KIND_F32 = 0, KIND_BITS = 1, KIND_TAIL_F32 = 2, KIND_TAIL_F16 = 3 };
 
 // PLAIN (module outputs outside branch mode only): the launcher has checked that
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     constexpr int STAGE_BYTES = NBLK * 1024;
     constexpr int NL = (NBLK + 3) / 4;           // loads per wave and chunk
     __shared__ uint4 stage[3 * NBLK * 64];
-    __shared__ int wpop_lds[WG_CH];
+    __shared__ __align__(16) float sub_lds[WG_CH];              // per channel: what the epilogue subtracts
     __shared__ int thr_lds[FUSED ? WG_CH : 1];                  // thresholds of the tile, fetched at kernel start
     // per tap: [parity][what the accumulator carries besides the tap's sum | the tap's sum where the tap is padding][channel]
     __shared__ __align__(16) float tapf_lds[BRANCH ? 2 : 1][2][WG_CH];
@@ -242,8 +243,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     const int n_tiles = a.n_ptiles * a.n_ctiles;
     const int per_xcd = n_tiles >> 3;
     if (tile < per_xcd * 8) tile = (tile & 7) * per_xcd + (tile >> 3);
-    const int ctile = tile % a.n_ctiles;
-    const int ptile = tile / a.n_ctiles;
+    const int ptile = a.div_ct(tile);
+    const int ctile = tile - ptile * a.n_ctiles;
     const int o0 = ctile * WG_CH;
     const int m0 = ptile * WG_PX;
 
@@ -547,11 +548,13 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // so that their trip to HBM hides behind the K loop instead of starting
     // after it (the real stream may be updated in place: these are reads of
     // elements only this workgroup writes, and it writes them later).
-    constexpr bool MODULE = OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16 || KIND >= KIND_TAIL_F32;
-    constexpr bool HALF = OUT == OUT_MODULE_F16 || KIND == KIND_TAIL_F16;
+    constexpr bool MODULE = (OUT >= OUT_MODULE_F32 && OUT <= OUT_MODULE_BF16) || KIND >= KIND_TAIL_F32;
+    // storage type of the real stream (branch mode: float or half)
+    constexpr int REAL = OUT == OUT_MODULE_BF16 ? REAL_BF16 : (OUT == OUT_MODULE_F16 || KIND == KIND_TAIL_F16) ? REAL_F16 : REAL_F32;
+    constexpr bool HALF = REAL != REAL_F32;                // a 16-bit stream
     // (only where 32 registers can be held through the loop: the half-precision stream outside branch mode)
     constexpr bool EARLY_IDS = MODULE && !BRANCH && HALF;
-    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+    using real_t = typename real_type<REAL>::type;
     typedef real_t real4 __attribute__((ext_vector_type(4)));
     constexpr int AHEAD = HALF ? 2 : 1;                    // pixel blocks in flight ahead of the one in work
     real4 early_ids[EARLY_IDS ? AHEAD : 1][8];
@@ -879,26 +882,29 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // the result is never zero, in the fused case) is kept in sub[][].
     float sub[CB][16];
     if constexpr (!BRANCH) {
+        // The lane that holds a channel's count turns it into the value to subtract and leaves it in
+        // LDS as a float; every lane then fetches its 2 x 16 channels with eight 16-byte reads.
+        const int base = a.z - 192 * a.n_chunks;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             // lanes l and l^32 read the two K-halves of the same weight row
             const int both = wpop[cb] + __shfl_xor(wpop[cb], 32, 64);
-            if (hsel == 0) wpop_lds[64 * wc + 32 * cb + row_to_channel(j)] = both;
+            if (hsel == 0) {
+                const int cl = 64 * wc + 32 * cb + row_to_channel(j);
+                int v = base + 2 * both;
+                if constexpr (FUSED) v += thr_lds[cl];
+                sub_lds[cl] = FUSED ? (float)v - 0.5f : (float)v;   // exact: multiples of 0.5 below 2^23
+            }
         }
         __syncthreads();
-        const int base = a.z - 192 * a.n_chunks;
+        typedef float sub4 __attribute__((ext_vector_type(4)));
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int cl = 64 * wc + 32 * cb + 16 * hsel + r;
-                int v = base + 2 * wpop_lds[cl];
-                if constexpr (FUSED) {
-                    const int th = thr_lds[cl];
-                    sub[cb][r] = (float)(v + th) - 0.5f;  // exact: multiples of 0.5 below 2^23
-                } else {
-                    sub[cb][r] = (float)v;
-                }
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const sub4 sb = *reinterpret_cast<const sub4*>(&sub_lds[64 * wc + 32 * cb + 16 * hsel + 4 * q4]);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) sub[cb][4 * q4 + k] = sb[k];
             }
     }
     if constexpr (FUSED || BRANCH_BITS) {
@@ -1097,10 +1103,10 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         if constexpr (BRANCH)
-                            v[k] = module_tail<HALF>(__int_as_float(qv[k]), has_id,
+                            v[k] = module_tail<REAL>(__int_as_float(qv[k]), has_id,
                                                      (float)ids[pb % (AHEAD + 1)][g][k], has_slope, pa[k]);
                         else
-                            v[k] = module_value<HALF>(__int_as_float(qv[k]), pg[k], pb_[k], has_id,
+                            v[k] = module_value<REAL>(__int_as_float(qv[k]), pg[k], pb_[k], has_id,
                                                       (float)ids[pb % (AHEAD + 1)][g][k], has_slope, pa[k]);
                         nib |= (uint32_t)((FAST || c0 + k < s.c_out) && v[k] + pc[k] >= 0.0f) << k;
                     }
@@ -1161,10 +1167,11 @@ hipError_t launch_pb(MfmaArgs a, const uint32_t* x, const uint32_t* w, const int
     const BranchEp b = bp ? *bp : BranchEp{};
     constexpr int WG_PX = 64 * PB;
     a.n_ptiles = (a.s.m + WG_PX - 1) / WG_PX;
+    a.div_ct = DivBy::make(a.n_ctiles);
     const unsigned blocks = (unsigned)(a.n_ptiles * a.n_ctiles);
-    if constexpr (OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16) {
+    if constexpr (OUT >= OUT_MODULE_F32 && OUT <= OUT_MODULE_BF16) {
         // the plain case of a module call (see the kernel's PLAIN parameter)
-        const uintptr_t al = OUT == OUT_MODULE_F16 ? 7 : 15;
+        const uintptr_t al = OUT == OUT_MODULE_F32 ? 15 : 7;
         // (c_out bound: a wave's rows of any of the three streams stay below 2^31 bytes)
         const bool plain = e.identity && e.r && e.x_next && a.s.c_out % WG_CH == 0 && e.id_channels % 4 == 0 &&
                            a.s.c_out <= (1 << 20) &&

@@ -28,7 +28,7 @@ namespace {
 using valu::TN;
 using valu::Tile;
 
-enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3 };
+enum { OUT_I32 = 0, OUT_BITS = 1, OUT_MODULE_F32 = 2, OUT_MODULE_F16 = 3, OUT_MODULE_BF16 = 4 };   // module: 2 + REAL_*
 
 template <int VEC>
 __device__ __forceinline__ void load_words(const uint32_t* p, bool ok, uint32_t (&out)[VEC])
@@ -145,13 +145,13 @@ __global__ __launch_bounds__(256) void conv_valu_kernel(
             if constexpr (OUT == OUT_I32)
                 valu::store_words_wave(s, t, m_first, lane, true, acc[i], static_cast<uint32_t*>(out), my_tile);
             else
-                valu::module_store_wave<OUT == OUT_MODULE_F16, true>(s, ep, t, m_first, ctile, lane, acc[i], my_tile);
+                valu::module_store_wave<OUT - OUT_MODULE_F32, true>(s, ep, t, m_first, ctile, lane, acc[i], my_tile);
         }
-    } else if constexpr (OUT == OUT_MODULE_F32 || OUT == OUT_MODULE_F16) {
+    } else if constexpr (OUT >= OUT_MODULE_F32) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             if (live[i])
-                valu::module_store<OUT == OUT_MODULE_F16, FULL, true>(s, ep, t, mtile * (64 * TM) + i * 64 + lane,
+                valu::module_store<OUT - OUT_MODULE_F32, FULL, true>(s, ep, t, mtile * (64 * TM) + i * 64 + lane,
                                                                       ctile, acc[i]);
     } else if constexpr (OUT == OUT_BITS) {
         uint32_t* yp = static_cast<uint32_t*>(out);
@@ -543,6 +543,7 @@ hipError_t launch_tm_vec(const ConvShape& s, const uint32_t* x, const uint32_t* 
                          const int32_t* thr, void* out, const ModuleEp* ep, hipStream_t stream)
 {
     const ModuleEp none = {};
+    if (ep && ep->half == REAL_BF16) return launch_out<TM, VEC, OUT_MODULE_BF16>(s, x, w, thr, out, *ep, stream);
     if (ep && ep->half) return launch_out<TM, VEC, OUT_MODULE_F16>(s, x, w, thr, out, *ep, stream);
     if (ep) return launch_out<TM, VEC, OUT_MODULE_F32>(s, x, w, thr, out, *ep, stream);
     if (thr) return launch_out<TM, VEC, OUT_BITS>(s, x, w, thr, out, none, stream);

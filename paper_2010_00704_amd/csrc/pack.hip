@@ -14,6 +14,7 @@ namespace {
 
 __device__ __forceinline__ bool nonneg(float v) { return v >= 0.0f; }
 __device__ __forceinline__ bool nonneg(_Float16 v) { return (float)v >= 0.0f; }
+__device__ __forceinline__ bool nonneg(__bf16 v) { return (float)v >= 0.0f; }
 __device__ __forceinline__ bool nonneg(int8_t v) { return v >= 0; }
 
 // The bit of one element: sign of the value, or (BIAS) of value + bias[channel]
@@ -413,11 +414,13 @@ hipError_t launch_pack(const void* src, int dtype, const float* bias, int64_t ou
         outer * 8 * ((channels + 31) / 32) <= 0x7FFFFFFF &&
         (reinterpret_cast<uintptr_t>(src) % (dtype == 0 ? 16 : 8)) == 0 &&
         (reinterpret_cast<uintptr_t>(bias) % 16) == 0)
-        return launch_avgpool_pack(src, dtype == 1, (int)outer, 1, 1, (int)channels, 1, bias, nullptr, dst, stream);
+        return launch_avgpool_pack(src, dtype == 1 ? REAL_F16 : REAL_F32, (int)outer, 1, 1, (int)channels, 1, bias, nullptr,
+                                   dst, stream);
     switch (dtype) {
         case 0: return pack_typed<float>(src, bias, outer, channels, src_channels, inner, dst, stream);
         case 1: return pack_typed<_Float16>(src, bias, outer, channels, src_channels, inner, dst, stream);
         case 2: return pack_typed<int8_t>(src, bias, outer, channels, src_channels, inner, dst, stream);
+        case 3: return pack_typed<__bf16>(src, bias, outer, channels, src_channels, inner, dst, stream);
         default: return hipErrorInvalidValue;
     }
 }

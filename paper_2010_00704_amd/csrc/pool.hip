@@ -38,6 +38,12 @@ __device__ __forceinline__ f4 load4(const __half* p)
     const __half2 hi = *reinterpret_cast<const __half2*>(&raw.y);
     return f4{__low2float(lo), __high2float(lo), __low2float(hi), __high2float(hi)};
 }
+__device__ __forceinline__ f4 load4(const __bf16* p)
+{
+    typedef __bf16 b4 __attribute__((ext_vector_type(4)));
+    const b4 v = *reinterpret_cast<const b4*>(p);
+    return f4{(float)v[0], (float)v[1], (float)v[2], (float)v[3]};
+}
 // Stores the four values in the stream's type and returns them as stored.
 __device__ __forceinline__ f4 round_and_store4(float* p, f4 v, bool store)
 {
@@ -56,7 +62,21 @@ __device__ __forceinline__ f4 round_and_store4(__half* p, f4 v, bool store)
     }
     return f4{__low2float(lo), __high2float(lo), __low2float(hi), __high2float(hi)};
 }
+__device__ __forceinline__ f4 round_and_store4(__bf16* p, f4 v, bool store)
+{
+    typedef __bf16 b4 __attribute__((ext_vector_type(4)));
+    const b4 r = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};     // to nearest even
+    if (store) *reinterpret_cast<b4*>(p) = r;
+    return f4{(float)r[0], (float)r[1], (float)r[2], (float)r[3]};
+}
 __device__ __forceinline__ float as_float(float v) { return v; }
+__device__ __forceinline__ float as_float(__bf16 v) { return (float)v; }
+__device__ __forceinline__ float round_and_store1(__bf16* p, float v, bool store)
+{
+    const __bf16 r = (__bf16)v;
+    if (store) *p = r;
+    return (float)r;
+}
 __device__ __forceinline__ float as_float(__half v) { return __half2float(v); }
 __device__ __forceinline__ float round_and_store1(float* p, float v, bool store)
 {
@@ -221,7 +241,7 @@ hipError_t launch_typed(const T* src, const float* bias, PoolShape p, T* pooled,
 
 }  // namespace
 
-hipError_t launch_avgpool_pack(const void* src, bool half, int n, int h, int w, int c, int s, const float* bias,
+hipError_t launch_avgpool_pack(const void* src, int real, int n, int h, int w, int c, int s, const float* bias,
                                void* pooled, uint32_t* bits, hipStream_t stream)
 {
     PoolShape p;
@@ -232,8 +252,10 @@ hipError_t launch_avgpool_pack(const void* src, bool half, int n, int h, int w, 
     p.upp_shift = -1;
     for (int sh = 3; sh < 31; ++sh)
         if ((8 * p.cw) == (1 << sh)) p.upp_shift = sh;
-    if (half)
+    if (real == REAL_F16)
         return launch_typed(static_cast<const __half*>(src), bias, p, static_cast<__half*>(pooled), bits, stream);
+    if (real == REAL_BF16)
+        return launch_typed(static_cast<const __bf16*>(src), bias, p, static_cast<__bf16*>(pooled), bits, stream);
     return launch_typed(static_cast<const float*>(src), bias, p, static_cast<float*>(pooled), bits, stream);
 }
 

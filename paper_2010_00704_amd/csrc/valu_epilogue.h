@@ -45,11 +45,12 @@ struct Tile {
 // FROM_SUMS: `vals` are the popcounts of a plain convolution (y = K - 2*vals,
 // batch-norm scale and bias applied here); otherwise they are the float sums
 // of a branch convolution, which already carry their scales and bias.
-template <bool HALF, bool FULL, bool FROM_SUMS, typename V>
+template <int REAL, bool FULL, bool FROM_SUMS, typename V>
 __device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp& ep, const Tile<FULL>& t,
                                              int m, int ctile, const V (&vals)[TN])
 {
-    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+    constexpr bool HALF = REAL != REAL_F32;             // a 16-bit stream
+    using real_t = typename real_type<REAL>::type;
     constexpr int PER = HALF ? 8 : 4;                  // elements per 16-byte vector
     typedef real_t realv __attribute__((ext_vector_type(PER)));
     const size_t row = (size_t)m * s.c_out + t.o0;
@@ -87,10 +88,10 @@ __device__ __forceinline__ void module_store(const ConvShape& s, const ModuleEp&
         const int oc = FULL ? o : (int)t.chan(o);
         const float slope = ep.slope ? (ep.slope + ob)[oc] : 1.0f;
         if constexpr (FROM_SUMS)
-            v[o] = module_value<HALF>((float)(s.k - 2 * vals[o]), (ep.scale + ob)[oc], (ep.bias + ob)[oc],
+            v[o] = module_value<REAL>((float)(s.k - 2 * vals[o]), (ep.scale + ob)[oc], (ep.bias + ob)[oc],
                                       ep.identity != nullptr, idv[o], ep.slope != nullptr, slope);
         else
-            v[o] = module_tail<HALF>(vals[o], ep.identity != nullptr, idv[o], ep.slope != nullptr, slope);
+            v[o] = module_tail<REAL>(vals[o], ep.identity != nullptr, idv[o], ep.slope != nullptr, slope);
         const float c = ep.next_bias ? (ep.next_bias + ob)[oc] : 0.0f;
         word |= (uint32_t)((FULL || t.stores(o)) && (v[o] + c >= 0.0f)) << o;
     }
@@ -176,11 +177,12 @@ __device__ __forceinline__ void store_words_wave(const ConvShape& s, const Tile<
 // FAST: all 64 pixels exist, the tile is not a shifted last tile, rows are
 // vector aligned and the module has every part (identity, real stream out,
 // next bits): no per-element predicates, loads and stores issue back to back.
-template <bool HALF, bool FROM_SUMS, bool FAST>
+template <int REAL, bool FROM_SUMS, bool FAST>
 __device__ __forceinline__ void module_store_wave_parked(const ConvShape& s, const ModuleEp& ep, const Tile<true>& t,
                                                          int m_first, int ctile, int lane, const uint32_t* tile)
 {
-    using real_t = typename std::conditional<HALF, _Float16, float>::type;
+    constexpr bool HALF = REAL != REAL_F32;             // a 16-bit stream
+    using real_t = typename real_type<REAL>::type;
     typedef real_t real4 __attribute__((ext_vector_type(4)));
     const int cg = lane & 7;
     const int c0 = t.o0 + 4 * cg;                      // the lane's four channels (all real: full tile)
@@ -232,9 +234,9 @@ __device__ __forceinline__ void module_store_wave_parked(const ConvShape& s, con
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if constexpr (FROM_SUMS)
-                v[j] = module_value<HALF>((float)(int)qv[j], pg[j], pb[j], has_id, (float)idv[k][j], has_slope, pa[j]);
+                v[j] = module_value<REAL>((float)(int)qv[j], pg[j], pb[j], has_id, (float)idv[k][j], has_slope, pa[j]);
             else
-                v[j] = module_tail<HALF>(__uint_as_float(qv[j]), has_id, (float)idv[k][j], has_slope, pa[j]);
+                v[j] = module_tail<REAL>(__uint_as_float(qv[j]), has_id, (float)idv[k][j], has_slope, pa[j]);
             nib |= (uint32_t)(v[j] + pc[j] >= 0.0f) << j;
         }
         if (FAST || (ep.r && m < s.m)) {
@@ -263,18 +265,18 @@ __device__ __forceinline__ void module_store_wave_parked(const ConvShape& s, con
     }
 }
 
-template <bool HALF, bool FROM_SUMS, typename V>
+template <int REAL, bool FROM_SUMS, typename V>
 __device__ __forceinline__ void module_store_wave(const ConvShape& s, const ModuleEp& ep, const Tile<true>& t,
                                                   int m_first, int ctile, int lane, const V (&vals)[TN],
                                                   uint32_t* tile)
 {
     park_values(tile, lane, s.k, FROM_SUMS, vals);
-    constexpr uintptr_t AL = HALF ? 7 : 15;
+    constexpr uintptr_t AL = REAL != REAL_F32 ? 7 : 15;
     const bool fast = ep.identity && ep.r && ep.x_next && t.shift == 0 && m_first + 64 <= s.m &&
                       s.c_out % 4 == 0 && ep.id_channels % 4 == 0 &&
                       ((reinterpret_cast<uintptr_t>(ep.identity) | reinterpret_cast<uintptr_t>(ep.r)) & AL) == 0;
-    if (fast) module_store_wave_parked<HALF, FROM_SUMS, true>(s, ep, t, m_first, ctile, lane, tile);
-    else module_store_wave_parked<HALF, FROM_SUMS, false>(s, ep, t, m_first, ctile, lane, tile);
+    if (fast) module_store_wave_parked<REAL, FROM_SUMS, true>(s, ep, t, m_first, ctile, lane, tile);
+    else module_store_wave_parked<REAL, FROM_SUMS, false>(s, ep, t, m_first, ctile, lane, tile);
 }
 
 }  // namespace valu

@@ -43,6 +43,38 @@ class Guarded:
         return data if count is None else data[:count]
 
 
+# ---- storage types of the real stream.  A test parameter `half` is False (float32), True (IEEE
+# half) or "bf16"; 16-bit values travel as numpy float16 arrays, bfloat16 as uint16 bit patterns.
+REAL_PARAMS = [False, True, "bf16"]
+REAL_IDS = ["f32", "f16", "bf16"]
+
+
+def real_code(half):
+    return B.BCNN_BF16 if half == "bf16" else (B.BCNN_F16 if half else B.BCNN_F32)
+
+
+def real_np_dtype(half):
+    return np.uint16 if half == "bf16" else (np.float16 if half else np.float32)
+
+
+def real_store(v32, half):
+    """float32 values -> the array as a stream of this type stores it (the oracle's rounding)."""
+    if half == "bf16":
+        return oracle.store_bf16(v32)[0]
+    return oracle.store_f16(v32) if half else np.ascontiguousarray(v32, dtype=np.float32)
+
+
+def real_values(stored, half):
+    """stored array -> its values as float32 (exact)."""
+    if half == "bf16":
+        return oracle.load_bf16(stored)
+    return stored.astype(np.float32)
+
+
+def real_seed(half):
+    return 2 if half == "bf16" else int(bool(half))
+
+
 def gpu_device():
     assert torch.cuda.is_available(), "these tests need the GPU"
     B.lib()

@@ -14,7 +14,8 @@ import torch
 import oracle
 from paper_2010_00704_amd import binding as B
 from paper_2010_00704_amd import workloads as W
-from gpu_helpers import Guarded, gpu_device, i32, run_variant, up
+from gpu_helpers import (REAL_IDS, REAL_PARAMS, Guarded, gpu_device, i32, real_code, real_np_dtype, real_seed,
+                         real_store, real_values, run_variant, up)
 
 pytestmark = pytest.mark.gpu
 
@@ -30,11 +31,11 @@ def dev():
 def oracle_module(x, wt, stride, pad, g, b, ident, alpha, c, half):
     y = oracle.conv2d_pm1(x, wt, stride, pad)
     n, ho, wo, o = y.shape
-    ident32 = None if ident is None else ident.astype(np.float32).reshape(y.shape)
+    ident32 = None if ident is None else real_values(ident, half).reshape(y.shape)
     _, r32 = oracle.module_epilogue(y, g, b, ident32, alpha)
-    stored = oracle.store_f16(r32) if half else r32
+    stored = real_store(r32, half)
     cc = c if c is not None else np.zeros(o, dtype=np.float32)
-    s = oracle.sign_bias_f32(stored.astype(np.float32).reshape(n * ho * wo, o, 1), cc)
+    s = oracle.sign_bias_f32(real_values(stored, half).reshape(n * ho * wo, o, 1), cc)
     bits = oracle.pack_channels(s.reshape(n, ho * wo, o).transpose(0, 2, 1))
     return stored.reshape(n * ho * wo, o), bits
 
@@ -52,8 +53,7 @@ def make_params(seed, m, o, half, grid):
         ident = W.uniform_f32(seed + 2, (m, o), -40.0, 40.0)
         alpha = W.uniform_f32(seed + 3, (o,), 0.05, 0.5)
         c = W.uniform_f32(seed + 4, (o,), -10.0, 10.0)
-    if half:
-        ident = oracle.store_f16(ident)
+    ident = real_store(ident, half)
     return g, b, ident, alpha, c
 
 
@@ -79,10 +79,10 @@ def gpu_module(dev, x, wt, stride, pad, g, b, ident, alpha, c, half, variant, wa
     bits = Guarded(m * cwo, dev)
     rc = B.bcnn_conv2d_binary_module(
         desc, xp, wp, up(g, dev), up(b, dev), idt, up(alpha, dev) if alpha is not None else None,
-        up(c, dev) if c is not None else None, B.BCNN_F16 if half else B.BCNN_F32,
+        up(c, dev) if c is not None else None, real_code(half),
         rbuf.ptr if want_r else None, bits.ptr if want_bits else None, variant)
     run_variant(rc, "module", variant)
-    r = rbuf.get(np.float16 if half else np.float32, m * o).reshape(m, o) if want_r else None
+    r = rbuf.get(real_np_dtype(half), m * o).reshape(m, o) if want_r else None
     xb = bits.get(np.uint32, m * cwo).reshape(n, ho * wo, cwo) if want_bits else None
     return r, xb
 
@@ -103,10 +103,10 @@ MODULE_SHAPES = [
 
 @pytest.mark.parametrize("shape", MODULE_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 def test_module_matches_oracle(dev, shape, variant, half):
     n, cin, h, w, o, k, stride, pad = shape
-    seed = 9500 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23))) + half
+    seed = 9500 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23))) + real_seed(half)
     x = W.pm1(seed, (n, cin, h, w), 0.45)
     wt = W.pm1(seed + 1, (o, cin, k, k))
     ho = (h + 2 * pad - k) // stride + 1
@@ -121,7 +121,7 @@ def test_module_matches_oracle(dev, shape, variant, half):
 
 
 @pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 def test_module_optional_parts(dev, variant, half):
     shape = (2, 128, 24, 24, 128, 1, 1, 0) if variant != B.BCNN_VARIANT_VALU else (2, 64, 10, 10, 70, 3, 1, 1)
     n, cin, h, w, o, k, stride, pad = shape
@@ -146,12 +146,12 @@ def test_module_optional_parts(dev, variant, half):
 
 
 @pytest.mark.parametrize("level", W.TABLE1_MODULES, ids=lambda t: t[0])
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 def test_module_table1_shapes(dev, level, half):
     """The 1x1 modules of the paper's network (Table 1), two images each."""
     _, ch, side = level
     n = 2
-    seed = 9700 + ch + half
+    seed = 9700 + ch + real_seed(half)
     x = W.pm1(seed, (n, ch, side, side), 0.5)
     wt = W.pm1(seed + 1, (ch, ch, 1, 1))
     m = n * side * side
@@ -167,12 +167,12 @@ def test_module_table1_shapes(dev, level, half):
                                    (2, 128, 20, 20, 100, 1, 1, 0, 25)],
                          ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 def test_module_replicated_identity(dev, shape, variant, half):
     """Section 4.2.2: the identity stream keeps its channels and is replicated by
     bookkeeping; the oracle adds a real copy."""
     n, cin, h, w, o, k, stride, pad, idc = shape
-    seed = 9800 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23, 29))) + half
+    seed = 9800 + sum(v * q for v, q in zip(shape, (3, 5, 7, 11, 13, 17, 19, 23, 29))) + real_seed(half)
     x = W.pm1(seed, (n, cin, h, w), 0.5)
     wt = W.pm1(seed + 1, (o, cin, k, k))
     ho = (h + 2 * pad - k) // stride + 1
@@ -180,8 +180,7 @@ def test_module_replicated_identity(dev, shape, variant, half):
     m = n * ho * wo
     g, b, _, alpha, c = make_params(seed + 2, 1, o, half, False)
     ident = W.uniform_f32(seed + 9, (m, idc), -40.0, 40.0)
-    if half:
-        ident = oracle.store_f16(ident)
+    ident = real_store(ident, half)
     rep = -(-o // idc)
     ident_full = oracle.replicate_channels(ident, rep, axis=1)[:, :o]
     want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident_full, alpha, c, half)
@@ -192,10 +191,10 @@ def test_module_replicated_identity(dev, shape, variant, half):
     cwo = (o + 31) // 32
     bits = Guarded(m * cwo, dev)
     rc = B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), up(ident, dev), up(alpha, dev), up(c, dev),
-                                     B.BCNN_F16 if half else B.BCNN_F32, rbuf.ptr, bits.ptr, variant,
+                                     real_code(half), rbuf.ptr, bits.ptr, variant,
                                      identity_channels=idc)
     run_variant(rc, "module", variant)
-    assert np.array_equal(rbuf.get(np.float16 if half else np.float32, m * o).reshape(m, o), want_r)
+    assert np.array_equal(rbuf.get(real_np_dtype(half), m * o).reshape(m, o), want_r)
     assert np.array_equal(bits.get(np.uint32, m * cwo).reshape(n, ho * wo, cwo), want_bits)
 
 
@@ -217,11 +216,11 @@ def test_module_argument_checks(dev):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 def test_module_full_size_1x1(dev, half):
     """The 1x1 benchmark shape as the paper's module (256 -> 256 channels, 56x56,
-    batch 32, identity path included), launched at full size; the oracle
-    evaluates the first, middle and last image."""
+    batch 32, identity path included), launched at full size and compared with
+    the oracle on the whole real stream and all packed words."""
     cfg = W.CONFIGS[1]
     _, x_all, ws, _ = W.make_inputs(2)
     wt = ws[0]
@@ -229,15 +228,14 @@ def test_module_full_size_1x1(dev, half):
     m = cfg.n * hw
     g, b, _, alpha, c = make_params(9950, 1, cfg.c_out, half, False)
     ident = W.uniform_f32(9960, (m, cfg.c_out), -40.0, 40.0)
-    if half:
-        ident = oracle.store_f16(ident)
+    ident = real_store(ident, half)
     desc = B.conv_desc(cfg.n, cfg.c_in, cfg.h, cfg.w, cfg.c_out, cfg.k, cfg.stride, cfg.pad)
     xp = B.pack_nchw(up(x_all, dev))
     wp = B.pack_nchw(up(wt, dev))
     stream_t = up(ident, dev)                 # updated in place
     bits = torch.empty((cfg.n, hw, cfg.c_out // 32), dtype=torch.int32, device=dev)
     B.check(B.bcnn_conv2d_binary_module(desc, xp, wp, up(g, dev), up(b, dev), stream_t, up(alpha, dev), up(c, dev),
-                                        B.BCNN_F16 if half else B.BCNN_F32, stream_t, bits), "module")
+                                        real_code(half), stream_t, bits), "module")
     torch.cuda.synchronize()
     got_r = stream_t.cpu().numpy().reshape(m, cfg.c_out)
     got_bits = bits.cpu().numpy().view(np.uint32)
@@ -247,7 +245,7 @@ def test_module_full_size_1x1(dev, half):
 
 
 @pytest.mark.parametrize("variant", VARIANTS, ids=VARIANT_IDS)
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 def test_module_special_values(dev, variant, half):
     """Signed zeros, denormals, the largest finite values and infinities in the
     identity stream, a next bias that holds -0 and cancels stored values exactly:
@@ -262,7 +260,11 @@ def test_module_special_values(dev, variant, half):
     m = n * h * w
     g, b, _, alpha, c = make_params(9972, m, o, half, True)
     alpha = np.maximum(alpha, np.float32(0.25))
-    if half:
+    if half == "bf16":
+        # zero, smallest subnormals (2^-133), largest subnormal, smallest normal, largest finite, infinities
+        special = real_store(np.array([0.0, -0.0, 9.2e-41, -9.2e-41, 1.166e-38, 1.1754944e-38, np.inf, -np.inf,
+                                       3.3895314e38, -3.3895314e38, 1.0, -2.5, 65504.0], dtype=np.float32), half)
+    elif half:
         special = np.array([0.0, -0.0, 6e-8, -6e-8, 6.1e-5, -6.1e-5, np.inf, -np.inf, 65504.0, -65504.0, 1.0, -2.5],
                            dtype=np.float16)
     else:
@@ -274,11 +276,11 @@ def test_module_special_values(dev, variant, half):
     c[0::7] = np.float32(-0.0)
     with np.errstate(over="ignore"):          # values too large for half become infinities, on purpose
         want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident, alpha, c, half)
-    assert not np.any(np.isnan(want_r.astype(np.float32)))      # no NaN in play
+    assert not np.any(np.isnan(real_values(want_r, half)))      # no NaN in play
     # a bias that cancels what the first row stores, so that r + c is exactly zero there
     c2 = c.copy()
-    fin = np.isfinite(want_r[0].astype(np.float32))
-    c2[fin] = -want_r[0].astype(np.float32)[fin]
+    fin = np.isfinite(real_values(want_r[0], half))
+    c2[fin] = -real_values(want_r[0], half)[fin]
     for cc in (c, c2):
         with np.errstate(over="ignore"):
             want_r, want_bits = oracle_module(x, wt, stride, pad, g, b, ident, alpha, cc, half)

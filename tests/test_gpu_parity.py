@@ -86,7 +86,7 @@ PACK_SHAPES = [
 
 
 @pytest.mark.parametrize("shape", PACK_SHAPES, ids=lambda s: "x".join(map(str, s)))
-@pytest.mark.parametrize("dtype", ["f32", "f16", "i8"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "i8", "bf16"])
 def test_pack_matches_oracle(dev, shape, dtype):
     outer, c, inner = shape
     rng = np.random.default_rng(outer * 1000 + c * 10 + inner)
@@ -103,6 +103,12 @@ def test_pack_matches_oracle(dev, shape, dtype):
         src = oracle.store_f16(vals)
         as_f32 = src.astype(np.float32)
         code = B.BCNN_F16
+    elif dtype == "bf16":
+        vals[rng.random(shape) < 0.02] = np.nan
+        vals[rng.random(shape) < 0.01] = -np.inf
+        vals[rng.random(shape) < 0.01] = -1e-40  # negative bfloat16 denormal
+        src, as_f32 = oracle.store_bf16(vals)
+        code = B.BCNN_BF16
     else:
         vals[rng.random(shape) < 0.02] = np.nan
         vals[rng.random(shape) < 0.01] = np.inf

@@ -9,7 +9,8 @@ import pytest
 import oracle
 from paper_2010_00704_amd import binding as B
 from paper_2010_00704_amd import workloads as W
-from gpu_helpers import Guarded, gpu_device, oracle_bits_of_sign, up
+from gpu_helpers import (REAL_IDS, REAL_PARAMS, Guarded, gpu_device, oracle_bits_of_sign, real_code, real_np_dtype,
+                         real_store, real_values, up)
 
 pytestmark = pytest.mark.gpu
 
@@ -21,11 +22,11 @@ def dev():
 
 def expected(src, s, bias, half):
     """Oracle side: the float chain, the value as stored, bias + sign, packed."""
-    _, p32 = oracle.avgpool_nhwc(src.astype(np.float32), s)
-    stored = oracle.store_f16(p32) if half else p32
+    _, p32 = oracle.avgpool_nhwc(real_values(src, half), s)
+    stored = real_store(p32, half)
     n, ho, wo, c = stored.shape
     b = np.zeros(c, dtype=np.float32) if bias is None else bias
-    sgn = oracle.sign_bias_f32(stored.astype(np.float32).reshape(n * ho * wo, c, 1), b)
+    sgn = oracle.sign_bias_f32(real_values(stored, half).reshape(n * ho * wo, c, 1), b)
     return stored, oracle_bits_of_sign(sgn.reshape(n, ho, wo, c))
 
 
@@ -33,7 +34,7 @@ def source(seed, shape, half):
     # a few magnitudes so that additions round, and exact zeros so that the tie of the sign shows up
     a = W.uniform_f32(seed, shape, -40.0, 40.0, steps=320)
     a = a * np.where(W.uniform_f32(seed + 1, shape, 0.0, 1.0) < 0.2, np.float32(1e-3), np.float32(1.0))
-    return oracle.store_f16(a) if half else a.astype(np.float32)
+    return real_store(a.astype(np.float32), half)
 
 
 def run(dev, src, s, bias, half, want_pooled=True, want_bits=True, misalign=0):
@@ -47,12 +48,12 @@ def run(dev, src, s, bias, half, want_pooled=True, want_bits=True, misalign=0):
     src_buf.put(raw)
     out = Guarded.of_bytes(stored.size * esz, dev)
     pk = Guarded(bits.size, dev)
-    rc = B.bcnn_avgpool_bias_sign_pack(src_buf.ptr + misalign * esz, B.BCNN_F16 if half else B.BCNN_F32, n, h, w, c, s,
+    rc = B.bcnn_avgpool_bias_sign_pack(src_buf.ptr + misalign * esz, real_code(half), n, h, w, c, s,
                                        None if bias is None else up(bias, dev),
                                        out.ptr if want_pooled else None, pk.ptr if want_bits else None)
     B.check(rc, "avgpool")
     if want_pooled:
-        got = out.get(np.float16 if half else np.float32, stored.size).reshape(stored.shape)
+        got = out.get(real_np_dtype(half), stored.size).reshape(stored.shape)
         assert np.array_equal(got, stored)
     if want_bits:
         assert np.array_equal(pk.get(np.uint32).reshape(bits.shape), bits)
@@ -77,7 +78,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 @pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_avgpool_bias_sign_pack(dev, shape, half):
     n, h, w, c, s = shape
@@ -86,7 +87,7 @@ def test_avgpool_bias_sign_pack(dev, shape, half):
     run(dev, src, s, bias, half)
 
 
-@pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
+@pytest.mark.parametrize("half", REAL_PARAMS, ids=REAL_IDS)
 def test_optional_arguments_and_alignment(dev, half):
     src = source(22000, (2, 8, 10, 64), half)
     bias = W.uniform_f32(22001, (64,), -10.0, 10.0)
@@ -111,7 +112,7 @@ def test_sign_of_exact_zero_and_ties(dev):
     assert bits[0, 1, 0] == 0x55555555 and bits[0, 0, 0] == 0
 
 
-@pytest.mark.parametrize("level,half", [("level1", True), ("level2", True), ("level3", False)])
+@pytest.mark.parametrize("level,half", [("level1", True), ("level2", True), ("level3", False), ("level2", "bf16")])
 def test_table1_transitions_full_size(dev, level, half):
     """The down-sampling steps of the paper's Table 1 at batch 32 (map sizes
     112 -> 56 -> 28 -> 14 with the channel counts of the level that is left),
