@@ -89,47 +89,46 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
     }
 }
 
-// ---- fp32, inner a multiple of 4: the same with four pixels per thread ------
-// 16-byte non-temporal loads (four consecutive pixels of one channel); the 32
-// channel loads of a word are issued in two batches of 16.  This is the form
-// that gets closest to the chip's read bandwidth.
+// ---- fp32, inner a multiple of 4: four pixels per thread, whole rows per block ----
+// The pixels of all images are numbered through (pixel a*inner + i is unit (a*inner + i) / 4, lane
+// position i % 4), so every lane of every wave has work whatever `inner` is.  A block owns 64
+// units = 256 consecutive output pixels and builds ALL packed words of them: wave w takes the
+// words w, w+4, ... (up to PACK4_WORDS per block; more channels go to further blocks along y), 32
+// independent 16-byte non-temporal loads per word, all in flight.  The words meet in LDS and leave
+// as one contiguous run of 256 * words * 4 bytes: whole cache lines, written once.
+constexpr int PACK4_WORDS = 32;   // packed words per pixel and block: 256 * 32 * 4 B = 32 KB of LDS
+
 template <bool BIAS, bool REP>
-__global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
+__global__ __launch_bounds__(PACK_THREADS) void pack_units4_kernel(
     const float* __restrict__ src, const float* __restrict__ bias, int64_t channels, int64_t src_channels,
-    int64_t inner, int64_t cw_total, int cwg, int groups, uint32_t* __restrict__ dst)
+    int64_t inner, int64_t units, int64_t cw_total, uint32_t* __restrict__ dst)
 {
     typedef float f4 __attribute__((ext_vector_type(4)));
-    __shared__ uint32_t stage[PACK_THREADS * 4 * PACK_CW_CHUNK];
-    const int64_t a = blockIdx.y / groups;
-    const int64_t j0 = (int64_t)(blockIdx.y % groups) * cwg;
-    const int64_t i0 = (int64_t)blockIdx.x * (PACK_THREADS * 4);
-    const int tid = threadIdx.x;
-    const int64_t i = i0 + 4 * tid;
-    const bool live = i < inner;                       // inner % 4 == 0: all four pixels or none
-    const int64_t icl = live ? i : inner - 4;
-    const float* col = src + a * src_channels * inner + icl;
-    const int64_t rest = inner - i0;
-    const int rows_here = (int)(rest < PACK_THREADS * 4 ? rest : PACK_THREADS * 4);
-    const int jn = (int)((cw_total - j0 < cwg) ? (cw_total - j0) : cwg);
+    extern __shared__ uint32_t stage[];               // [256 pixels][jn words]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t j0 = (int64_t)blockIdx.y * PACK4_WORDS;
+    const int jn = (int)((cw_total - j0 < PACK4_WORDS) ? (cw_total - j0) : PACK4_WORDS);
+    const int64_t u0 = (int64_t)blockIdx.x * 64;
+    const int64_t u = u0 + lane < units ? u0 + lane : units - 1;       // clamped: duplicates, not stored
+    const int64_t per_image = inner >> 2;
+    const int64_t a = u / per_image;
+    const float* col = src + a * src_channels * inner + 4 * (u - a * per_image);
 
-    for (int j = 0; j < jn; ++j) {
+    for (int j = wave; j < jn; j += 4) {
         const int64_t c0 = (j0 + j) * 32;
         uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
         if (c0 + 32 <= channels) {
+            f4 v[32];
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                f4 v[16];
+            for (int b = 0; b < 32; ++b)
+                v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(
+                    col + src_channel<REP>(c0 + b, src_channels) * inner));
 #pragma unroll
-                for (int b = 0; b < 16; ++b)
-                    v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(
-                        col + src_channel<REP>(c0 + 16 * half + b, src_channels) * inner));
-#pragma unroll
-                for (int b = 0; b < 16; ++b) {
-                    w0 |= (uint32_t)bit_of<BIAS>(v[b][0], bias, c0 + 16 * half + b) << (16 * half + b);
-                    w1 |= (uint32_t)bit_of<BIAS>(v[b][1], bias, c0 + 16 * half + b) << (16 * half + b);
-                    w2 |= (uint32_t)bit_of<BIAS>(v[b][2], bias, c0 + 16 * half + b) << (16 * half + b);
-                    w3 |= (uint32_t)bit_of<BIAS>(v[b][3], bias, c0 + 16 * half + b) << (16 * half + b);
-                }
+            for (int b = 0; b < 32; ++b) {
+                w0 |= (uint32_t)bit_of<BIAS>(v[b][0], bias, c0 + b) << b;
+                w1 |= (uint32_t)bit_of<BIAS>(v[b][1], bias, c0 + b) << b;
+                w2 |= (uint32_t)bit_of<BIAS>(v[b][2], bias, c0 + b) << b;
+                w3 |= (uint32_t)bit_of<BIAS>(v[b][3], bias, c0 + b) << b;
             }
         } else {
             for (int b = 0; c0 + b < channels; ++b) {
@@ -140,16 +139,23 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns4_kernel(
                 w3 |= (uint32_t)bit_of<BIAS>(v[3], bias, c0 + b) << b;
             }
         }
-        stage[(4 * tid + 0) * jn + j] = w0;
-        stage[(4 * tid + 1) * jn + j] = w1;
-        stage[(4 * tid + 2) * jn + j] = w2;
-        stage[(4 * tid + 3) * jn + j] = w3;
+        stage[(4 * lane + 0) * jn + j] = w0;
+        stage[(4 * lane + 1) * jn + j] = w1;
+        stage[(4 * lane + 2) * jn + j] = w2;
+        stage[(4 * lane + 3) * jn + j] = w3;
     }
     __syncthreads();
-    const int total = rows_here * jn;
-    for (int t = tid; t < total; t += PACK_THREADS) {
-        const int r = t / jn, j = t - r * jn;
-        dst[(a * inner + i0 + r) * cw_total + j0 + j] = stage[t];
+    // pixel 4*u0 + r, word j0 + j; rows of a block that owns every word are contiguous in dst
+    const int64_t live = units - u0 < 64 ? units - u0 : 64;
+    const int total = (int)(4 * live) * jn;
+    uint32_t* out = dst + 4 * u0 * cw_total + j0;
+    if (jn == cw_total) {
+        for (int t = threadIdx.x; t < total; t += PACK_THREADS) out[t] = stage[t];
+    } else {
+        for (int t = threadIdx.x; t < total; t += PACK_THREADS) {
+            const int r = t / jn, j = t - r * jn;
+            out[(int64_t)r * cw_total + j] = stage[t];
+        }
     }
 }
 
@@ -271,16 +277,17 @@ hipError_t pack_dispatch(const T* src, const float* bias, int64_t outer, int64_t
         const int64_t blocks = (waves + 3) / 4;
         hipLaunchKernelGGL((pack_rows_kernel<T, ROWS, BIAS, REP>), dim3((unsigned)blocks), dim3(256), 0, stream,
                            src, bias, outer, channels, src_channels, cw, dst);
-    } else if (std::is_same<T, float>::value && inner >= 256 && inner % 4 == 0 &&
+    } else if (std::is_same<T, float>::value && inner >= 64 && inner % 4 == 0 && outer * (inner / 4) >= 64 * 128 &&
                (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
-        const int64_t bx = (inner + PACK_THREADS * 4 - 1) / (PACK_THREADS * 4);
-        int cwg = PACK_CW_CHUNK;
-        while (cwg > 1 && bx * outer * ((cw + cwg - 1) / cwg) < 512) cwg >>= 1;
-        const int64_t groups = (cw + cwg - 1) / cwg;
-        if (outer * groups > 65535) goto generic;
-        hipLaunchKernelGGL((pack_columns4_kernel<BIAS, REP>), dim3((unsigned)bx, (unsigned)(outer * groups)),
-                           dim3(PACK_THREADS), 0, stream, reinterpret_cast<const float*>(src), bias, channels,
-                           src_channels, inner, cw, cwg, (int)groups, dst);
+        // (from 128 blocks on; smaller inputs spread better over the chip with one pixel per thread)
+        const int64_t units = outer * (inner / 4);
+        const int64_t bx = (units + 63) / 64;
+        const int64_t by = (cw + PACK4_WORDS - 1) / PACK4_WORDS;
+        if (bx > 0x7FFFFFFF || by > 65535) goto generic;
+        const int words = (int)(cw < PACK4_WORDS ? cw : PACK4_WORDS);
+        hipLaunchKernelGGL((pack_units4_kernel<BIAS, REP>), dim3((unsigned)bx, (unsigned)by), dim3(PACK_THREADS),
+                           (size_t)256 * words * 4, stream, reinterpret_cast<const float*>(src), bias, channels,
+                           src_channels, inner, units, cw, dst);
     } else if (inner >= 64) {
         const int64_t bx = (inner + PACK_THREADS - 1) / PACK_THREADS;
         // words per block: as many as possible (up to 8) while two blocks per CU remain

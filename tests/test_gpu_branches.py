@@ -40,6 +40,7 @@ def pack_padv(padv):
 PACK_BIAS_SHAPES = [
     # outer, channels, inner   (every kernel family: rows, small inner, columns, 4-pixel columns, generic)
     (5, 70, 1), (3, 64, 49), (2, 100, 9), (2, 33, 300), (2, 64, 784), (1, 32, 4), (3, 96, 17), (2, 256, 1024),
+    (33, 70, 1000),
 ]
 
 
@@ -78,6 +79,7 @@ def test_pack_bias(dev, outer, channels, inner, dtype):
 
 REPLICATED_SHAPES = [
     # outer, source channels, inner, replication   (every kernel family; ragged and word-aligned channel counts)
+    (12, 48, 2800, 3),
     (5, 35, 1, 2), (3, 32, 49, 4), (2, 50, 9, 3), (2, 33, 300, 2), (2, 32, 784, 8), (1, 16, 4, 2), (3, 64, 1, 3),
     (2, 64, 1024, 2),
 ]

@@ -82,6 +82,7 @@ PACK_SHAPES = [
     (7, 64, 9), (64, 64, 9), (3, 40, 1), (100, 256, 1), (9, 65, 1), (1, 32, 1), (2, 300, 5),
     (13, 96, 63), (1, 1, 1), (4, 1024, 49), (3, 70, 17), (2, 96, 33), (6, 33, 8), (3, 64, 4),
     (40, 256, 196), (2, 512, 3136),
+    (11, 65, 3000), (9, 1030, 3644), (170, 96, 196),      # four pixels per thread, whole rows per block
 ]
 
 
