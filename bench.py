@@ -228,6 +228,8 @@ def main():
             "tbops": round(tb, 1), "frac_valu_peak": round(tb / VALU_PEAK_TBOPS, 4),
             "pack_ms": round(pack_ms, 4),
             "pack_gbs": round(src_bytes / (pack_ms * 1e-3) / 1e9, 1),
+            # against the published 8 TB/s; event-timed inside the step, launch gap included
+            "pack_frac_hbm": round(src_bytes / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         })
 
     # ---------------------------------------------------------------- roofline

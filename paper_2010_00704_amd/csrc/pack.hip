@@ -94,7 +94,7 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_columns_kernel(
 // position i % 4), so every lane of every wave has work whatever `inner` is.  A block owns 64
 // units = 256 consecutive output pixels and builds ALL packed words of them: wave w takes the
 // words w, w+4, ... (up to PACK4_WORDS per block; more channels go to further blocks along y), 32
-// independent 16-byte non-temporal loads per word, all in flight.  The words meet in LDS and leave
+// independent 16-byte non-temporal loads per word in two batches of 16.  The words meet in LDS and leave
 // as one contiguous run of 256 * words * 4 bytes: whole cache lines, written once.
 constexpr int PACK4_WORDS = 32;   // packed words per pixel and block: 256 * 32 * 4 B = 32 KB of LDS
 
@@ -118,17 +118,20 @@ __global__ __launch_bounds__(PACK_THREADS) void pack_units4_kernel(
         const int64_t c0 = (j0 + j) * 32;
         uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
         if (c0 + 32 <= channels) {
-            f4 v[32];
 #pragma unroll
-            for (int b = 0; b < 32; ++b)
-                v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(
-                    col + src_channel<REP>(c0 + b, src_channels) * inner));
+            for (int half = 0; half < 2; ++half) {      // two batches of 16 loads: 64 registers in flight
+                f4 v[16];
 #pragma unroll
-            for (int b = 0; b < 32; ++b) {
-                w0 |= (uint32_t)bit_of<BIAS>(v[b][0], bias, c0 + b) << b;
-                w1 |= (uint32_t)bit_of<BIAS>(v[b][1], bias, c0 + b) << b;
-                w2 |= (uint32_t)bit_of<BIAS>(v[b][2], bias, c0 + b) << b;
-                w3 |= (uint32_t)bit_of<BIAS>(v[b][3], bias, c0 + b) << b;
+                for (int b = 0; b < 16; ++b)
+                    v[b] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(
+                        col + src_channel<REP>(c0 + 16 * half + b, src_channels) * inner));
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {
+                    w0 |= (uint32_t)bit_of<BIAS>(v[b][0], bias, c0 + 16 * half + b) << (16 * half + b);
+                    w1 |= (uint32_t)bit_of<BIAS>(v[b][1], bias, c0 + 16 * half + b) << (16 * half + b);
+                    w2 |= (uint32_t)bit_of<BIAS>(v[b][2], bias, c0 + 16 * half + b) << (16 * half + b);
+                    w3 |= (uint32_t)bit_of<BIAS>(v[b][3], bias, c0 + 16 * half + b) << (16 * half + b);
+                }
             }
         } else {
             for (int b = 0; c0 + b < channels; ++b) {

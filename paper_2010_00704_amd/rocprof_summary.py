@@ -201,13 +201,14 @@ def main(argv=None):
     ap.add_argument("--out", required=True)
     ap.add_argument("--command", action="append", default=[], help="the full command of a run (repeatable)")
     ap.add_argument("--title")
+    ap.add_argument("--append", action="store_true", help="add to the file instead of replacing it")
     ap.add_argument("--shapes", default="1,2,3,4,5")
     ap.add_argument("--copy-bytes", type=int, default=64 << 20, help="size of the copy probe's buffer")
     args = ap.parse_args(argv)
     args.shapes = [int(v) for v in args.shapes.split(",")]
     lines = {"trace": cmd_trace, "counters": cmd_counters, "traffic": cmd_traffic}[args.mode](args)
-    with open(args.out, "w") as f:
-        f.write("\n".join(lines))
+    with open(args.out, "a" if args.append else "w") as f:
+        f.write("\n".join(lines) + "\n")
     print("wrote", args.out)
 
 
