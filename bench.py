@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma_i8", "mfma_fp4", "mfma_fp4_t4", "mfma_fp4_t7"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "valu", "mfma_i8", "mfma_fp4", "mfma_fp4_t4", "mfma_fp4_t7", "mfma_fp4_p6", "mfma_fp4_p7", "mfma_fp4_p5", "mfma_fp4_p68"])
     ap.add_argument("--shapes", default="1,2,3,4,5",
                     help="comma list of layer shapes in the step (default all five; a subset is for profiling)")
     ap.add_argument("--eager", action="store_true", help="time eagerly enqueued steps instead of graph replays")
@@ -67,7 +67,9 @@ def main():
     dev = torch.device("cuda:0")
     variant = {"auto": B.BCNN_VARIANT_AUTO, "valu": B.BCNN_VARIANT_VALU,
                "mfma_i8": B.BCNN_VARIANT_MFMA_I8, "mfma_fp4": B.BCNN_VARIANT_MFMA_FP4,
-               "mfma_fp4_t4": B.BCNN_VARIANT_MFMA_FP4_T4, "mfma_fp4_t7": B.BCNN_VARIANT_MFMA_FP4_T7}[args.variant]
+               "mfma_fp4_t4": B.BCNN_VARIANT_MFMA_FP4_T4, "mfma_fp4_t7": B.BCNN_VARIANT_MFMA_FP4_T7,
+               "mfma_fp4_p6": B.BCNN_VARIANT_MFMA_FP4_P6, "mfma_fp4_p7": B.BCNN_VARIANT_MFMA_FP4_P7,
+               "mfma_fp4_p5": B.BCNN_VARIANT_MFMA_FP4_P5, "mfma_fp4_p68": B.BCNN_VARIANT_MFMA_FP4_P68}[args.variant]
 
     # ---------------------------------------------------------------- inputs
     work = []
@@ -239,11 +241,27 @@ def main():
     dom_ms = dom["conv_ms"] / args.steps / dom["cfg"].layers
     dom_bops = W.binary_ops(dom["cfg"]) / dom["cfg"].layers
     achieved = dom_bops / (dom_ms * 1e-3) / 1e12
-    on_mfma = args.variant in ("auto", "mfma_fp4", "mfma_fp4_t4", "mfma_fp4_t7")
+    on_mfma = args.variant.startswith("mfma_fp4") or args.variant == "auto"
     if on_mfma:
-        # fp4 matrix-core path: one binary multiply-accumulate is one fp4 FMA = 2 FLOP
+        # fp4 matrix-core path: one binary multiply-accumulate is one fp4 FMA = 2 FLOP.  The kernel
+        # the library launches for the dominant shape under each variant (shape 5: AUTO takes the
+        # position-major kernel with two-wave workgroups)
+        pos = {"mfma_fp4_p5": "<5, 8, 2>", "mfma_fp4_p68": "<6, 8, 2>", "mfma_fp4_p6": "<6, 7, 4>", "mfma_fp4_p7": "<7, 7, 4>"}
+        if args.variant in pos:
+            kernel = "conv_mfma_fp4_pos_kernel" + pos[args.variant]
+        elif args.variant in ("auto", "mfma_fp4") and dom["cfg"].name.startswith("cfg5"):
+            kernel = "conv_mfma_fp4_pos_kernel<5, 8, 2>"
+        else:
+            kernel = "conv_mfma_fp4_kernel"
+        # share of the filter taps that lie inside the image: the position-major kernel does not walk
+        # the others (it adds their closed form), the algorithmic count above includes them
+        cfg = dom["cfg"]
+        ho, wo = W.out_hw(cfg)
+        inside = sum(sum(0 <= o * cfg.stride - cfg.pad + u < cfg.h for u in range(cfg.k)) for o in range(ho)) * \
+            sum(sum(0 <= o * cfg.stride - cfg.pad + v < cfg.w for v in range(cfg.k)) for o in range(wo))
         roofline = {
-            "kernel": "conv_mfma_fp4_kernel on " + dom["cfg"].name + " (per launch)",
+            "kernel": kernel + " on " + dom["cfg"].name + " (per launch)",
+            "taps_inside_image": round(inside / float(ho * wo * cfg.k * cfg.k), 4),
             "bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_FP4_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / MFMA_FP4_PEAK_TFLOPS, 4),
             "avg_launch_ms": round(dom_ms, 4),

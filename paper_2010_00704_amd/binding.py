@@ -21,6 +21,7 @@ BCNN_ERR_DEVICE = -4
 BCNN_F32, BCNN_F16, BCNN_I8, BCNN_BF16 = 0, 1, 2, 3
 BCNN_VARIANT_AUTO, BCNN_VARIANT_VALU, BCNN_VARIANT_MFMA_I8, BCNN_VARIANT_MFMA_FP4 = 0, 1, 2, 3
 BCNN_VARIANT_MFMA_FP4_T4, BCNN_VARIANT_MFMA_FP4_T7 = 4, 5
+BCNN_VARIANT_MFMA_FP4_P6, BCNN_VARIANT_MFMA_FP4_P7, BCNN_VARIANT_MFMA_FP4_P5, BCNN_VARIANT_MFMA_FP4_P68 = 6, 7, 8, 9
 BCNN_PAD_WORDS, BCNN_PAD_ZERO = 0, 1
 
 EXPORTS = (

@@ -77,6 +77,15 @@ int conv_entry(const bcnn_conv_desc* desc, const uint32_t* x, const uint32_t* w,
             e = launch_conv_mfma_fp4(s, x, w, fused ? thr : nullptr, out, nullptr,
                                      variant == BCNN_VARIANT_MFMA_FP4_T7 ? 7 : variant == BCNN_VARIANT_MFMA_FP4_T4 ? 4 : 0, st);
             break;
+        case BCNN_VARIANT_MFMA_FP4_P6:
+        case BCNN_VARIANT_MFMA_FP4_P7:
+        case BCNN_VARIANT_MFMA_FP4_P5:
+        case BCNN_VARIANT_MFMA_FP4_P68:
+            if (!fused || !conv_mfma_fp4_supported(s, x, w) || !conv_mfma_fp4_pos_supported(s)) return BCNN_ERR_UNSUPPORTED;
+            e = launch_conv_mfma_fp4(s, x, w, thr, out, nullptr,
+                                     variant == BCNN_VARIANT_MFMA_FP4_P6 ? 67 : variant == BCNN_VARIANT_MFMA_FP4_P7 ? 77 :
+                                     variant == BCNN_VARIANT_MFMA_FP4_P68 ? 68 : 58, st);
+            break;
         case BCNN_VARIANT_MFMA_I8:
             if (!conv_mfma_i8_supported(s, x, w)) return BCNN_ERR_UNSUPPORTED;
             e = launch_conv_mfma_i8(s, x, w, fused ? thr : nullptr, out, st);

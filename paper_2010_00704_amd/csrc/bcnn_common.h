@@ -70,7 +70,10 @@ hipError_t launch_conv_valu(const ConvShape& s, const uint32_t* x, const uint32_
                             const int32_t* thr, void* out, const ModuleEp* ep, hipStream_t stream);
 // fp4 matrix-core variant; `supported` says whether it covers the shape/alignment.
 bool conv_mfma_fp4_supported(const ConvShape& s, const uint32_t* x, const uint32_t* w);
-// tile: pixel blocks per wave, 4 or 7 (7 exists for the fused kernel only), 0 = choose
+// whether the position-major tiling covers the shape (fused output only; see the launcher)
+bool conv_mfma_fp4_pos_supported(const ConvShape& s);
+// tile: pixel blocks per wave, 4 or 7 (7 exists for the fused kernel only), 0 = choose;
+// 58, 67, 77: position-major tiles, 10 * (blocks per wave of interior tiles) + (of edge tiles), fused output only
 hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                                 const int32_t* thr, void* out, const ModuleEp* ep, int tile,
                                 hipStream_t stream);

@@ -28,6 +28,118 @@ static double tile_cost(const ConvShape& s, int pb)
     return (double)rounds * pb;
 }
 
+// ---- position-major tiling (kernel: conv_mfma_fp4_pos_kernel)
+// Valid taps along one axis for output index o: [lo, hi] within 0..2.
+static void axis_taps(int o, int stride, int pad, int extent, int& lo, int& hi)
+{
+    const int p = o * stride - pad;
+    lo = p < 0 ? -p : 0;
+    hi = p + 2 >= extent ? extent - 1 - p : 2;
+}
+// Splits 0..count-1 into leading indices that miss taps at the low end, a middle with all three taps
+// and trailing indices that miss taps at the high end; false if that is not the structure.
+static bool axis_classes(int count, int stride, int pad, int extent, int& first_full, int& end_full,
+                         int& lead_lo, int& trail_hi)
+{
+    first_full = 0;
+    lead_lo = 0;
+    trail_hi = 2;
+    int lo, hi;
+    while (first_full < count) {
+        axis_taps(first_full, stride, pad, extent, lo, hi);
+        if (lo == 0) break;
+        if (hi < 2 || lo > 2) return false;
+        lead_lo = first_full == 0 ? lo : (lo < lead_lo ? lo : lead_lo);
+        ++first_full;
+    }
+    end_full = first_full;
+    while (end_full < count) {
+        axis_taps(end_full, stride, pad, extent, lo, hi);
+        if (lo != 0) return false;
+        if (hi < 2) break;
+        ++end_full;
+    }
+    for (int o = end_full; o < count; ++o) {
+        axis_taps(o, stride, pad, extent, lo, hi);
+        if (lo != 0 || hi < 0) return false;
+        trail_hi = o == end_full ? hi : (hi > trail_hi ? hi : trail_hi);
+    }
+    if (end_full == count) trail_hi = 2;
+    return true;
+}
+
+// Fills a.pos and a.n_ptiles for workgroups of nw waves, interior tiles of pbi blocks per wave and
+// edge tiles of pbe.  Returns the cost in the units of tile_cost() times taps (rounds of workgroups
+// x the longest tile), or a negative number if the shape does not fit the scheme.
+static double plan_pos(const ConvShape& s, int pbi, int pbe, int nw, MfmaArgs& a)
+{
+    if (s.ks != 3 || s.cw % 8 != 0 || s.n % 32 != 0 || s.n <= 0 || s.ho > 1023 || s.wo > 1023) return -1.0;
+    int r0, r1, c0, c1, top_lo, bottom_hi, left_lo, right_hi;
+    if (!axis_classes(s.ho, s.stride, s.pad, s.h, r0, r1, top_lo, bottom_hi)) return -1.0;
+    if (!axis_classes(s.wo, s.stride, s.pad, s.w, c0, c1, left_lo, right_hi)) return -1.0;
+    PosArgs& p = a.pos;
+    p.groups = s.n / 32;
+    p.div_groups = DivBy::make(p.groups);
+    p.c_in = s.k / (s.ks * s.ks);
+    p.z_per_tap = 32 * s.cw - p.c_in;
+    p.div_per_tap = DivBy::make(s.cw / 4);
+    struct Rect { int oh0, rows, ow0, cols, u_lo, nu, v_lo, nv; };
+    const Rect rects[5] = {
+        {r0, r1 - r0, c0, c1 - c0, 0, 3, 0, 3},                         // interior
+        {0, r0, 0, s.wo, top_lo, 3 - top_lo, 0, 3},                     // top rows, corners included
+        {r1, s.ho - r1, 0, s.wo, 0, bottom_hi + 1, 0, 3},               // bottom rows, corners included
+        {r0, r1 - r0, 0, c0, 0, 3, left_lo, 3 - left_lo},               // left columns
+        {r0, r1 - r0, c1, s.wo - c1, 0, 3, 0, right_hi + 1},            // right columns
+    };
+    int tiles = 0, longest = 0;
+    for (int i = 0; i < 5; ++i) {
+        const Rect& r = rects[i];
+        PosSeg& g = p.seg[i];
+        g.tile0 = tiles;
+        g.blocks = r.rows * r.cols * p.groups;
+        g.oh0 = r.oh0; g.ow0 = r.ow0; g.width = r.cols > 0 ? r.cols : 1;
+        g.u_lo = r.u_lo; g.nu = r.nu; g.v_lo = r.v_lo; g.nv = r.nv;
+        g.pb = i == 0 ? pbi : pbe;
+        g.div_width = DivBy::make(g.width);
+        const int per_tile = (nw / 2) * g.pb;
+        const int n = (g.blocks + per_tile - 1) / per_tile;
+        tiles += n;
+        if (n > 0 && r.nu * r.nv * g.pb > longest) longest = r.nu * r.nv * g.pb;
+    }
+    a.n_ptiles = tiles;
+    const int64_t wgs = (int64_t)tiles * a.n_ctiles;
+    const int64_t resident = 256 * (4 / nw);     // one wave per SIMD
+    return (double)((wgs + resident - 1) / resident) * longest;
+}
+
+bool conv_mfma_fp4_pos_supported(const ConvShape& s)
+{
+    MfmaArgs a;
+    a.n_ctiles = (s.c_out + WG_CH - 1) / WG_CH;
+    return plan_pos(s, 7, 7, 4, a) > 0.0;
+}
+
+// (interior, edge) pixel blocks per wave the position-major kernel is built for, as tile codes
+// 10 * pbi + pbe; and the waves per workgroup of each
+static const int POS_TILES[] = {58, 68, 67, 77};
+static int pos_waves(int code) { return code == 58 || code == 68 ? 2 : 4; }
+
+static hipError_t launch_pos(MfmaArgs& a, int code, const uint32_t* x, const uint32_t* w, const int32_t* thr, void* out,
+                             hipStream_t stream)
+{
+    a.div_ct = DivBy::make(a.n_ctiles);
+    const dim3 blocks((unsigned)(a.n_ptiles * a.n_ctiles));
+    uint32_t* y = static_cast<uint32_t*>(out);
+    switch (code) {
+        case 58: hipLaunchKernelGGL((conv_mfma_fp4_pos_kernel<5, 8, 2>), blocks, dim3(128), 0, stream, a, x, w, thr, y); break;
+        case 68: hipLaunchKernelGGL((conv_mfma_fp4_pos_kernel<6, 8, 2>), blocks, dim3(128), 0, stream, a, x, w, thr, y); break;
+        case 67: hipLaunchKernelGGL((conv_mfma_fp4_pos_kernel<6, 7, 4>), blocks, dim3(256), 0, stream, a, x, w, thr, y); break;
+        case 77: hipLaunchKernelGGL((conv_mfma_fp4_pos_kernel<7, 7, 4>), blocks, dim3(256), 0, stream, a, x, w, thr, y); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uint32_t* w,
                                 const int32_t* thr, void* out, const ModuleEp* ep, int tile,
                                 hipStream_t stream)
@@ -65,10 +177,34 @@ hipError_t launch_conv_mfma_fp4(const ConvShape& s, const uint32_t* x, const uin
     if (ep && ep->half) return launch_pb<4, OUT_MODULE_F16>(a, x, w, nullptr, nullptr, ep, stream);
     if (ep) return launch_pb<4, OUT_MODULE_F32>(a, x, w, nullptr, nullptr, ep, stream);
     if (!thr) return launch_pb<4, OUT_I32>(a, x, w, thr, out, nullptr, stream);
+    // `tile` = 58, 67 or 77: position-major tiles of that (interior, edge) width, forced.
+    if (tile > 10) {
+        if (plan_pos(s, tile / 10, tile % 10, pos_waves(tile), a) < 0.0) return hipErrorInvalidValue;
+        return launch_pos(a, tile, x, w, thr, out, stream);
+    }
     const int64_t wgs4 = ((s.m + 255) / 256) * a.n_ctiles;     // workgroups of the 2 x 4 tile; 512 are resident at once
     const bool long_enough = a.n_chunks >= 16 || (a.n_chunks >= 9 && wgs4 <= 512);
-    if (tile == 7 || (tile == 0 && long_enough && tile_cost(s, 7) < tile_cost(s, 4)))
-        return launch_pb<7, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
+    const bool wide = tile == 7 || (tile == 0 && long_enough && tile_cost(s, 7) < tile_cost(s, 4));
+    // Position-major tiles where they shorten the longest workgroup by a tenth or more against the
+    // 2 x 7 tile (they walk fewer taps on the edges and level the rest; their set-up is longer),
+    // and only where a pixel's channels fill whole 128-byte lines: the rows of a position-major
+    // block lie a whole image apart, so with fewer channels every 32-byte piece a chunk needs
+    // costs a line of its own (measured: 28 x 28 map with 256 channels, 21 us against 18 us).
+    if (tile == 0 && wide && s.cw >= 32) {
+        const double plain = tile_cost(s, 7) * 9.0;
+        double best = 0.9 * plain;
+        int best_code = 0;
+        for (const int code : POS_TILES) {
+            MfmaArgs ap = a;
+            const double cost = plan_pos(s, code / 10, code % 10, pos_waves(code), ap);
+            if (cost > 0.0 && cost < best) { best = cost; best_code = code; }
+        }
+        if (best_code) {
+            plan_pos(s, best_code / 10, best_code % 10, pos_waves(best_code), a);
+            return launch_pos(a, best_code, x, w, thr, out, stream);
+        }
+    }
+    if (wide) return launch_pb<7, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
     return launch_pb<4, OUT_BITS>(a, x, w, thr, out, nullptr, stream);
 }
 

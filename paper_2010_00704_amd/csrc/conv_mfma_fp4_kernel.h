@@ -60,6 +60,26 @@
 
 namespace bcnn {
 
+// Position-major tiling (see the section in front of conv_mfma_fp4_pos_kernel):
+// a segment is a rectangle of output positions whose windows miss the image in
+// the same filter rows / columns.
+struct PosSeg {
+    int32_t tile0;      // first tile (per channel tile) of the segment; tiles of pb blocks per wave along the pixels
+    int32_t blocks;     // pixel blocks of the segment = positions * groups of 32 images
+    int32_t oh0, ow0, width;   // the rectangle's corner and width (positions are numbered row by row)
+    int32_t u_lo, nu, v_lo, nv; // filter rows / columns that some window of the segment has inside the image
+    int32_t pb;         // pixel blocks per wave of the segment's tiles
+    DivBy div_width;
+};
+struct PosArgs {
+    PosSeg seg[5];
+    int32_t groups;     // n / 32
+    DivBy div_groups;
+    int32_t z_per_tap;  // 32 * cw - c_in: channel-tail positions of one tap (zero on both sides)
+    int32_t c_in;
+    DivBy div_per_tap;  // by cw / 4, the 16-byte units of a tap
+};
+
 struct MfmaArgs {
     ConvShape s;
     int32_t n_ptiles, n_ctiles;
@@ -74,6 +94,7 @@ struct MfmaArgs {
     int32_t chunks_per_tap; // branch mode: cw / 8
     DivBy div_hw, div_wo;   // division of a pixel index by ho*wo and by wo
     DivBy div_ct;           // division of a tile index by n_ctiles
+    PosArgs pos;            // position-major kernel only
 };
 
 // Branch mode (see the section in front of the fold below): per-branch scales,
@@ -150,14 +171,14 @@ template <int NS> constexpr int slot_base(int slot)
     const int sl = slot % NS;
     return 2 + 3 * ((sl + 1) * 8 / NS - sl * 8 / NS);
 }
-template <int NS, int NL>
-constexpr LoaderSlots<1 + 3 * (NL - 1)> loader_slots()
+template <int NS, int NWL, int NXL>     // NWL weight blocks and NXL input blocks per wave and chunk
+constexpr LoaderSlots<NWL + 3 * NXL> loader_slots()
 {
-    constexpr int N = 1 + 3 * (NL - 1);
+    constexpr int N = NWL + 3 * NXL;
     constexpr int CAP = 7;
     int cost[N] = {};
-    cost[0] = 5;
-    for (int p = 0; p < NL - 1; ++p) { cost[1 + 3 * p] = 3; cost[2 + 3 * p] = 1; cost[3 + 3 * p] = 4; }
+    for (int p = 0; p < NWL; ++p) cost[p] = 5;
+    for (int p = 0; p < NXL; ++p) { cost[NWL + 3 * p] = 3; cost[NWL + 1 + 3 * p] = 1; cost[NWL + 2 + 3 * p] = 4; }
     int minbase = slot_base<NS>(0);
     for (int i = 1; i < NS; ++i) minbase = slot_base<NS>(i) < minbase ? slot_base<NS>(i) : minbase;
     const int last = 2 * NS - 2;
@@ -175,13 +196,17 @@ constexpr LoaderSlots<1 + 3 * (NL - 1)> loader_slots()
     }
     return r;
 }
-// n-th (from 1, up to 6) slot of a K-step that has no share of the weight expansion; evenly spread if there are none
+// n-th (from 1, up to 6) slot of a K-step that has no share of the weight expansion; evenly spread
+// if there are fewer than six of those.  Increasing in n: statements placed by it keep their order.
 template <int NS> constexpr int light_slot(int n)
 {
+    int light = 0;
+    for (int sl = 0; sl < NS; ++sl) light += slot_base<NS>(sl) == 2;
+    if (light < 6) return (n - 1) * NS / 6;
     int seen = 0;
     for (int sl = 0; sl < NS; ++sl)
         if (slot_base<NS>(sl) == 2 && ++seen == n) return sl;
-    return (n - 1) * NS / 6;
+    return NS - 1;
 }
 
 constexpr int PAD_LDS_WORDS = 9 * 64;   // pad words kept in LDS: taps * cw <= this
@@ -201,27 +226,52 @@ enum { KIND_F32 = 0, KIND_BITS = 1, KIND_TAIL_F32 = 2, KIND_TAIL_F16 = 3 };
 // predicate-free epilogue (rows past the end are the one thing it still checks)
 // instead of that and the general one: a third of the code, which a short
 // kernel would otherwise spend its time fetching.
-template <int PB, int OUT, bool EVEN, bool PLAIN = false>
-__global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void conv_mfma_fp4_kernel(
-    MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
-    const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep, BranchEp bp)
+//
+// POS: the tile is a run of pixel blocks of one segment of the position-major
+// order (`pt`; a block = one output position in 32 consecutive images) and only
+// the filter taps of the segment's rectangle are walked; see
+// conv_mfma_fp4_pos_kernel.  `stage` is the workgroup's staging area in LDS,
+// stage_units(PB) 16-byte units.
+struct PosTile {
+    int32_t block0;     // first block of the tile within its segment
+    int32_t blocks;     // blocks of the segment
+    int32_t oh0, ow0, width;
+    int32_t u_lo, nu, v_lo, nv;
+    DivBy div_width;
+};
+// NW = waves of the workgroup: 4 (2 along the channels x 2 along the pixels, the
+// tile described above) or 2 (2 x 1: half the pixels, for tiles of finer grain;
+// two such workgroups share a CU).
+constexpr int stage_units(int pb, int nw = 4) { return 3 * (4 + (nw / 2) * pb) * 64; }
+
+template <int PB, int OUT, bool EVEN, bool PLAIN, bool POS, int NW = 4>
+__device__ __forceinline__ void conv_mfma_fp4_tile(
+    const MfmaArgs& a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
+    const int32_t* __restrict__ thr, void* __restrict__ out, const ModuleEp& ep, const BranchEp& bp,
+    uint4* stage, const int ptile, const int ctile, const PosTile& pt)
 {
+    static_assert(!POS || (OUT == OUT_BITS && EVEN && !PLAIN), "position-major tiles: fused output, whole chunks per tap");
+    static_assert(NW == 4 || (NW == 2 && OUT == OUT_BITS), "two-wave workgroups: fused output only");
+    constexpr int WP = NW / 2;        // waves along the pixels
+    constexpr int NT = 64 * NW;       // threads
     constexpr bool FUSED = OUT == OUT_BITS;
     constexpr bool BRANCH = OUT >= OUT_BRANCH;
     constexpr int KIND = BRANCH ? (OUT - OUT_BRANCH) % 4 : -1;
     constexpr bool BRANCH_BITS = KIND == KIND_BITS;
     constexpr int PADMODE = BRANCH ? (OUT - OUT_BRANCH) / 4 : 0;       // 0: -1, 1: pad words, 2: skip
     static_assert(!BRANCH || EVEN, "branch mode needs whole chunks per tap");
-    constexpr int WG_PX = 64 * PB;
+    constexpr int WG_PX = 32 * WP * PB;
     // One stage = the chunk's 8 K-words of every row of the tile, as 16-byte
     // units (4 words = one K-half of a row).  Unit order: [block of 32 rows]
     // [K-half][row], blocks 0..3 weights, 4.. inputs; one wave-wide load fills
     // one block (1 KB), and lane l of a reader wave finds the words of its MFMA
     // row at unit 64*block + l.  Three stages rotate.
-    constexpr int NBLK = 4 + 2 * PB;             // blocks per stage
+    constexpr int NBLK = 4 + WP * PB;            // blocks per stage
     constexpr int STAGE_BYTES = NBLK * 1024;
-    constexpr int NL = (NBLK + 3) / 4;           // loads per wave and chunk
-    __shared__ uint4 stage[3 * NBLK * 64];
+    constexpr int NWL = 4 / NW;                  // weight blocks a wave loads per chunk
+    constexpr int NXL = (WP * PB + NW - 1) / NW; // input blocks
+    constexpr int NL = NWL + NXL;                // loads per wave and chunk
+    static_assert(3 * NBLK * 64 == stage_units(PB, NW), "size of the staging area");
     __shared__ __align__(16) float sub_lds[WG_CH];              // per channel: what the epilogue subtracts
     __shared__ int thr_lds[FUSED ? WG_CH : 1];                  // thresholds of the tile, fetched at kernel start
     // per tap: [parity][what the accumulator carries besides the tap's sum | the tap's sum where the tap is padding][channel]
@@ -236,17 +286,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     const int hsel = lane >> 5;
     const int j = lane & 31;
 
-    // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs; give
-    // each XCD a contiguous range of tiles (channel tile fastest) so that the
-    // workgroups sharing an input tile share an L2.
-    int tile = blockIdx.x;
-    const int n_tiles = a.n_ptiles * a.n_ctiles;
-    const int per_xcd = n_tiles >> 3;
-    if (tile < per_xcd * 8) tile = (tile & 7) * per_xcd + (tile >> 3);
-    const int ptile = a.div_ct(tile);
-    const int ctile = tile - ptile * a.n_ctiles;
     const int o0 = ctile * WG_CH;
-    const int m0 = ptile * WG_PX;
+    const int m0 = ptile * WG_PX;   // (unused by position-major tiles)
 
     // The tile's thresholds are fetched now and parked in LDS behind the first
     // chunk's loads; the epilogue reads them there instead of waiting for global
@@ -259,6 +300,11 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         }
     }
 
+    __shared__ int skip_lds[POS ? WG_CH : 1];   // position-major tiles: see below, behind the first loads
+    if constexpr (POS) {
+        if (t < WG_CH) skip_lds[t] = 0;
+    }
+
     // ---- loader state.  Global -> LDS directly (buffer_load ... lds: lane l
     // of a wave writes 16 bytes at the LDS base of the instruction + 16*l, no
     // registers in between).  Per chunk wave w loads block w (weights) and the
@@ -266,11 +312,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // K-half l/32 (even or odd 16-byte unit of the chunk).  A block index past
     // the end is clamped: the same data lands twice, which is harmless, and
     // every wave issues the same number of loads.
-    int wrow_bytes;
-    {
-        int ch = o0 + 32 * wave + row_to_channel(j);
+    int wrow_bytes[NWL];
+#pragma unroll
+    for (int i = 0; i < NWL; ++i) {
+        int ch = o0 + 32 * (wave + NW * i) + row_to_channel(j);
         ch = ch < s.c_out ? ch : s.c_out - 1;
-        wrow_bytes = ch * a.n_units * 16;
+        wrow_bytes[i] = ch * a.n_units * 16;
     }
     // For input block i of this wave: word offset of the row's window top-left
     // tap (may point outside the image; only used where the tap's validity
@@ -287,18 +334,38 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         for (int u = 0; u < 3; ++u) vm |= ((uint32_t)(ph + u) < (uint32_t)s.h) ? cols << (3 * u) : 0u;
         return vm;
     };
-    int rbase[NL - 1];
-    uint32_t vmask[NL - 1];
-    int bblk[NL - 1];
+    // Position-major tiles: block `bl` of the tile -> first image, output position; false past the
+    // segment's end (the last block's numbers are returned then).  Wave-uniform when `bl` is.
+    auto block_pos = [&](int bl, int& n0, int& oh, int& ow) -> bool {
+        const int bidx = pt.block0 + bl;
+        const bool active = bidx < pt.blocks;
+        const int bc = active ? bidx : pt.blocks - 1;
+        const int pi = a.pos.div_groups(bc);
+        n0 = 32 * (bc - pi * a.pos.groups);
+        const int q = pt.div_width(pi);
+        oh = pt.oh0 + q;
+        ow = pt.ow0 + (pi - q * pt.width);
+        return active;
+    };
+    int rbase[NXL];
+    uint32_t vmask[NXL];
+    int bblk[NXL];
 #pragma unroll
-    for (int i = 0; i < NL - 1; ++i) {
-        int b = wave + 4 * i;
-        b = b < 2 * PB ? b : 2 * PB - 1;
+    for (int i = 0; i < NXL; ++i) {
+        int b = wave + NW * i;
+        b = b < WP * PB ? b : WP * PB - 1;
         bblk[i] = b;
         const int row = 32 * b + j;
         int m = m0 + row;
         m = m < s.m ? m : s.m - 1;
-        if (s.ks == 1 && s.stride == 1) {   // 1x1, unit stride: output pixel m is input pixel m, no divisions
+        if constexpr (POS) {
+            int n0, oh, ow;
+            const bool active = block_pos(b, n0, oh, ow);
+            const int ph = oh * s.stride - s.pad;
+            const int pw = ow * s.stride - s.pad;
+            rbase[i] = (((n0 + j) * s.h + ph) * s.w + pw) * s.cw;
+            vmask[i] = active ? tap_mask(ph, pw) : 0u;     // a block past the end fetches nothing
+        } else if (s.ks == 1 && s.stride == 1) {   // 1x1, unit stride: output pixel m is input pixel m, no divisions
             rbase[i] = m * s.cw;
             vmask[i] = 0xFFFFFFFFu;
         } else {
@@ -326,9 +393,21 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     //     the weights) into stages whose contents are never multiplied.
     //   otherwise: the two units are tracked separately and each lane selects
     //     its own; units past the end (K padding) read as zero.
-    const int row_jump = a.row_jump;
-    struct KPos { int unit, tap, v, ut, off; };
-    KPos k0 = {0, 0, 0, 0, 0}, k1 = {0, 0, 0, 0, 0};
+    //   position-major tiles walk the taps (u, v) of the rectangle u_lo .. u_lo+nu-1 x v_lo .. v_lo+nv-1
+    //     only: `tap` stays the tap's number in the full filter (the validity bits are indexed by
+    //     it), the weights' offset `woff` is tracked beside the inputs' and both jump at the end of
+    //     a filter row.
+    const int row_jump = POS ? (s.w - pt.nv) * s.cw : a.row_jump;
+    const int w_row_jump = POS ? (s.ks - pt.nv) * s.cw * 4 : 0;     // bytes
+    const int n_chunks = POS ? pt.nu * pt.nv * (a.units_per_tap >> 1) : a.n_chunks;
+    const int taps_per_row = POS ? pt.nv : s.ks;
+    struct KPos { int unit, tap, v, ut, off, woff; };
+    KPos k0 = {0, 0, 0, 0, 0, 0}, k1 = {0, 0, 0, 0, 0, 0};
+    if constexpr (POS) {
+        k0.tap = pt.u_lo * s.ks + pt.v_lo;
+        k0.off = (pt.u_lo * s.w + pt.v_lo) * s.cw;
+        k0.woff = k0.tap * s.cw * 4;
+    }
     auto advance1 = [&](KPos& p, int per_tap, int step_words, int go) {
         const int ut1 = p.ut + go;
         const int tap_done = ut1 == per_tap ? 1 : 0;
@@ -343,19 +422,33 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     if constexpr (!EVEN) advance1(k1, a.units_per_tap, 4, 1);
     int fetched = 0;   // chunks fetched so far (EVEN only)
     auto advance = [&]() {
-        if constexpr (EVEN) {
+        if constexpr (POS) {
+            fetched += 1;
+            const int go = k0.unit + 1 < n_chunks ? 1 : 0;
+            const int ut1 = k0.ut + go;
+            const int tap_done = ut1 == (a.units_per_tap >> 1) ? 1 : 0;
+            k0.ut = ut1 * (1 - tap_done);
+            const int v1 = k0.v + tap_done;
+            const int row_done = v1 == taps_per_row ? 1 : 0;
+            k0.v = v1 * (1 - row_done);
+            k0.tap += tap_done + row_done * (s.ks - taps_per_row);
+            k0.off += go * 8 + row_done * row_jump;
+            k0.woff += go * 32 + row_done * w_row_jump;
+            k0.unit += go;
+        } else if constexpr (EVEN) {
             fetched += 1;
             // k0.unit counts chunks here; stop on the last one
-            advance1(k0, a.units_per_tap >> 1, 8, k0.unit + 1 < a.n_chunks ? 1 : 0);
+            advance1(k0, a.units_per_tap >> 1, 8, k0.unit + 1 < n_chunks ? 1 : 0);
         } else {
             advance1(k0, a.units_per_tap, 4, 1); advance1(k0, a.units_per_tap, 4, 1);
             advance1(k1, a.units_per_tap, 4, 1); advance1(k1, a.units_per_tap, 4, 1);
         }
     };
     if constexpr (EVEN) {   // fold the lane's K-half into its base offsets
-        wrow_bytes += 16 * hsel;
 #pragma unroll
-        for (int i = 0; i < NL - 1; ++i) rbase[i] += 4 * hsel;
+        for (int i = 0; i < NWL; ++i) wrow_bytes[i] += 16 * hsel;
+#pragma unroll
+        for (int i = 0; i < NXL; ++i) rbase[i] += 4 * hsel;
     }
 
     // ---- global -> LDS loads.
@@ -380,10 +473,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     const v4i wres = make_rsrc(w, a.w_bytes);
     const uint32_t stage_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) char*)stage;
     // LDS byte addresses, within a stage, of the blocks this wave fills (`buf` below is a stage's byte offset)
-    const uint32_t w_lds = stage_lds + (uint32_t)wave * 1024u;
-    uint32_t x_lds[NL - 1];
+    uint32_t w_lds[NWL];
 #pragma unroll
-    for (int i = 0; i < NL - 1; ++i) x_lds[i] = stage_lds + (uint32_t)(4 + bblk[i]) * 1024u;
+    for (int i = 0; i < NWL; ++i) w_lds[i] = stage_lds + (uint32_t)(wave + NW * i) * 1024u;
+    uint32_t x_lds[NXL];
+#pragma unroll
+    for (int i = 0; i < NXL; ++i) x_lds[i] = stage_lds + (uint32_t)(4 + bblk[i]) * 1024u;
     auto dma16 = [&](const v4i& rsrc, uint32_t lds_byte, uint32_t offset, uint32_t mask) {
         uint32_t tmp;
         // wave-uniform by construction; the compiler may still park it in a vector register when
@@ -398,42 +493,43 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         if constexpr (EVEN) {
             // weights of a chunk past the end must read as zero: the readers
             // count the set bits of every weight word that passes through
-            f_real = -(fetched < a.n_chunks ? 1 : 0);
+            f_real = -(fetched < n_chunks ? 1 : 0);
             f_tap = k0.tap;
             f_off = k0.off;
-            f_woff = wrow_bytes + k0.unit * 32;
+            f_woff = POS ? k0.woff : k0.unit * 32;
         } else {
             const int unit = hsel ? k1.unit : k0.unit;
             f_real = unit < a.n_units ? -1 : 0;
             f_tap = hsel ? k1.tap : k0.tap;
             f_off = hsel ? k1.off : k0.off;
-            f_woff = wrow_bytes + unit * 16;
+            f_woff = unit * 16;
         }
     };
-    auto fetch_piece = [&](int buf, int i) {  // i = 0: weight block; i = 1..NL-1: input blocks
-        if (i == 0) {
-            dma16(wres, w_lds + (uint32_t)buf, (uint32_t)f_woff, (uint32_t)f_real);
+    // f_woff: byte offset along K of the chunk within a weight row
+    auto fetch_piece = [&](int buf, int i) {  // i < NWL: weight blocks; then the input blocks
+        if (i < NWL) {
+            dma16(wres, w_lds[i] + (uint32_t)buf, (uint32_t)(wrow_bytes[i] + f_woff), (uint32_t)f_real);
         } else {
             // validity bit of the tap, sign-extended to a mask
-            int m = __builtin_amdgcn_sbfe((int)vmask[i - 1], (uint32_t)f_tap & 31u, 1u);
+            int m = __builtin_amdgcn_sbfe((int)vmask[i - NWL], (uint32_t)f_tap & 31u, 1u);
             m &= f_real;     // chunks past the end fetch nothing (an out-of-range offset returns 0 at once)
-            dma16(xres, x_lds[i - 1] + (uint32_t)buf,
-                  (uint32_t)(rbase[i - 1] + f_off) << 2, (uint32_t)m);
+            dma16(xres, x_lds[i - NWL] + (uint32_t)buf,
+                  (uint32_t)(rbase[i - NWL] + f_off) << 2, (uint32_t)m);
         }
     };
 
     // The same work cut into statements for the chunk loop (see loader_slots()).
     constexpr int ADV_STMTS = EVEN ? 5 : 4;
-    constexpr int N_PIECE = 1 + 3 * (NL - 1);
+    constexpr int N_PIECE = NWL + 3 * NXL;
     int p_mask = 0;
     uint32_t p_off = 0;
     int adv_go = 0, adv_td = 0, adv_rd = 0;
     auto piece_stmt = [&](auto jc, int buf) {
         constexpr int j = decltype(jc)::value;
-        if constexpr (j == 0) {
-            fetch_piece(buf, 0);
+        if constexpr (j < NWL) {
+            fetch_piece(buf, j);
         } else {
-            constexpr int pi = (j - 1) / 3, part = (j - 1) % 3;      // input block pi of this wave
+            constexpr int pi = (j - NWL) / 3, part = (j - NWL) % 3;      // input block pi of this wave
             if constexpr (part == 0) {
                 p_mask = __builtin_amdgcn_sbfe((int)vmask[pi], (uint32_t)f_tap & 31u, 1u) & f_real;
             } else if constexpr (part == 1) {
@@ -447,20 +543,23 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         constexpr int part = decltype(kc)::value;
         if constexpr (EVEN) {            // advance() in five parts
             if constexpr (part == 0) {
-                adv_go = k0.unit + 1 < a.n_chunks ? 1 : 0;   // k0.unit counts chunks here; stop on the last one
+                adv_go = k0.unit + 1 < n_chunks ? 1 : 0;   // k0.unit counts chunks here; stop on the last one
             } else if constexpr (part == 1) {
                 const int ut1 = k0.ut + adv_go;
                 adv_td = ut1 == (a.units_per_tap >> 1) ? 1 : 0;
                 k0.ut = adv_td ? 0 : ut1;
             } else if constexpr (part == 2) {
-                k0.tap += adv_td;
                 const int v1 = k0.v + adv_td;
-                adv_rd = v1 == s.ks ? 1 : 0;
+                adv_rd = v1 == taps_per_row ? 1 : 0;
                 k0.v = adv_rd ? 0 : v1;
+                k0.tap += adv_td;
+                if constexpr (POS) k0.tap += adv_rd ? s.ks - taps_per_row : 0;
             } else if constexpr (part == 3) {
-                k0.off += (adv_go ? 8 : 0) + (adv_td ? a.tap_step : 0);
+                k0.off += (adv_go ? 8 : 0) + (POS ? 0 : (adv_td ? a.tap_step : 0));
+                if constexpr (POS) k0.woff += adv_go ? 32 : 0;
             } else {
                 k0.off += adv_rd ? row_jump : 0;
+                if constexpr (POS) k0.woff += adv_rd ? w_row_jump : 0;
                 k0.unit += adv_go;
                 fetched += 1;
             }
@@ -472,7 +571,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         constexpr int part = decltype(kc)::value;
         if constexpr (part == 0) {
             if constexpr (EVEN) {
-                f_real = -(fetched < a.n_chunks ? 1 : 0);
+                f_real = -(fetched < n_chunks ? 1 : 0);
                 f_tap = k0.tap;
                 f_off = k0.off;
             } else {
@@ -482,8 +581,9 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 f_off = hsel ? k1.off : k0.off;
             }
         } else {
-            if constexpr (EVEN) f_woff = wrow_bytes + k0.unit * 32;
-            else f_woff = wrow_bytes + (hsel ? k1.unit : k0.unit) * 16;
+            if constexpr (POS) f_woff = k0.woff;
+            else if constexpr (EVEN) f_woff = k0.unit * 32;
+            else f_woff = (hsel ? k1.unit : k0.unit) * 16;
         }
     };
 
@@ -506,12 +606,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         return ch < s.c_out ? ch : s.c_out - 1;
     };
     if constexpr (BRANCH) {
-        for (int i = t; i < a.taps * WG_CH; i += 256) {
+        for (int i = t; i < a.taps * WG_CH; i += NT) {
             const int tp = i / WG_CH, cl = i - tp * WG_CH;
             const int ch = o0 + cl < s.c_out ? o0 + cl : s.c_out - 1;
             scale_lds[tp][cl] = bp.scale[(size_t)tp * s.c_out + ch];
         }
-        for (int i = t; i < PAD_LDS_WORDS + 8; i += 256)
+        for (int i = t; i < PAD_LDS_WORDS + 8; i += NT)
             pad_lds[i] = (PADMODE == 1 && i < a.taps * s.cw) ? bp.pad_words[i] : 0u;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
@@ -626,9 +726,12 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     // are issued a whole chunk after that.
     constexpr int NF = CB + PB;       // words per lane and K-step: weights first, then inputs
     constexpr int NS = CB * PB;       // MFMA slots per K-step
-    constexpr auto LSLOTS = loader_slots<NS, NL>();
+    constexpr auto LSLOTS = loader_slots<NS, NWL, NXL>();
     static_assert(LSLOTS.v[N_PIECE - 1] <= 2 * NS - 2, "the loads must be issued before the wait of K-step 1");
     static_assert(light_slot<NS>(ADV_STMTS + 1) < NS && light_slot<NS>(2 + 2 * CB) < NS, "bookkeeping slots must exist");
+    static_assert(light_slot<NS>(1) < light_slot<NS>(2) && light_slot<NS>(2) < light_slot<NS>(3) &&
+                  light_slot<NS>(3) < light_slot<NS>(4) && light_slot<NS>(4) < light_slot<NS>(5) &&
+                  light_slot<NS>(5) < light_slot<NS>(6), "bookkeeping statements must keep their order");
     static_assert(CB == 2, "slot program assumes two channel blocks");
     // the fragments of the next chunk's blocks 0 and 1 are expanded behind pixel blocks PB-2 and PB-1 of
     // K-step 3, from words re-read behind blocks 0 and 1 of the same K-step: that needs a few slots between
@@ -766,6 +869,71 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         advance();
     }
     fetch_begin();                                       // chunk 2: the loop expects its position ready
+    // Position-major tiles: what the taps that are not walked add to every pixel of the tile, per
+    // channel.  Such a tap is outside the image for all of them, i.e. -1 in every channel: its sum is
+    // c_in - 2 * popcount(the tap's weight words).  skip_lds[channel] collects the popcounts.  The
+    // workgroup's threads run over (channel, 16-byte unit) of a tap, neighbouring lanes on
+    // neighbouring units; a thread's place in that order does not depend on the tap, so its offsets
+    // are computed once and the taps only add a wave-uniform term.  The loads of three taps (an edge
+    // misses one filter row or column) are in flight together: one trip to memory, which at the
+    // start of a kernel is some 4000 cycles.  They are issued behind the first chunks' loads so that
+    // the two waits overlap: loads complete in order, so the wait for these also covers the
+    // loader's, whose own wait (counted by hand) then finds nothing left.
+    if constexpr (POS) {
+        const int n_skip = s.ks * s.ks - pt.nu * pt.nv;
+        if (n_skip > 0) {
+            __syncthreads();                                        // skip_lds is cleared
+            uint64_t list = 0;                                      // the skipped taps, four bits each
+            {
+                int cnt = 0;
+                for (int u = 0; u < s.ks; ++u)
+                    for (int v = 0; v < s.ks; ++v) {
+                        const bool walked = u >= pt.u_lo && u < pt.u_lo + pt.nu && v >= pt.v_lo && v < pt.v_lo + pt.nv;
+                        if (!walked) { list |= (uint64_t)(u * s.ks + v) << (4 * cnt); cnt += 1; }
+                    }
+            }
+            const int per_tap = s.cw >> 2;                          // 16-byte units of a tap
+            const int per_wg = WG_CH * per_tap;                     // of a tap over the tile's channels
+            const int rounds = (per_wg + NT - 1) / NT;              // per thread and tap
+            const auto wbuf = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w), 0, a.w_bytes, 0x00020000);
+            constexpr int RMAX = 1024 / NT, TU = 3;
+            for (int r0 = 0; r0 < rounds; r0 += RMAX) {
+                int off[RMAX], cl[RMAX], pop[RMAX];
+#pragma unroll
+                for (int k = 0; k < RMAX; ++k) {
+                    const int e = t + (r0 + k) * NT;
+                    const bool ok = r0 + k < rounds && e < per_wg;
+                    cl[k] = a.pos.div_per_tap(ok ? e : 0);
+                    const int q = (ok ? e : 0) - cl[k] * per_tap;
+                    const int ch = o0 + cl[k] < s.c_out ? o0 + cl[k] : s.c_out - 1;
+                    off[k] = ok ? (ch * (s.ks * s.ks) * per_tap + q) * 16 : -1;   // negative: reads nothing
+                    pop[k] = 0;
+                }
+                for (int g0 = 0; g0 < n_skip; g0 += TU) {
+                    v4i d[TU][RMAX];
+#pragma unroll
+                    for (int g = 0; g < TU; ++g) {
+                        const int gi = g0 + g < n_skip ? g0 + g : n_skip - 1;
+                        const int tap_off = (int)((list >> (4 * gi)) & 15u) * per_tap * 16;
+                        const bool real = g0 + g < n_skip;
+#pragma unroll
+                        for (int k = 0; k < RMAX; ++k)   // offsets past the tensor read as zero: no bits
+                            d[g][k] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(
+                                wbuf, (real && off[k] >= 0) ? off[k] + tap_off : -16, 0, 0));
+                    }
+#pragma unroll
+                    for (int g = 0; g < TU; ++g)
+#pragma unroll
+                        for (int k = 0; k < RMAX; ++k)
+                            pop[k] += __builtin_popcount((uint32_t)d[g][k][0]) + __builtin_popcount((uint32_t)d[g][k][1]) +
+                                      __builtin_popcount((uint32_t)d[g][k][2]) + __builtin_popcount((uint32_t)d[g][k][3]);
+                }
+#pragma unroll
+                for (int k = 0; k < RMAX; ++k) atomicAdd(&skip_lds[cl[k]], pop[k]);
+            }
+        }
+    }
+
     // The accumulators are cleared here, while the first chunks are on their way from memory.  Left to
     // itself the compiler re-creates the zeros right in front of the loop, after the wait; the empty
     // statements below take every accumulator as input and output, so the zeros must exist here.
@@ -779,7 +947,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             // (branch mode holds a second accumulator set; pinning this one to a register class there
             // leaves the allocator no room and it spills, so the compiler places those zeros itself)
             if constexpr (BRANCH) continue;
-            else if constexpr (PB >= 7) asm volatile("" : "+a"(acc[cb][pb]));     // the wide tile keeps them in acc registers
+            else if constexpr (PB >= 6) asm volatile("" : "+a"(acc[cb][pb]));     // the wide tiles keep them in acc registers
             else asm volatile("" : "+v"(acc[cb][pb]));
         }
     __builtin_amdgcn_sched_barrier(0);
@@ -809,7 +977,7 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
         int b0 = 0, b1 = STAGE_BYTES, b2 = 2 * STAGE_BYTES;   // byte offsets of the three stages
         int tap = 0, chunk_in_tap = 0, par = 0;
         const int c_in = 256 * a.chunks_per_tap;
-        for (int chunk = 0; chunk < a.n_chunks; ++chunk) {
+        for (int chunk = 0; chunk < n_chunks; ++chunk) {
             if constexpr (PADMODE == 1)   // pad words of the chunk whose weights this body reads ahead
                 padq = *reinterpret_cast<const uint4*>(pad_lds + 8 * (chunk + 1) + 4 * hsel);
             chunk_body(b1, b2);
@@ -884,7 +1052,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
     if constexpr (!BRANCH) {
         // The lane that holds a channel's count turns it into the value to subtract and leaves it in
         // LDS as a float; every lane then fetches its 2 x 16 channels with eight 16-byte reads.
-        const int base = a.z - 192 * a.n_chunks;
+        // (position-major tiles: Z counts the walked taps only)
+        const int base = (POS ? pt.nu * pt.nv * a.pos.z_per_tap : a.z) - 192 * n_chunks;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             // lanes l and l^32 read the two K-halves of the same weight row
@@ -893,6 +1062,8 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
                 const int cl = 64 * wc + 32 * cb + row_to_channel(j);
                 int v = base + 2 * both;
                 if constexpr (FUSED) v += thr_lds[cl];
+                // y = walked taps + skipped taps
+                if constexpr (POS) v -= (s.ks * s.ks - pt.nu * pt.nv) * a.pos.c_in - 2 * skip_lds[cl];
                 sub_lds[cl] = FUSED ? (float)v - 0.5f : (float)v;   // exact: multiples of 0.5 below 2^23
             }
         }
@@ -934,9 +1105,15 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             const uint32_t got = (uint32_t)__shfl_xor((int)give, 32, 64);
             const uint32_t mine = hsel ? part[1] : part[0];
             uint32_t word = hsel ? (got | (mine << 16)) : (mine | (got << 16));
-            const int m = m0 + 32 * (PB * wp + pb) + j;
+            int m = m0 + 32 * (PB * wp + pb) + j;
+            bool row_ok = m < s.m;
+            if constexpr (POS) {
+                int n0, oh, ow;
+                row_ok = block_pos(PB * wp + pb, n0, oh, ow);
+                m = ((n0 + j) * s.ho + oh) * s.wo + ow;
+            }
             const int wi = (o0 >> 5) + 2 * wc + hsel;  // packed word index along channels
-            if (m < s.m && wi < s.cwo) {
+            if (row_ok && wi < s.cwo) {
                 const int valid = s.c_out - 32 * wi;   // real channels in this word
                 if (valid < 32) word &= (1u << valid) - 1u;
                 yp[(size_t)m * s.cwo + wi] = word;
@@ -1157,6 +1334,84 @@ __global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void 
             run(std::false_type{});
         }
     }
+}
+
+// Workgroup -> tile.  Consecutive workgroup ids go to different XCDs; give
+// each XCD a contiguous range of tiles (channel tile fastest) so that the
+// workgroups sharing an input tile share an L2.
+__device__ __forceinline__ void decode_tile(const MfmaArgs& a, int& ptile, int& ctile)
+{
+    int tile = blockIdx.x;
+    const int n_tiles = a.n_ptiles * a.n_ctiles;
+    const int per_xcd = n_tiles >> 3;
+    if (tile < per_xcd * 8) tile = (tile & 7) * per_xcd + (tile >> 3);
+    ptile = a.div_ct(tile);
+    ctile = tile - ptile * a.n_ctiles;
+}
+
+template <int PB, int OUT, bool EVEN, bool PLAIN = false>
+__global__ __launch_bounds__(256, ((PB <= 4 && OUT < OUT_BRANCH) ? 2 : 1)) void conv_mfma_fp4_kernel(
+    MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
+    const int32_t* __restrict__ thr, void* __restrict__ out, ModuleEp ep, BranchEp bp)
+{
+    __shared__ uint4 stage[stage_units(PB)];
+    int ptile, ctile;
+    decode_tile(a, ptile, ctile);
+    conv_mfma_fp4_tile<PB, OUT, EVEN, PLAIN, false>(a, x, w, thr, out, ep, bp, stage, ptile, ctile, PosTile{});
+}
+
+// Position-major tiling of the fused 3x3 convolution, for small feature maps in
+// large batches (7 x 7: 40 of 49 windows reach outside the image and 18 % of all
+// taps are padding).
+//
+// The GEMM rows of a tile need not be consecutive pixels: any set of output
+// pixels will do, as long as each result is stored where it belongs.  Here a
+// pixel block is ONE output position in 32 consecutive images, and the blocks
+// are ordered by position class: the interior rectangle (every tap inside the
+// image), the top rows, the bottom rows, the left and the right columns.  All
+// windows of a class miss the image in the same filter rows or columns, so a
+// tile of one class walks only the taps of that class's rectangle (6 of 9 for
+// an edge) and accounts for the others in closed form: a tap outside the image
+// reads -1 in every channel, so its dot product with the weights is
+// c_in - 2 * popcount(weight words of that tap), one number per output channel,
+// counted when the workgroup starts.  A corner shares the tile of its edge row:
+// the tap columns it misses on top of the row's are read as zero words, as in
+// the pixel-major kernel.
+//
+// The classes also level the work: interior tiles (9 taps) take PBI pixel
+// blocks per wave, edge tiles (6 taps) PBE > PBI, chosen by the launcher so
+// that every tile of the launch gets its own CU and the longest tile is as
+// short as possible (7 x 7 map, 256 images, 1024 channels: 160 tiles of 10
+// blocks x 9 taps and 96 tiles of 16 blocks x 6 taps on 256 CUs, against 224
+// tiles of 14 blocks x 9 taps pixel-major).  One kernel holds both tile bodies
+// and a workgroup picks its own.
+template <int PBI, int PBE, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void conv_mfma_fp4_pos_kernel(
+    MfmaArgs a, const uint32_t* __restrict__ x, const uint32_t* __restrict__ w,
+    const int32_t* __restrict__ thr, uint32_t* __restrict__ out)
+{
+    __shared__ uint4 stage[stage_units(PBI > PBE ? PBI : PBE, NW)];
+    int ptile, ctile;
+    decode_tile(a, ptile, ctile);
+    int k = 0;
+#pragma unroll
+    for (int i = 1; i < 5; ++i) k += ptile >= a.pos.seg[i].tile0 ? 1 : 0;
+    PosSeg sg = a.pos.seg[0];
+#pragma unroll
+    for (int i = 1; i < 5; ++i)
+        if (k == i) sg = a.pos.seg[i];
+    PosTile pt;
+    pt.block0 = (ptile - sg.tile0) * (NW / 2) * sg.pb;
+    pt.blocks = sg.blocks;
+    pt.oh0 = sg.oh0; pt.ow0 = sg.ow0; pt.width = sg.width;
+    pt.u_lo = sg.u_lo; pt.nu = sg.nu; pt.v_lo = sg.v_lo; pt.nv = sg.nv;
+    pt.div_width = sg.div_width;
+    const ModuleEp ep{};
+    const BranchEp bp{};
+    if (PBI != PBE && sg.pb == PBI)
+        conv_mfma_fp4_tile<PBI, OUT_BITS, true, false, true, NW>(a, x, w, thr, out, ep, bp, stage, ptile, ctile, pt);
+    else
+        conv_mfma_fp4_tile<PBE, OUT_BITS, true, false, true, NW>(a, x, w, thr, out, ep, bp, stage, ptile, ctile, pt);
 }
 
 template <int PB, int OUT>

@@ -19,8 +19,9 @@ from gpu_helpers import COVER_ALL, Guarded, gpu_device, i32, oracle_pack_nchw, r
 pytestmark = pytest.mark.gpu
 
 VARIANTS = [B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_VALU, B.BCNN_VARIANT_MFMA_FP4_T4, B.BCNN_VARIANT_MFMA_FP4_T7,
-            B.BCNN_VARIANT_MFMA_I8]
-VARIANT_IDS = ["auto", "valu", "mfma_fp4_t4", "mfma_fp4_t7", "mfma_i8"]
+            B.BCNN_VARIANT_MFMA_I8, B.BCNN_VARIANT_MFMA_FP4_P6, B.BCNN_VARIANT_MFMA_FP4_P7, B.BCNN_VARIANT_MFMA_FP4_P5,
+            B.BCNN_VARIANT_MFMA_FP4_P68]
+VARIANT_IDS = ["auto", "valu", "mfma_fp4_t4", "mfma_fp4_t7", "mfma_i8", "mfma_fp4_p6", "mfma_fp4_p7", "mfma_fp4_p5", "mfma_fp4_p68"]
 
 
 @pytest.fixture(scope="module")
@@ -40,8 +41,9 @@ def rand_pm1(rng, shape, p=0.5):
     return np.where(rng.random(shape) < p, 1, -1).astype(np.int8)
 
 
-def gpu_conv(dev, x, w, stride, pad, thr=None, variant=B.BCNN_VARIANT_AUTO, entry="variant"):
-    """x, w logical +-1 tensors (packed on the host by the oracle's packer)."""
+def gpu_conv(dev, x, w, stride, pad, thr=None, variant=B.BCNN_VARIANT_AUTO, entry="variant", must_cover=False):
+    """x, w logical +-1 tensors (packed on the host by the oracle's packer).  must_cover: a refusal
+    of the shape by the variant is a failure, not a skip."""
     n, c, h, wd = x.shape
     o, _, k, _ = w.shape
     desc = B.conv_desc(n, c, h, wd, o, k, stride, pad)
@@ -63,7 +65,7 @@ def gpu_conv(dev, x, w, stride, pad, thr=None, variant=B.BCNN_VARIANT_AUTO, entr
         rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, t, out.ptr, variant)
     else:
         rc = B.bcnn_conv2d_binary_sign_pack(desc, xp, wp, t, out.ptr)
-    run_variant(rc, "conv_sign_pack", variant if entry == "variant" else B.BCNN_VARIANT_AUTO)
+    run_variant(rc, "conv_sign_pack", variant if entry == "variant" and not must_cover else B.BCNN_VARIANT_AUTO)
     return out.get(np.uint32).reshape(n, ho * wo, cwo)
 
 
@@ -207,6 +209,54 @@ def test_fused_epilogue_matches_oracle(dev, shape, tight, variant):
     out = Guarded(rows * ((o + 31) // 32), dev)
     B.check(B.bcnn_threshold_sign_pack(up(y_gpu, dev), up(thr, dev), rows, o, out.ptr), "thr")
     np.testing.assert_array_equal(out.get().reshape(want.shape), want)
+
+
+# Position-major tiles (a block of 32 GEMM rows = one output position in 32 images; taps outside
+# the image are not walked but accounted for per channel).  Shapes the scheme covers: a refusal is a
+# failure here.  They span: no interior (2 x 2), no edges (pad 0), edges on two sides only (stride 2),
+# ragged last tiles of every class, several groups of 32 images, a ragged channel tile, channel counts
+# that leave tail bits in the last word of every tap, thresholds out of reach.
+POS_SHAPES = [
+    (32, 256, 7, 7, 128, 3, 1, 1), (64, 256, 5, 6, 130, 3, 1, 1), (32, 512, 9, 8, 64, 3, 2, 1),
+    (96, 256, 3, 3, 96, 3, 1, 1), (32, 256, 4, 5, 32, 3, 1, 0), (32, 256, 2, 2, 40, 3, 1, 1),
+    (32, 250, 6, 6, 40, 3, 1, 1), (64, 225, 8, 8, 257, 3, 2, 1), (32, 256, 15, 13, 64, 3, 1, 1),
+    (128, 256, 2, 3, 33, 3, 1, 1), (32, 768, 3, 4, 256, 3, 1, 1),
+]
+
+
+POS_VARIANTS = [B.BCNN_VARIANT_MFMA_FP4_P6, B.BCNN_VARIANT_MFMA_FP4_P7, B.BCNN_VARIANT_MFMA_FP4_P5, B.BCNN_VARIANT_MFMA_FP4_P68]
+
+
+@pytest.mark.parametrize("variant", POS_VARIANTS, ids=["p6", "p7", "p5", "p68"])
+@pytest.mark.parametrize("shape", POS_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_position_major_tiles_match_oracle(dev, shape, variant):
+    n, c, h, wd, o, k, s, p = shape
+    rng = np.random.default_rng(sum(shape) * 13 + variant)
+    x = rand_pm1(rng, (n, c, h, wd), 0.35)
+    w = rand_pm1(rng, (o, c, k, k), 0.45)
+    kk = c * k * k
+    bound = int(2 * math.sqrt(kk))
+    thr = rng.integers(-bound, bound + 1, size=o).astype(np.int32)
+    thr[0] = np.iinfo(np.int32).min
+    thr[-1] = np.iinfo(np.int32).max
+    y, want = oracle_fused(x, w, s, p, thr)
+    assert (np.abs(y - thr) <= 1).any()
+    got = gpu_conv(dev, x, w, s, p, thr=thr, variant=variant, must_cover=True)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_position_major_refusals(dev):
+    """What the scheme does not cover is refused, not computed some other way."""
+    dummy = torch.zeros(1 << 16, dtype=torch.int32, device=dev)
+    for shape in [(31, 256, 7, 7, 64, 3, 1, 1), (32, 128, 7, 7, 64, 3, 1, 1), (32, 256, 7, 7, 64, 1, 1, 0),
+                  (32, 256, 1, 1, 64, 3, 1, 1)]:
+        n, c, h, wd, o, k, s, p = shape
+        desc = B.conv_desc(n, c, h, wd, o, k, s, p)
+        for variant in POS_VARIANTS:
+            assert B.bcnn_conv2d_binary_variant(desc, dummy, dummy, dummy, dummy.data_ptr() + 4096, variant) == B.BCNN_ERR_UNSUPPORTED
+    desc = B.conv_desc(32, 256, 7, 7, 64, 3, 1, 1)
+    assert B.bcnn_conv2d_binary_variant(desc, dummy, dummy, None, dummy.data_ptr() + 4096,
+                                        B.BCNN_VARIANT_MFMA_FP4_P6) == B.BCNN_ERR_UNSUPPORTED   # int32 sums
 
 
 def test_threshold_extremes(dev):
