@@ -34,7 +34,11 @@
 // Tiling.  MFMA rows (M of the instruction) are output channels, columns are
 // output pixels.  A workgroup of 4 waves (2 x 2) owns 128 channels x 64*PB
 // pixels; a wave owns 2 x PB blocks of 32 x 32 (PB = 4 or 7; 7 divides the
-// pixel counts of 7/14/28/56-wide feature maps, see the launcher).
+// pixel counts of 7/14/28/56-wide feature maps, see the launcher).  The tile
+// body is a device function (conv_mfma_fp4_tile) shared by two kernels: the
+// pixel-major one (GEMM rows = consecutive pixels) and the position-major one
+// for small maps in large batches (conv_mfma_fp4_pos_kernel below), which also
+// runs it with PB = 5, 6, 8 and with workgroups of 2 waves (2 x 1).
 // K is walked in chunks of 8 packed words (256 bits = 4 MFMA K-steps) over the
 // flattened (tap, channel-word) axis; each chunk of both operands is staged
 // once per workgroup in LDS (double buffered) with full-width global loads,
