@@ -66,7 +66,8 @@ typedef enum {
     BCNN_VARIANT_MFMA_FP4_T7 = 5, /* the same with 2 x 7 blocks forced (fused output only) */
     /* position-major tiles forced: a block of 32 rows is one output position in 32 consecutive
      * images, tiles are sorted by which filter taps fall outside the image and do not walk those.
-     * Fused output, 3 x 3 filter, pad <= 1, c_in a multiple of 256 and n a multiple of 32 only.
+     * Fused output, 3 x 3 filter, c_in a multiple of 256 and n a multiple of 32 only, and no
+     * output row or column whose window misses the image on both sides.
      * P6: interior tiles of 2 x 6 blocks per wave, edge tiles of 2 x 7; P7: 2 x 7 throughout;
      * P5: workgroups of two waves (one block column), interior tiles of 2 x 5 blocks, edge 2 x 8;
      * P68: two waves, interior 2 x 6, edge 2 x 8 */

@@ -28,84 +28,16 @@ static double tile_cost(const ConvShape& s, int pb)
     return (double)rounds * pb;
 }
 
-// ---- position-major tiling (kernel: conv_mfma_fp4_pos_kernel)
-// Valid taps along one axis for output index o: [lo, hi] within 0..2.
-static void axis_taps(int o, int stride, int pad, int extent, int& lo, int& hi)
-{
-    const int p = o * stride - pad;
-    lo = p < 0 ? -p : 0;
-    hi = p + 2 >= extent ? extent - 1 - p : 2;
-}
-// Splits 0..count-1 into leading indices that miss taps at the low end, a middle with all three taps
-// and trailing indices that miss taps at the high end; false if that is not the structure.
-static bool axis_classes(int count, int stride, int pad, int extent, int& first_full, int& end_full,
-                         int& lead_lo, int& trail_hi)
-{
-    first_full = 0;
-    lead_lo = 0;
-    trail_hi = 2;
-    int lo, hi;
-    while (first_full < count) {
-        axis_taps(first_full, stride, pad, extent, lo, hi);
-        if (lo == 0) break;
-        if (hi < 2 || lo > 2) return false;
-        lead_lo = first_full == 0 ? lo : (lo < lead_lo ? lo : lead_lo);
-        ++first_full;
-    }
-    end_full = first_full;
-    while (end_full < count) {
-        axis_taps(end_full, stride, pad, extent, lo, hi);
-        if (lo != 0) return false;
-        if (hi < 2) break;
-        ++end_full;
-    }
-    for (int o = end_full; o < count; ++o) {
-        axis_taps(o, stride, pad, extent, lo, hi);
-        if (lo != 0 || hi < 0) return false;
-        trail_hi = o == end_full ? hi : (hi > trail_hi ? hi : trail_hi);
-    }
-    if (end_full == count) trail_hi = 2;
-    return true;
-}
-
+// ---- position-major tiling (kernel: conv_mfma_fp4_pos_kernel; plan: pos_plan.h)
 // Fills a.pos and a.n_ptiles for workgroups of nw waves, interior tiles of pbi blocks per wave and
 // edge tiles of pbe.  Returns the cost in the units of tile_cost() times taps (rounds of workgroups
 // x the longest tile), or a negative number if the shape does not fit the scheme.
 static double plan_pos(const ConvShape& s, int pbi, int pbe, int nw, MfmaArgs& a)
 {
-    if (s.ks != 3 || s.cw % 8 != 0 || s.n % 32 != 0 || s.n <= 0 || s.ho > 1023 || s.wo > 1023) return -1.0;
-    int r0, r1, c0, c1, top_lo, bottom_hi, left_lo, right_hi;
-    if (!axis_classes(s.ho, s.stride, s.pad, s.h, r0, r1, top_lo, bottom_hi)) return -1.0;
-    if (!axis_classes(s.wo, s.stride, s.pad, s.w, c0, c1, left_lo, right_hi)) return -1.0;
-    PosArgs& p = a.pos;
-    p.groups = s.n / 32;
-    p.div_groups = DivBy::make(p.groups);
-    p.c_in = s.k / (s.ks * s.ks);
-    p.z_per_tap = 32 * s.cw - p.c_in;
-    p.div_per_tap = DivBy::make(s.cw / 4);
-    struct Rect { int oh0, rows, ow0, cols, u_lo, nu, v_lo, nv; };
-    const Rect rects[5] = {
-        {r0, r1 - r0, c0, c1 - c0, 0, 3, 0, 3},                         // interior
-        {0, r0, 0, s.wo, top_lo, 3 - top_lo, 0, 3},                     // top rows, corners included
-        {r1, s.ho - r1, 0, s.wo, 0, bottom_hi + 1, 0, 3},               // bottom rows, corners included
-        {r0, r1 - r0, 0, c0, 0, 3, left_lo, 3 - left_lo},               // left columns
-        {r0, r1 - r0, c1, s.wo - c1, 0, 3, 0, right_hi + 1},            // right columns
-    };
-    int tiles = 0, longest = 0;
-    for (int i = 0; i < 5; ++i) {
-        const Rect& r = rects[i];
-        PosSeg& g = p.seg[i];
-        g.tile0 = tiles;
-        g.blocks = r.rows * r.cols * p.groups;
-        g.oh0 = r.oh0; g.ow0 = r.ow0; g.width = r.cols > 0 ? r.cols : 1;
-        g.u_lo = r.u_lo; g.nu = r.nu; g.v_lo = r.v_lo; g.nv = r.nv;
-        g.pb = i == 0 ? pbi : pbe;
-        g.div_width = DivBy::make(g.width);
-        const int per_tile = (nw / 2) * g.pb;
-        const int n = (g.blocks + per_tile - 1) / per_tile;
-        tiles += n;
-        if (n > 0 && r.nu * r.nv * g.pb > longest) longest = r.nu * r.nv * g.pb;
-    }
+    const PosShape ps = {s.n, s.h, s.w, s.cw, s.ks > 0 ? s.k / (s.ks * s.ks) : 0, s.ks, s.stride, s.pad, s.ho, s.wo};
+    int longest = 0;
+    const int tiles = pos_plan(ps, pbi, pbe, nw, a.pos, &longest);
+    if (tiles < 0) return -1.0;
     a.n_ptiles = tiles;
     const int64_t wgs = (int64_t)tiles * a.n_ctiles;
     const int64_t resident = 256 * (4 / nw);     // one wave per SIMD

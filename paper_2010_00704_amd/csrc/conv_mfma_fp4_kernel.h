@@ -57,32 +57,13 @@
 #pragma once
 #include "bcnn_common.h"
 #include "div_by.h"
+#include "pos_plan.h"
 
 #include <type_traits>
 
 #include <utility>
 
 namespace bcnn {
-
-// Position-major tiling (see the section in front of conv_mfma_fp4_pos_kernel):
-// a segment is a rectangle of output positions whose windows miss the image in
-// the same filter rows / columns.
-struct PosSeg {
-    int32_t tile0;      // first tile (per channel tile) of the segment; tiles of pb blocks per wave along the pixels
-    int32_t blocks;     // pixel blocks of the segment = positions * groups of 32 images
-    int32_t oh0, ow0, width;   // the rectangle's corner and width (positions are numbered row by row)
-    int32_t u_lo, nu, v_lo, nv; // filter rows / columns that some window of the segment has inside the image
-    int32_t pb;         // pixel blocks per wave of the segment's tiles
-    DivBy div_width;
-};
-struct PosArgs {
-    PosSeg seg[5];
-    int32_t groups;     // n / 32
-    DivBy div_groups;
-    int32_t z_per_tap;  // 32 * cw - c_in: channel-tail positions of one tap (zero on both sides)
-    int32_t c_in;
-    DivBy div_per_tap;  // by cw / 4, the 16-byte units of a tap
-};
 
 struct MfmaArgs {
     ConvShape s;
@@ -236,13 +217,6 @@ enum { KIND_F32 = 0, KIND_BITS = 1, KIND_TAIL_F32 = 2, KIND_TAIL_F16 = 3 };
 // the filter taps of the segment's rectangle are walked; see
 // conv_mfma_fp4_pos_kernel.  `stage` is the workgroup's staging area in LDS,
 // stage_units(PB) 16-byte units.
-struct PosTile {
-    int32_t block0;     // first block of the tile within its segment
-    int32_t blocks;     // blocks of the segment
-    int32_t oh0, ow0, width;
-    int32_t u_lo, nu, v_lo, nv;
-    DivBy div_width;
-};
 // NW = waves of the workgroup: 4 (2 along the channels x 2 along the pixels, the
 // tile described above) or 2 (2 x 1: half the pixels, for tiles of finer grain;
 // two such workgroups share a CU).
@@ -340,17 +314,7 @@ __device__ __forceinline__ void conv_mfma_fp4_tile(
     };
     // Position-major tiles: block `bl` of the tile -> first image, output position; false past the
     // segment's end (the last block's numbers are returned then).  Wave-uniform when `bl` is.
-    auto block_pos = [&](int bl, int& n0, int& oh, int& ow) -> bool {
-        const int bidx = pt.block0 + bl;
-        const bool active = bidx < pt.blocks;
-        const int bc = active ? bidx : pt.blocks - 1;
-        const int pi = a.pos.div_groups(bc);
-        n0 = 32 * (bc - pi * a.pos.groups);
-        const int q = pt.div_width(pi);
-        oh = pt.oh0 + q;
-        ow = pt.ow0 + (pi - q * pt.width);
-        return active;
-    };
+    auto block_pos = [&](int bl, int& n0, int& oh, int& ow) -> bool { return pos_block(a.pos, pt, bl, n0, oh, ow); };
     int rbase[NXL];
     uint32_t vmask[NXL];
     int bblk[NXL];
@@ -1397,22 +1361,10 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_mfma_fp4_pos_kernel(
     __shared__ uint4 stage[stage_units(PBI > PBE ? PBI : PBE, NW)];
     int ptile, ctile;
     decode_tile(a, ptile, ctile);
-    int k = 0;
-#pragma unroll
-    for (int i = 1; i < 5; ++i) k += ptile >= a.pos.seg[i].tile0 ? 1 : 0;
-    PosSeg sg = a.pos.seg[0];
-#pragma unroll
-    for (int i = 1; i < 5; ++i)
-        if (k == i) sg = a.pos.seg[i];
-    PosTile pt;
-    pt.block0 = (ptile - sg.tile0) * (NW / 2) * sg.pb;
-    pt.blocks = sg.blocks;
-    pt.oh0 = sg.oh0; pt.ow0 = sg.ow0; pt.width = sg.width;
-    pt.u_lo = sg.u_lo; pt.nu = sg.nu; pt.v_lo = sg.v_lo; pt.nv = sg.nv;
-    pt.div_width = sg.div_width;
+    const PosTile pt = pos_tile(a.pos, ptile, NW / 2);   // segment table -> this workgroup's tile (wave-uniform selects)
     const ModuleEp ep{};
     const BranchEp bp{};
-    if (PBI != PBE && sg.pb == PBI)
+    if (PBI != PBE && pt.pb == PBI)
         conv_mfma_fp4_tile<PBI, OUT_BITS, true, false, true, NW>(a, x, w, thr, out, ep, bp, stage, ptile, ctile, pt);
     else
         conv_mfma_fp4_tile<PBE, OUT_BITS, true, false, true, NW>(a, x, w, thr, out, ep, bp, stage, ptile, ctile, pt);

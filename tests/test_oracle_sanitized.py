@@ -1,7 +1,7 @@
 """The oracle's C files and the host-side checks under AddressSanitizer and
 UndefinedBehaviorSanitizer.  The files are compiled with gcc
 -fsanitize=address,undefined into executables of their own
-(tests/host/oracle_san_driver.c, tests/host/div_by_check.cpp) and run on the
+(tests/host/oracle_san_driver.c, tests/host/div_by_check.cpp, tests/host/pos_plan_check.cpp) and run on the
 hand-worked cases and on seeded shapes with ragged sizes; any report ends the
 run with a non-zero status.  Outputs are compared with the hand-worked values
 and with the ordinary build of the oracle.  CPU only.
@@ -148,6 +148,15 @@ def test_division_constants_under_sanitizers(tmp_path):
     exe = str(tmp_path / "div_by_check_san")
     subprocess.run(["g++", "-std=c++17", "-I", os.path.join(ROOT, "paper_2010_00704_amd", "csrc")] + SAN +
                    [os.path.join(ROOT, "tests", "host", "div_by_check.cpp"), "-o", exe], check=True)
+    out = subprocess.run([exe], env=ENV, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
+    assert out.returncode == 0, out.stdout
+    assert "mismatches: 0" in out.stdout and "runtime error" not in out.stdout
+
+
+def test_position_major_plan_under_sanitizers(tmp_path):
+    exe = str(tmp_path / "pos_plan_check_san")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-I", os.path.join(ROOT, "paper_2010_00704_amd", "csrc")] + SAN +
+                   [os.path.join(ROOT, "tests", "host", "pos_plan_check.cpp"), "-o", exe], check=True)
     out = subprocess.run([exe], env=ENV, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
     assert out.returncode == 0, out.stdout
     assert "mismatches: 0" in out.stdout and "runtime error" not in out.stdout
