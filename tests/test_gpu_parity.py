@@ -221,6 +221,8 @@ POS_SHAPES = [
     (96, 256, 3, 3, 96, 3, 1, 1), (32, 256, 4, 5, 32, 3, 1, 0), (32, 256, 2, 2, 40, 3, 1, 1),
     (32, 250, 6, 6, 40, 3, 1, 1), (64, 225, 8, 8, 257, 3, 2, 1), (32, 256, 15, 13, 64, 3, 1, 1),
     (128, 256, 2, 3, 33, 3, 1, 1), (32, 768, 3, 4, 256, 3, 1, 1),
+    # wide channel counts: the skipped taps' weight words are counted in one pass (1024 channels) or two (2048, 2540)
+    (32, 1024, 4, 5, 130, 3, 1, 1), (32, 2048, 3, 3, 64, 3, 1, 1), (32, 2540, 2, 3, 40, 3, 1, 1),
 ]
 
 
@@ -236,11 +238,15 @@ def test_position_major_tiles_match_oracle(dev, shape, variant):
     w = rand_pm1(rng, (o, c, k, k), 0.45)
     kk = c * k * k
     bound = int(2 * math.sqrt(kk))
-    thr = rng.integers(-bound, bound + 1, size=o).astype(np.int32)
+    # thresholds around the sums' median (the operands are biased, so the sums are not centred on 0)
+    centre = int(np.median(oracle.conv2d_pm1(x, w, s, p)))
+    thr = (centre + rng.integers(-bound, bound + 1, size=o)).astype(np.int32)
     thr[0] = np.iinfo(np.int32).min
     thr[-1] = np.iinfo(np.int32).max
     y, want = oracle_fused(x, w, s, p, thr)
     assert (np.abs(y - thr) <= 1).any()
+    on = oracle.threshold_sign(y, thr) > 0
+    assert on[..., 1:-1].any() and (~on[..., 1:-1]).any()
     got = gpu_conv(dev, x, w, s, p, thr=thr, variant=variant, must_cover=True)
     np.testing.assert_array_equal(got, want)
 
