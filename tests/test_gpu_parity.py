@@ -251,6 +251,31 @@ def test_position_major_tiles_match_oracle(dev, shape, variant):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("variant", POS_VARIANTS, ids=["p6", "p7", "p5", "p68"])
+def test_position_major_closed_form(dev, variant):
+    """All-(+1) inputs and weights on a 3 x 3 map with -1 padding: the sums are C * [[-1, 3, -1], [3, 9, 3],
+    [-1, 3, -1]] (a corner has 4 taps inside and 5 outside, an edge 6 and 3), whatever the oracle says.  With
+    all-(-1) weights the signs flip.  Thresholds just below, at and above each value show every class of
+    position taking the right side, which fixes sign and size of the term that stands for the taps the
+    position-major tiles do not walk."""
+    n, c, o = 32, 256, 64
+    x = up(np.full((n, 9, c // 32), -1, dtype=np.int32), dev)                     # every bit set: +1
+    pattern = np.array([-1, 3, -1, 3, 9, 3, -1, 3, -1]) * c
+    desc = B.conv_desc(n, c, 3, 3, o, 3, 1, 1)
+    for wsign in (1, -1):
+        w = up(np.full((o, 9, c // 32), -1 if wsign > 0 else 0, dtype=np.int32), dev)
+        values = sorted(set((wsign * pattern).tolist()))
+        thr = np.array([v + d for v in values for d in (-1, 0, 1)] * 8, dtype=np.int32)[:o]
+        out = Guarded(n * 9 * (o // 32), dev)
+        B.check(B.bcnn_conv2d_binary_variant(desc, x, w, up(thr, dev), out.ptr, variant), "position-major conv")
+        got = out.get().reshape(n, 9, o // 32)
+        want_bits = (wsign * pattern)[:, None] >= thr[None, :]                    # [position][channel]
+        want = np.zeros((9, o // 32), dtype=np.uint32)
+        for ch in range(o):
+            want[:, ch // 32] |= want_bits[:, ch].astype(np.uint32) << np.uint32(ch % 32)
+        np.testing.assert_array_equal(got, np.broadcast_to(want, (n, 9, o // 32)))
+
+
 def test_position_major_refusals(dev):
     """What the scheme does not cover is refused, not computed some other way."""
     dummy = torch.zeros(1 << 16, dtype=torch.int32, device=dev)
