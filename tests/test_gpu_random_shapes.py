@@ -78,6 +78,37 @@ def test_random_plain_and_fused(dev, seed, mfma_friendly):
     assert ran >= 4
 
 
+@pytest.mark.parametrize("seed", range(16 + EXTRA))
+def test_random_position_major(dev, seed):
+    """Shapes the position-major tilings cover (3 x 3 filter, whole groups of 32 images, c_in a multiple of 256
+    give or take tail bits): every such tiling and the default choice against the oracle."""
+    rng = np.random.default_rng(17000 + seed)
+    n = 32 * int(rng.integers(1, 4))
+    c = int(rng.choice([256, 512, 768, 1024])) - int(rng.choice([0, 0, 5, 31]))
+    h, w = int(rng.integers(2, 13)), int(rng.integers(2, 13))
+    o = int(rng.choice([32, 64, 100, 128, 130, 257]))
+    stride, pad = int(rng.choice([1, 2])), int(rng.integers(0, 2))
+    if (h + 2 * pad - 3) // stride + 1 < 1 or (w + 2 * pad - 3) // stride + 1 < 1:
+        pad = 1
+    x = W.pm1(17100 + seed, (n, c, h, w), float(rng.choice([0.3, 0.5, 0.7])))
+    wt = W.pm1(17200 + seed, (o, c, 3, 3))
+    y = oracle.conv2d_pm1(x, wt, stride, pad)
+    thr = (int(np.median(y)) + W.thresholds(17300 + seed, o, max(1, int(2 * np.sqrt(9 * c))))).astype(np.int32)
+    want_bits = oracle_bits_of_sign(oracle.threshold_sign(y, thr))
+    desc = B.conv_desc(n, c, h, w, o, 3, stride, pad)
+    xp = up(i32(oracle_pack_nchw(x)), dev)
+    wp = up(i32(oracle_pack_nchw(wt)), dev)
+    ran = 0
+    for v in (B.BCNN_VARIANT_AUTO, B.BCNN_VARIANT_MFMA_FP4_P5, B.BCNN_VARIANT_MFMA_FP4_P68, B.BCNN_VARIANT_MFMA_FP4_P6,
+              B.BCNN_VARIANT_MFMA_FP4_P7):
+        bits = Guarded(want_bits.size, dev)
+        rc = B.bcnn_conv2d_binary_variant(desc, xp, wp, up(thr, dev), bits.ptr, v)
+        B.check(rc, "fused")       # (maps of two or more rows and columns: no window misses the image on both sides)
+        assert np.array_equal(bits.get(np.uint32).reshape(want_bits.shape), want_bits), "variant %d bits" % v
+        ran += 1
+    assert ran == 5
+
+
 @pytest.mark.parametrize("seed,mfma_friendly", CASES[:24 + EXTRA])
 @pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
 def test_random_module(dev, seed, mfma_friendly, half):
